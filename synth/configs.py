@@ -1,0 +1,182 @@
+"""Seeded synthetic workloads shaped like the paper's Llama-3.1 target models.
+
+The paper evaluates Llama-3.1-8B drafting for Llama-3.1-70B / 405B targets
+(Sec. 4.2, Table 1; judge width 8192 / 16384 in App. B.1; M = 25 judge drafts and
+M = 10 standard drafts in Sec. 4.2).  None of those weights or prompts exist here,
+so these generators stand in for them: same shapes, Gaussian statistics chosen so
+that logits have unit variance and the draft is a noisy copy of the target.
+
+Every array is a pure function of ``(shape, seed)``.  Randomness comes from
+numpy's counter-based Philox generator, one independent stream per (tensor tag,
+vocabulary chunk), so chunks can be drawn in parallel threads and the result does
+not depend on the thread count.
+
+Nothing in this file is part of the verification method: the only arithmetic is
+drawing numbers, rounding to bf16, one single-precision matmul to make the draft
+logits a perturbed copy of the target logits, and a Gumbel arg-max to draw the
+draft tokens from the draft distribution.
+"""
+
+from __future__ import annotations
+
+import os
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
+from typing import Dict, Tuple, Union
+
+import numpy as np
+
+# tensor tags: each selects its own family of Philox streams
+_TAG_EMB, _TAG_W, _TAG_JUDGE, _TAG_SCALE, _TAG_NOISE, _TAG_GUMBEL, _TAG_UNIF = range(1, 8)
+
+_VOCAB_CHUNK = 2048  # rows of W_lm drawn per Philox stream
+
+
+@dataclass(frozen=True)
+class VerifyShape:
+    """One verification workload: B sequences, M drafted tokens (+1 bonus row)."""
+
+    name: str
+    B: int
+    M: int
+    d: int
+    V: int
+    dtype: str  # "f32" | "bf16": storage type of embeddings, W_lm and w_judge
+    noise: Union[float, Tuple[float, float]]  # std of draft-logit noise, or U(lo, hi) per sequence
+    note: str = ""
+
+    @property
+    def R(self) -> int:
+        return self.B * (self.M + 1)
+
+
+CONFIGS: Dict[str, VerifyShape] = {
+    "C1": VerifyShape("C1", 1, 5, 256, 1024, "f32", 1.0, "tiny oracle-scale verify, fp32"),
+    "C2": VerifyShape("C2", 1, 5, 4096, 128256, "bf16", 1.5, "Llama-3.1-8B-shaped head"),
+    "C3": VerifyShape("C3", 1, 25, 8192, 128256, "bf16", 1.0, "Llama-3.1-70B-shaped head, long drafts"),
+    "C4": VerifyShape("C4", 1, 25, 16384, 128256, "bf16", 2.0, "Llama-3.1-405B-shaped head (headline, HBM bound)"),
+    "C5": VerifyShape("C5", 64, 10, 8192, 128256, "bf16", (0.5, 2.5), "batched verification (MFMA bound)"),
+}
+
+
+def bf16_bits_from_f32(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (round-to-nearest-even) and return the 16-bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def f32_from_bf16_bits(b: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns to float32 (exact)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _stream(seed: int, tag: int, chunk: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64((tag << 40) | chunk)]))
+
+
+def _n_threads() -> int:
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:  # pragma: no cover
+        avail = os.cpu_count() or 1
+    return max(1, min(16, avail))
+
+
+def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
+    """Draw every input of one verify call.
+
+    Returns a dict with
+      emb           [B, M+1, d]  float32, or uint16 bf16 bit patterns
+      W             [V, d]       same storage type; row v is vocabulary entry v (K contiguous)
+      w_judge       [d]          same storage type
+      draft_logits  [B, M+1, V]  float32 (row M is present but unused by verification)
+      draft_tokens  [B, M]       int32, token j drawn from softmax(draft_logits[:, j])
+      uniforms      [B, M+1]     float32 in [0, 1): M accept draws, then one sampler draw
+    """
+    B, M, d, V = shape.B, shape.M, shape.d, shape.V
+    R = B * (M + 1)
+    is_bf16 = shape.dtype == "bf16"
+    if shape.dtype not in ("f32", "bf16"):
+        raise ValueError(f"unknown dtype {shape.dtype!r}")
+
+    # embeddings: N(0,1), each row rescaled to unit rms, then stored
+    h = _stream(seed, _TAG_EMB).standard_normal((R, d), dtype=np.float32)
+    h /= np.sqrt(np.mean(h.astype(np.float64) ** 2, axis=1, keepdims=True)).astype(np.float32)
+    if is_bf16:
+        emb_store = bf16_bits_from_f32(h)
+        h = f32_from_bf16_bits(emb_store)
+    else:
+        emb_store = h.copy()
+
+    wj = _stream(seed, _TAG_JUDGE).standard_normal(d, dtype=np.float32) * np.float32(1.0 / np.sqrt(d))
+    wj_store = bf16_bits_from_f32(wj) if is_bf16 else wj
+
+    if isinstance(shape.noise, tuple):
+        lo, hi = shape.noise
+        sigma_b = _stream(seed, _TAG_SCALE).uniform(lo, hi, size=B).astype(np.float32)
+    else:
+        sigma_b = np.full(B, shape.noise, dtype=np.float32)
+    sigma_r = np.repeat(sigma_b, M + 1)[:, None]  # [R, 1]
+
+    W_store = np.empty((V, d), dtype=np.uint16 if is_bf16 else np.float32)
+    D = np.empty((R, V), dtype=np.float32)
+    best_val = np.full(R, -np.inf, dtype=np.float32)
+    best_idx = np.zeros(R, dtype=np.int64)
+    inv_sqrt_d = np.float32(1.0 / np.sqrt(d))
+
+    def draw_chunk(ci: int):
+        v0 = ci * _VOCAB_CHUNK
+        rows = min(_VOCAB_CHUNK, V - v0)
+        w = _stream(seed, _TAG_W, ci).standard_normal((rows, d), dtype=np.float32)
+        w *= inv_sqrt_d
+        w_bits = bf16_bits_from_f32(w) if is_bf16 else None
+        noise = _stream(seed, _TAG_NOISE, ci).standard_normal((R, rows), dtype=np.float32)
+        gumbel = _stream(seed, _TAG_GUMBEL, ci).gumbel(size=(R, rows)).astype(np.float32)
+        return ci, (w_bits if is_bf16 else w), noise, gumbel
+
+    n_chunks = (V + _VOCAB_CHUNK - 1) // _VOCAB_CHUNK
+    nthreads = _n_threads()
+    with ThreadPoolExecutor(max_workers=nthreads) as pool:
+        # keep at most ~2*nthreads chunks in flight so float32 temporaries stay bounded
+        pending = []
+        next_ci = 0
+
+        def top_up():
+            nonlocal next_ci
+            while next_ci < n_chunks and len(pending) < 2 * nthreads:
+                pending.append(pool.submit(draw_chunk, next_ci))
+                next_ci += 1
+
+        top_up()
+        while pending:
+            ci, w_chunk, noise, gumbel = pending.pop(0).result()
+            top_up()
+            v0 = ci * _VOCAB_CHUNK
+            rows = w_chunk.shape[0]
+            W_store[v0:v0 + rows] = w_chunk
+            w32 = f32_from_bf16_bits(w_chunk) if is_bf16 else w_chunk
+            # draft logits = (single-precision) target logits + Gaussian noise
+            Dc = h @ w32.T
+            Dc += sigma_r * noise
+            D[:, v0:v0 + rows] = Dc
+            # Gumbel arg-max draws one token per row from softmax(D[row])
+            g = Dc + gumbel
+            loc = np.argmax(g, axis=1)
+            val = g[np.arange(R), loc]
+            upd = val > best_val
+            best_val[upd] = val[upd]
+            best_idx[upd] = loc[upd] + v0
+
+    tokens = best_idx.reshape(B, M + 1)[:, :M].astype(np.int32)
+    uniforms = _stream(seed, _TAG_UNIF).random((B, M + 1), dtype=np.float32)
+
+    return {
+        "emb": emb_store.reshape(B, M + 1, d),
+        "W": W_store,
+        "w_judge": wj_store,
+        "draft_logits": D.reshape(B, M + 1, V),
+        "draft_tokens": np.ascontiguousarray(tokens),
+        "uniforms": uniforms,
+        "sigma_b": sigma_b,
+    }

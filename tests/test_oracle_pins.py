@@ -1,0 +1,501 @@
+"""Pins for the float64 oracle: things the paper and the mathematics fix, none of
+which is computed by the oracle itself.
+
+  * Eq. 4 on hand cases, the OR rule and the prefix cut (text fixtures)
+  * exact integer arithmetic for the LM-head contraction (catches a transposed
+    operand or a wrong index)
+  * scipy / closed forms for softmax and the inverse CDF
+  * brute-force enumeration at V = 8, M = 3 with every interval edge probed
+  * Monte-Carlo chi-square: standard-only verification emits the target distribution
+    (and the plausible wrong reading "resample from p" is shown to fail it)
+  * residual invariants, special cases, judge row offset
+  * acceptance statistics of the synthetic workloads against the closed form
+    1 - TV(p, q) -> 2 Phi(-sigma / 2)
+"""
+
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+
+from oracle import verify_oracle as vo
+from synth import VerifyShape, make_inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- builders
+
+def direct_case(P_rows, Q_rows, judge_bits, tokens, uniforms, **kw):
+    """Build oracle inputs whose target distributions are exactly softmax(log P_rows).
+
+    d = V, W = identity, embeddings = float32(log P).  The judge reads a separate
+    tensor whose row j+1 is (+1 | -1, 0, ...) with w_judge = e_0, so judge logits
+    are +-1.  Draft is handed over as probabilities.
+    """
+    P_rows = np.asarray(P_rows, dtype=np.float64)
+    Mp1, V = P_rows.shape
+    M = Mp1 - 1
+    tokens = np.asarray(tokens, dtype=np.int32).reshape(-1, M)
+    B = tokens.shape[0]
+    emb = np.broadcast_to(np.log(P_rows).astype(np.float32), (B, Mp1, V)).copy()
+    W = np.eye(V, dtype=np.float32)
+    ej = np.zeros((B, Mp1, V), dtype=np.float32)
+    jb = np.asarray(judge_bits).reshape(-1, M)
+    ej[:, 1:, 0] = np.where(np.broadcast_to(jb, (B, M)) > 0, 1.0, -1.0)
+    ej[:, 0, 0] = 77.0  # row 0 must never be read by the judge
+    wj = np.zeros(V, dtype=np.float32); wj[0] = 1.0
+    Q = np.broadcast_to(np.asarray(Q_rows, dtype=np.float32), (B, M, V)).copy()
+    u = np.asarray(uniforms, dtype=np.float32).reshape(B, Mp1)
+    return vo.verify(emb, W, wj, tokens, Q, u, emb_judge=ej, draft_kind=vo.DRAFT_PROBS, **kw)
+
+
+def py_softmax(logits):
+    mx = max(logits)
+    ex = [math.exp(x - mx) for x in logits]
+    s = math.fsum(ex)
+    return [e / s for e in ex]
+
+
+def random_dist(rng, V, conc=1.0):
+    x = rng.gamma(conc, size=V) + 1e-3
+    return x / x.sum()
+
+
+# ----------------------------------------------------------------------------- Eq. 4, OR, prefix
+
+def test_eq4_hand_cases():
+    # p >= q: accepted for every eps in [0, 1)
+    for u in (0.0, 0.3, 0.999999, float(np.float32(1) - np.float32(2 ** -24))):
+        assert vo.accept_standard(u, 0.6, 0.5)
+        assert vo.accept_standard(u, 0.5, 0.5) == (u < 1.0)
+    # p = q / 2: accepted iff eps < 1/2 (strict)
+    assert vo.accept_standard(0.49999, 0.2, 0.4)
+    assert not vo.accept_standard(0.5, 0.2, 0.4)
+    assert not vo.accept_standard(0.50001, 0.2, 0.4)
+    # q[c] = 0 corner: accept iff p[c] > 0, no NaN
+    assert vo.accept_standard(0.9, 0.1, 0.0)
+    assert not vo.accept_standard(0.0, 0.0, 0.0)
+
+
+def _golden_cases():
+    with open(os.path.join(GOLDEN, "mask_prefix_cases.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            lhs, rhs = line.split("->")
+            zs, zj = lhs.split()
+            z, m = rhs.split()
+            yield [int(c) for c in zs], [int(c) for c in zj], [int(c) for c in z], int(m)
+
+
+def test_prefix_and_or_fixture():
+    rng = np.random.default_rng(5)
+    n = 0
+    for zs, zj, z, m in _golden_cases():
+        n += 1
+        M, V = len(zs), 8
+        assert vo.accepted_prefix(z) == m
+        # realise the masks through the full oracle: z_stand via p/q and eps
+        P = np.stack([random_dist(rng, V) for _ in range(M + 1)])
+        Q = np.stack([random_dist(rng, V) for _ in range(M)])
+        toks, us = [], []
+        for j in range(M):
+            ratio = P[j] / Q[j].astype(np.float32).astype(np.float64)
+            if zs[j]:
+                c = int(np.argmax(ratio)); u = min(0.99, 0.5 * ratio[c])
+            else:
+                c = int(np.argmin(ratio)); assert ratio[c] < 0.9; u = 0.5 * (ratio[c] + 1.0)
+            toks.append(c); us.append(u)
+        out = direct_case(P, Q, zj, toks, us + [0.37])
+        assert out["z_stand"][0].tolist() == zs
+        assert out["z_judge"][0].tolist() == zj
+        assert int(out["accept_len"][0]) == m
+        # standard-only mode ignores the judge; OR can only add accepts
+        std = direct_case(P, Q, zj, toks, us + [0.37], mode=vo.MODE_STANDARD)
+        assert int(std["accept_len"][0]) == vo.accepted_prefix(zs) <= m
+        # delta = 1 reduces to standard SD (Sec. 4.1)
+        d1 = direct_case(P, Q, zj, toks, us + [0.37], delta=1.0)
+        assert int(d1["accept_len"][0]) == int(std["accept_len"][0])
+        assert int(d1["next_token"][0]) == int(std["next_token"][0])
+        assert not d1["z_judge"].any()
+    assert n >= 10
+
+
+def test_judge_threshold_and_logit_form():
+    assert vo.judge_threshold(0.5) == 0.0
+    assert vo.judge_threshold(1.0) == math.inf
+    for delta in (0.6, 0.9, 0.999):
+        t = vo.judge_threshold(delta)
+        # sigmoid(t) == delta and the comparison is monotone around it
+        assert abs(scipy.special.expit(t) - delta) < 1e-15
+        assert scipy.special.expit(t + 1e-9) > delta > scipy.special.expit(t - 1e-9)
+    with pytest.raises(ValueError):
+        vo.judge_threshold(0.4)
+
+
+def test_judge_reads_row_of_the_judged_token():
+    # Sec. 4.1: c_i is judged on its own embedding e_i; with rows [s_L, c_1..c_M]
+    # that is row j+1 for slot j.  Only row j+1 carries a positive judge logit.
+    V, M = 8, 4
+    rng = np.random.default_rng(0)
+    P = np.stack([random_dist(rng, V) for _ in range(M + 1)])
+    Q = P[:M].copy()
+    for target in range(M):
+        bits = [1 if j == target else 0 for j in range(M)]
+        out = direct_case(P, Q, bits, [0] * M, [0.5] * (M + 1))
+        assert out["z_judge"][0].tolist() == bits
+        assert np.allclose(out["judge_logit"][0], np.where(np.array(bits) > 0, 1.0, -1.0))
+    # bias shifts the logit; threshold moves with delta
+    out = direct_case(P, Q, [0] * M, [0] * M, [0.5] * (M + 1), judge_bias=1.5)
+    assert out["z_judge"].all() and np.allclose(out["judge_logit"], 0.5)
+    out = direct_case(P, Q, [1] * M, [0] * M, [0.5] * (M + 1), delta=0.75)  # logit(0.75)=1.0986 > 1
+    assert not out["z_judge"].any()
+    assert np.allclose(out["judge_margin"], math.log(3.0) - 1.0)
+
+
+# ----------------------------------------------------------------------------- textbook reductions
+
+def test_logits_exact_integer_arithmetic():
+    # integer-valued operands: the contraction is exact, compare with Python ints
+    rng = np.random.default_rng(1)
+    R, d, V = 3, 7, 11
+    X = rng.integers(-8, 9, size=(R, d)); W = rng.integers(-8, 9, size=(V, d))
+    want = [[sum(int(X[r, k]) * int(W[v, k]) for k in range(d)) for v in range(V)] for r in range(R)]
+    got = vo.target_logits(X.astype(np.float32), W.astype(np.float32))
+    assert got.shape == (R, V) and np.array_equal(got, np.array(want, dtype=np.float64))
+    got_dv = vo.target_logits(X.astype(np.float32), np.ascontiguousarray(W.T).astype(np.float32), w_layout="dv")
+    assert np.array_equal(got_dv, got)
+    got_T = vo.target_logits(X.astype(np.float32), W.astype(np.float32), temperature=2.0)
+    assert np.array_equal(got_T, got / 2.0)
+
+
+def test_bf16_widening_is_exact():
+    bits = np.array([0x3F80, 0xBF80, 0x4049, 0x0000, 0x8000, 0x3DCD, 0x7F7F], dtype=np.uint16)
+    want = [1.0, -1.0, 3.140625, 0.0, -0.0, 0.10009765625, 3.3895313892515355e38]
+    assert vo.widen(bits).tolist() == want
+    # chunked path must see every vocabulary row once (chunk edge at 2048)
+    rng = np.random.default_rng(2)
+    V, d = 2048 + 37, 16
+    Wb = rng.integers(0x3C00, 0x4100, size=(V, d)).astype(np.uint16)
+    x = np.zeros((1, d), dtype=np.float32); x[0, 3] = 1.0
+    assert np.array_equal(vo.target_logits(x, Wb)[0], vo.widen(Wb)[:, 3])
+
+
+def test_softmax_against_scipy():
+    rng = np.random.default_rng(3)
+    L = rng.normal(size=(5, 1000)) * 4.0
+    L[2] += 700.0  # would overflow a naive exp
+    P, m, s = vo.softmax_rows(L)
+    assert np.allclose(P, scipy.special.softmax(L, axis=1), rtol=1e-12, atol=0)
+    assert np.allclose(np.log(P), scipy.special.log_softmax(L, axis=1), rtol=0, atol=1e-12)
+    assert np.allclose(P.sum(1), 1.0, atol=1e-12)
+    assert np.array_equal(m, L.max(1))
+    assert np.allclose(np.log(s) + m, scipy.special.logsumexp(L, axis=1), atol=1e-12)
+
+
+def test_inverse_cdf_closed_forms():
+    # uniform mass over V tokens: token = floor(u * V)
+    V = 10
+    for u in (0.0, 0.05, 0.1, 0.15, 0.95, 0.999999):
+        tok, _ = vo.inverse_cdf(np.ones(V), u)
+        # u*V exactly on an edge belongs to the upper token (cdf > thresh is strict)
+        assert tok == int(math.floor(u * V + 1e-12))
+    # zero-mass tokens are never returned, including at u = 0 and u -> 1
+    mass = np.array([0.0, 0.0, 2.0, 0.0, 1.0, 0.0])
+    assert vo.inverse_cdf(mass, 0.0)[0] == 2
+    assert vo.inverse_cdf(mass, 0.66)[0] == 2
+    assert vo.inverse_cdf(mass, 0.67)[0] == 4
+    assert vo.inverse_cdf(mass, 1.0 - 2 ** -24)[0] == 4
+    # searchsorted form on random mass; margin is the distance to the nearest edge
+    rng = np.random.default_rng(4)
+    mass = rng.random(257) * (rng.random(257) > 0.3)
+    cdf = np.cumsum(mass); S = mass.sum()
+    for u in rng.random(200):
+        tok, margin = vo.inverse_cdf(mass, u)
+        assert tok == int(np.searchsorted(cdf, u * S, side="right"))
+        assert mass[tok] > 0 and 0 <= margin <= mass[tok] / S
+
+
+# ----------------------------------------------------------------------------- residual
+
+def test_residual_invariants():
+    rng = np.random.default_rng(6)
+    for _ in range(50):
+        V = int(rng.integers(2, 200))
+        p, q = random_dist(rng, V, 0.3), random_dist(rng, V, 0.3)
+        r = vo.residual(p, q)
+        assert (r >= 0).all()
+        S = r.sum()
+        assert abs(S - (1.0 - np.minimum(p, q).sum())) < 1e-12
+        assert abs(S - np.maximum(0.0, q - p).sum()) < 1e-12
+        assert abs((r / S).sum() - 1.0) < 1e-12
+        # a token the standard test can reject has p < q, hence zero residual mass
+        assert (r[p < q] == 0).all()
+
+
+def test_rejected_token_is_never_reemitted():
+    shape = VerifyShape("t", 32, 4, 32, 96, "f32", 1.5)
+    for seed in range(3):
+        x = make_inputs(shape, seed)
+        out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"],
+                        x["uniforms"], mode=vo.MODE_STANDARD)
+        rej = out["accept_len"] < shape.M
+        assert rej.any()
+        b = np.nonzero(rej)[0]
+        assert (out["next_token"][b] != x["draft_tokens"][b, out["accept_len"][b]]).all()
+        assert (out["status"] == 0).all()
+
+
+# ----------------------------------------------------------------------------- brute force V=8, M=3
+
+def _brute_setup():
+    rng = np.random.default_rng(11)
+    V, M = 8, 3
+    P = np.stack([random_dist(rng, V, 0.7) for _ in range(M + 1)])
+    Q = np.stack([random_dist(rng, V, 0.7) for _ in range(M)]).astype(np.float32)
+    judge_bits = [0, 1, 0]
+    # independent evaluation of what the oracle should see: p from float32 logits
+    Pt = [py_softmax([float(x) for x in np.log(P[r]).astype(np.float32)]) for r in range(M + 1)]
+    Qt = [[float(x) for x in Q[j]] for j in range(M)]
+    return V, M, P, Q, judge_bits, Pt, Qt
+
+
+def _mass_after(m, M, Pt, Qt, V):
+    if m < M:
+        return [max(0.0, Pt[m][v] - Qt[m][v]) for v in range(V)]
+    return list(Pt[M])
+
+
+def test_bruteforce_every_interval_edge():
+    V, M, P, Q, jb, Pt, Qt = _brute_setup()
+    eps = 1e-6  # probes sit this far inside each interval (float32 uniforms resolve 6e-8)
+    toks, us, want_m, want_tok = [], [], [], []
+    for c in itertools.product(range(V), repeat=M):
+        a = [min(1.0, Pt[j][c[j]] / Qt[j][c[j]]) for j in range(M)]  # Pr[z_stand_j = 1]
+        for m in range(M + 1):
+            # force prefix length m: slots < m accepted (judge bit, or eps just inside),
+            # slot m rejected (needs judge bit 0 and a < 1, eps just outside)
+            if m < M and (jb[m] or a[m] >= 1.0 - 2 * eps):
+                continue
+            u = []
+            for j in range(M):
+                if j < m:
+                    u.append(0.999 if jb[j] else max(0.0, a[j] - eps))
+                    if not jb[j] and a[j] - eps <= 0.0:
+                        break
+                elif j == m:
+                    u.append(a[j] + eps)
+                else:
+                    u.append(0.123)  # irrelevant after the cut
+            if len(u) < M:
+                continue
+            mass = _mass_after(m, M, Pt, Qt, V)
+            S = math.fsum(mass)
+            edge = 0.0
+            for v in range(V):
+                lo, hi = edge / S, (edge + mass[v]) / S
+                edge += mass[v]
+                if hi - lo < 4 * eps:
+                    continue
+                for us_ in (lo + eps, hi - eps):
+                    toks.append(c); us.append(u + [us_]); want_m.append(m); want_tok.append(v)
+    assert len(toks) > 10000
+    out = direct_case(P, Q, jb, toks, us)
+    assert np.array_equal(out["accept_len"], np.array(want_m))
+    assert np.array_equal(out["next_token"], np.array(want_tok))
+    assert (out["status"] == 0).all()
+
+
+def test_bruteforce_law_on_a_grid():
+    # Law of (m*, next) for fixed drafts: Pr[z_j = 1] = 1 if judge bit else min(1, p/q);
+    # Pr[next = v | m* = m] = mass_m[v] / S_m.  A midpoint grid over the four uniforms
+    # must reproduce it to grid resolution.
+    V, M, P, Q, jb, Pt, Qt = _brute_setup()
+    G, GS = 8, 64
+    mids = (np.arange(G) + 0.5) / G
+    smid = (np.arange(GS) + 0.5) / GS
+    grid = np.array([(a, b, c, s) for a in mids for b in mids for c in mids for s in smid])
+    for c in [(0, 1, 2), (7, 7, 7), (3, 0, 5)]:
+        out = direct_case(P, Q, jb, [c] * len(grid), grid)
+        acc = [1.0 if jb[j] else min(1.0, Pt[j][c[j]] / Qt[j][c[j]]) for j in range(M)]
+        for m in range(M + 1):
+            pm = np.prod(acc[:m]) * ((1.0 - acc[m]) if m < M else 1.0)
+            sel = out["accept_len"] == m
+            assert abs(sel.mean() - pm) <= 1.5 / G
+            if pm < 0.05:
+                continue
+            mass = _mass_after(m, M, Pt, Qt, V)
+            S = math.fsum(mass)
+            for v in range(V):
+                emp = (out["next_token"][sel] == v).mean()
+                assert abs(emp - mass[v] / S) <= 2.0 / GS
+
+
+def test_vectorised_tier_matches_scalar_tier():
+    for seed, kind in [(0, "f32"), (1, "bf16"), (2, "f32")]:
+        shape = VerifyShape("t", 2, 3, 8, 32, kind, 1.0)
+        x = make_inputs(shape, seed)
+        for mode in (vo.MODE_JUDGE, vo.MODE_STANDARD):
+            out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"],
+                            x["uniforms"], mode=mode)
+            acc, nxt, zs, zj = vo.verify_scalar(x["emb"], x["W"], x["w_judge"], x["draft_tokens"],
+                                                x["draft_logits"], x["uniforms"], mode=mode)
+            assert out["accept_len"].tolist() == acc
+            assert out["next_token"].tolist() == nxt
+            assert out["z_stand"].tolist() == zs and out["z_judge"].tolist() == zj
+
+
+# ----------------------------------------------------------------------------- Monte-Carlo
+
+def _first_emitted(out, tokens):
+    first = np.where(out["accept_len"] > 0, tokens[:, 0], out["next_token"])
+    return first
+
+
+def test_standard_verification_preserves_target_distribution():
+    # Sec. 1 / Sec. 3.1: standard SD emits tokens distributed exactly as the target.
+    # Draw c ~ q, eps, u_s many times; the first emitted token must follow p_1.
+    rng = np.random.default_rng(2025)
+    V, M, N = 8, 2, 120_000
+    P = np.stack([random_dist(rng, V, 0.8) for _ in range(M + 1)])
+    Q = np.stack([random_dist(rng, V, 0.8) for _ in range(M)]).astype(np.float32)
+    q0 = Q[0].astype(np.float64); q0 /= q0.sum()
+    Qn = Q.astype(np.float64) / Q.astype(np.float64).sum(1, keepdims=True)
+    tokens = np.stack([rng.choice(V, size=N, p=Qn[j]) for j in range(M)], 1)
+    u = rng.random((N, M + 1)).astype(np.float32)
+    out = direct_case(P, Q, [0] * M, tokens, u, mode=vo.MODE_STANDARD)
+    p1 = np.array(py_softmax([float(x) for x in np.log(P[0]).astype(np.float32)]))
+    first = _first_emitted(out, tokens)
+    counts = np.bincount(first, minlength=V)
+    chi = scipy.stats.chisquare(counts, p1 * N)
+    assert chi.pvalue > 0.01, chi
+    # second emitted token given the first was accepted follows p_2
+    sel = out["accept_len"] >= 1
+    second = np.where(out["accept_len"][sel] > 1, tokens[sel, 1], out["next_token"][sel])
+    p2 = np.array(py_softmax([float(x) for x in np.log(P[1]).astype(np.float32)]))
+    chi2 = scipy.stats.chisquare(np.bincount(second, minlength=V), p2 * sel.sum())
+    assert chi2.pvalue > 0.01, chi2
+    # all accepted: the bonus token follows p_{M+1}
+    full = out["accept_len"] == M
+    p3 = np.array(py_softmax([float(x) for x in np.log(P[2]).astype(np.float32)]))
+    chi3 = scipy.stats.chisquare(np.bincount(out["next_token"][full], minlength=V), p3 * full.sum())
+    assert chi3.pvalue > 0.01, chi3
+
+    # power of the test: resampling from plain p after a rejection (the wrong reading
+    # of "sample a correct token from p_i") is rejected by the same statistic
+    cdf = np.cumsum(p1)
+    wrong = np.where(out["accept_len"] > 0, tokens[:, 0],
+                     np.minimum(np.searchsorted(cdf, u[:, M].astype(np.float64) * cdf[-1], side="right"), V - 1))
+    assert scipy.stats.chisquare(np.bincount(wrong, minlength=V), p1 * N).pvalue < 1e-6
+    # and so is a rule with the ratio upside down (eps < q/p)
+    flipped = u[:, 0] * p1[tokens[:, 0]] < q0[tokens[:, 0]]
+    wrong2 = np.where(flipped, tokens[:, 0], out["next_token"])
+    assert scipy.stats.chisquare(np.bincount(wrong2, minlength=V), p1 * N).pvalue < 1e-6
+
+
+# ----------------------------------------------------------------------------- special cases
+
+def _exact_logit_inputs(seed, B=3, M=4, d=16, V=40):
+    """Embeddings / weights on a coarse dyadic grid so that logits are exact in float32."""
+    rng = np.random.default_rng(seed)
+    emb = (rng.integers(-8, 9, size=(B, M + 1, d)) / 8.0).astype(np.float32)
+    W = (rng.integers(-8, 9, size=(V, d)) / 8.0).astype(np.float32)
+    wj = (rng.integers(-8, 9, size=d) / 8.0).astype(np.float32)
+    L = np.einsum("brk,vk->brv", emb.astype(np.float64), W.astype(np.float64))
+    assert np.array_equal(L, L.astype(np.float32).astype(np.float64))
+    tokens = rng.integers(0, V, size=(B, M)).astype(np.int32)
+    return emb, W, wj, L.astype(np.float32), tokens
+
+
+def test_identical_draft_accepts_everything():
+    emb, W, wj, L32, tokens = _exact_logit_inputs(0)
+    B, Mp1, _ = emb.shape
+    for u_val in (0.0, 0.5, float(np.float32(1) - np.float32(2 ** -24))):
+        u = np.full((B, Mp1), u_val, dtype=np.float32)
+        out = vo.verify(emb, W, wj, tokens, L32, u, mode=vo.MODE_STANDARD)
+        assert (out["accept_len"] == Mp1 - 1).all()
+        assert out["z_stand"].all()
+        assert np.array_equal(out["p_at_draft"], out["q_at_draft"])
+
+
+def test_huge_judge_bias_gives_bonus_token_from_last_row():
+    emb, W, wj, L32, tokens = _exact_logit_inputs(1)
+    B, Mp1, _ = emb.shape
+    rng = np.random.default_rng(9)
+    D = (L32 + rng.normal(size=L32.shape) * 3).astype(np.float32)
+    u = rng.random((B, Mp1)).astype(np.float32)
+    out = vo.verify(emb, W, wj, tokens, D, u, judge_bias=1e6)
+    assert (out["accept_len"] == Mp1 - 1).all() and out["z_judge"].all()
+    for b in range(B):
+        pM = scipy.special.softmax(L32[b, -1].astype(np.float64))
+        want = int(np.searchsorted(np.cumsum(pM), float(u[b, -1]) * pM.sum(), side="right"))
+        assert int(out["next_token"][b]) == want
+
+
+def test_all_rejecting_case_gives_zero_prefix():
+    emb, W, wj, L32, tokens = _exact_logit_inputs(2)
+    B, Mp1, V = L32.shape
+    D = L32.copy()
+    for b in range(B):
+        for j in range(Mp1 - 1):
+            D[b, j, tokens[b, j]] += 5.0  # q[c] > p[c] at every drafted token
+    u = np.full((B, Mp1), np.float32(1) - np.float32(2 ** -24), dtype=np.float32)
+    out = vo.verify(emb, W, wj, tokens, D, u, judge_bias=-1e6)
+    assert (out["accept_len"] == 0).all() and not out["z_stand"].any() and not out["z_judge"].any()
+    assert (out["next_token"] != tokens[:, 0]).all()
+
+
+def test_bad_token_and_nan_status():
+    emb, W, wj, L32, tokens = _exact_logit_inputs(3)
+    B, Mp1, V = L32.shape
+    u = np.full((B, Mp1), 0.25, dtype=np.float32)
+    tokens = tokens.copy(); tokens[1, 2] = V; tokens[2, 0] = -1
+    Dn = (L32 + np.random.default_rng(0).normal(size=L32.shape)).astype(np.float32)
+    out = vo.verify(emb, W, wj, tokens, Dn, u, judge_bias=1e6)
+    assert out["status"].tolist() == [0, vo.STATUS_BAD_TOKEN, vo.STATUS_BAD_TOKEN]
+    assert out["accept_len"].tolist() == [Mp1 - 1, 2, 0]
+    # q == p at the cut leaves no residual mass: flagged, and the token comes from p
+    out = vo.verify(emb, W, wj, tokens, L32, u, judge_bias=1e6)
+    assert out["status"].tolist() == [0, vo.STATUS_BAD_TOKEN | vo.STATUS_ZERO_RESIDUAL] * 1 + \
+        [vo.STATUS_BAD_TOKEN | vo.STATUS_ZERO_RESIDUAL]
+    pm = scipy.special.softmax(L32[1, 2].astype(np.float64))
+    assert int(out["next_token"][1]) == int(np.searchsorted(np.cumsum(pm), 0.25 * pm.sum(), side="right"))
+    D = L32.copy(); D[0, 1, 5] = np.nan
+    out = vo.verify(emb, W, wj, np.clip(tokens, 0, V - 1), D, u)
+    assert out["status"][0] & vo.STATUS_NAN and not (out["status"][1:] & vo.STATUS_NAN).any()
+
+
+def test_subset_of_sequences_is_exact():
+    shape = VerifyShape("t", 6, 3, 16, 64, "bf16", 1.0)
+    x = make_inputs(shape, 4)
+    args = (x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"])
+    full = vo.verify(*args, return_probs=True)
+    part = vo.verify(*args, seqs=[4, 1], return_probs=True)
+    for k in full:
+        assert np.array_equal(part[k], full[k][[4, 1]]), k
+
+
+# ----------------------------------------------------------------------------- workload statistics
+
+@pytest.mark.parametrize("sigma,want", [(1.0, 0.617), (2.0, 0.326)])
+def test_synthetic_acceptance_rate_matches_closed_form(sigma, want):
+    # draft logits = target logits + sigma * N(0,1) iid over a large vocabulary gives a
+    # per-slot standard acceptance probability 1 - TV(p, q) -> 2 Phi(-sigma/2)
+    # (0.617 at sigma = 1; at V = 1024 the finite-vocabulary value for sigma = 2 is 0.326).
+    shape = VerifyShape("t", 64, 5, 64, 1024, "f32", sigma)
+    acc, n, jacc = 0, 0, 0
+    for seed in range(4):
+        x = make_inputs(shape, seed)
+        out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"])
+        acc += int(out["z_stand"].sum()); jacc += int(out["z_judge"].sum()); n += out["z_stand"].size
+        assert (out["status"] == 0).all()
+    assert abs(acc / n - want) < 0.045
+    assert abs(scipy.stats.norm.cdf(-0.5) * 2 - 0.617) < 1e-3
+    # the synthetic judge is a fair coin per slot
+    assert abs(jacc / n - 0.5) < 0.05
