@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched verification head on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4] [--seed 0] [--no-cpu-baseline]
+
+One step = one jd_verify_run call (LM head, vocabulary softmax, draft statistics, accept
+tests, judge, OR, accepted prefix, residual/bonus sampler) on one batch of seeded
+synthetic inputs that are already resident in HBM.  Prints ONE JSON line.
+
+The headline workload is the Llama-3.1-405B-shaped head (B=1, M=25, d=16384, V=128256,
+bf16 weights): the metric "verified draft positions/s" = B*M / time per call, with the
+fraction of the 8 TB/s HBM roofline reached by the LM-head kernel that dominates it.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+# HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the verification head is built and measured on a "
+              "single MI355X; no collectives exist). Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2501_19309_amd import binding as jb, harness
+    from synth import CONFIGS, make_inputs
+
+    jb.load_library()  # no fallback: raises when the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a HIP device"
+    shape = CONFIGS[args.config]
+    B, M, d, V = shape.B, shape.M, shape.d, shape.V
+    R = B * (M + 1)
+
+    t0 = time.time()
+    x = make_inputs(shape, args.seed)
+    log(f"[bench] inputs for {shape.name} drawn in {time.time() - t0:.1f}s")
+    dev = harness.to_device(x)
+    ver = harness.make_verifier(dev)
+    out = ver.alloc_outputs(B, M)
+    torch.cuda.synchronize()
+    log(f"[bench] context ready, workspace {ver.workspace_bytes() / 2**30:.2f} GiB")
+
+    def step():
+        ver.run(dev["emb"], dev["draft_tokens"], dev["draft_logits"], dev["uniforms"], out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps, HIP events around every kernel group on the same stream
+    K = args.steps
+    ver.profile_begin(K)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms, n_prof = ver.profile_end()
+    ms_per_step = (t1 - t0) * 1e3 / K
+
+    # same K steps without the per-kernel events (reported for reference)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    ms_plain = (time.perf_counter() - t0) * 1e3 / K
+    log(f"[bench] ms/step with events {ms_per_step:.4f}, without {ms_plain:.4f}; kernels {kernel_ms}")
+
+    got = out.to_numpy()
+    elem = 2 if shape.dtype == "bf16" else 4
+    w_bytes = V * d * elem
+    x_bytes = R * d * elem
+    lm_ms = kernel_ms["lmhead"]
+    flops = 2.0 * R * d * V
+    if args.config == "C5":
+        achieved = flops / (lm_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)}
+    else:
+        achieved = (w_bytes + x_bytes) / (lm_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)}
+    roofline["kernel"] = "lmhead"
+    roofline["kernel_ms"] = lm_ms
+    roofline["algorithmic_bytes"] = w_bytes + x_bytes
+    roofline["algorithmic_flops"] = flops
+
+    # whole-call algorithmic bytes: W + X + draft rows once + one target and one draft row again
+    call_bytes = w_bytes + x_bytes + B * M * V * 4 + B * V * 8 + B * (2 * M + 1) * 4
+    record = {
+        "metric": "verified draft positions/s (verify head, 1 GPU)",
+        "value": B * M / (ms_per_step * 1e-3),
+        "unit": "positions/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{shape.name}: B={B} M={M} (+1 bonus row) d={d} V={V} {shape.dtype} W_lm, "
+                               f"fp32 draft logits; {shape.note}", "seed": args.seed,
+                   "rows": R, "W_lm_bytes": w_bytes,
+                   "W_lm_retiled_copy": shape.dtype == "bf16"},
+        "roofline": roofline,
+        "whole_call": {"ms_per_step_without_events": ms_plain, "algorithmic_bytes": call_bytes,
+                       "gbs": call_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "frac_hbm_peak": call_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "kernel_ms": kernel_ms},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import verify_oracle as vo
+        from oracle.compare import compare
+        try:
+            from threadpoolctl import threadpool_info
+            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            blas_threads = 1
+        cores = len(os.sched_getaffinity(0))
+        # bounded sample: whole call when B == 1, else the first sequences up to ~26 rows
+        seqs = list(range(B)) if R <= 32 else list(range(max(1, 26 // (M + 1))))
+        t0 = time.perf_counter()
+        ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+                        seqs=seqs)
+        t_cpu = time.perf_counter() - t0
+        record["cpu_baseline"] = {
+            "value": len(seqs) * M / t_cpu, "unit": "positions/s", "cores": min(cores, blas_threads),
+            "kind": "oracle", "seconds": t_cpu,
+            "sample": (f"one full verify call of the same workload ({len(seqs)} of {B} sequences, "
+                       f"{len(seqs) * (M + 1)} rows, all {V} vocabulary entries), float64 numpy oracle"),
+        }
+        sub = {k: v[seqs] for k, v in got.items()}
+        try:
+            rep = compare(sub, ref)
+            record["parity"] = {"ok": True, **{k: v for k, v in rep.items()}}
+        except AssertionError as e:
+            record["parity"] = {"ok": False, "error": str(e)[:300]}
+
+    ver.destroy()
+    print(json.dumps(record))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

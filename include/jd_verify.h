@@ -1,0 +1,163 @@
+/*
+ * jd_verify.h - C ABI of the batched verification head of Judge Decoding
+ * (arXiv 2501.19309) for AMD MI355X (gfx950).
+ *
+ * One call verifies, for B independent sequences, M drafted tokens against the
+ * target model's final-layer embeddings of the M+1 positions [s_L, c_1, ..., c_M]
+ * (Fig. 4, right):
+ *
+ *   1. LM head: L[b,r,:] = (x[b,r,:] . W_lm) / T, p_{r+1} = softmax(L[b,r,:])   (Sec. 3.1, Eq. 2)
+ *   2. draft probabilities q_{j+1}[c_{j+1}] from the draft tensor                 (Sec. 3.1, Eq. 3)
+ *   3. standard test   z_stand[j] = ( eps_j * q[c] < p[c] )                       (Sec. 3.1, Eq. 4)
+ *   4. judge test      z_judge[j] = ( w_judge . e[b,j+1,:] + bias > logit(delta) )
+ *      i.e. sigmoid(f_judge(e)) > delta on the embedding of the judged token      (Sec. 4.1; App. B.1)
+ *   5. z = z_stand OR z_judge                                                     (Sec. 4.1, "Inference")
+ *   6. accept_len = number of leading ones of z                                   (Eq. 4; App. B.2, Fig. 8)
+ *   7. next_token: inverse-CDF draw from norm(max(0, p - q)) of the first rejected
+ *      position, or from p_{M+1} when all M were accepted                         (Sec. 3.1, after Eq. 4)
+ *
+ * Index convention (0-based): slot j holds the paper's c_{j+1}, q_{j+1}, eps_{j+1};
+ * its standard test reads LM-head row j, its judge test reads embedding row j+1.
+ *
+ * All tensor arguments are DEVICE pointers owned by the caller and only borrowed:
+ * W_lm and w_judge for the lifetime of the context, everything else for the call.
+ * Tensors are dense, row-major, last index contiguous.  Work is enqueued on the
+ * caller's HIP stream and NOT synchronised; outputs are valid once the stream has
+ * reached the end of the call.  A context is not thread-safe; distinct contexts are
+ * independent.  No function throws; every function returns 0 (JD_OK) or a negative
+ * JD_ERR_* code, and jd_verify_strerror() names it.
+ */
+#ifndef JD_VERIFY_H
+#define JD_VERIFY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- error codes ---------------------------------------------------------------- */
+#define JD_OK                     0
+#define JD_ERR_INVALID_ARG       -1   /* NULL pointer, bad enum, delta outside [0.5,1], T <= 0 ...   */
+#define JD_ERR_SHAPE             -2   /* B/M beyond the context's maxima, M > 63, d % 8 != 0 ...      */
+#define JD_ERR_UNSUPPORTED_DTYPE -3   /* dtype combination the kernels do not cover                   */
+#define JD_ERR_OOM               -4   /* workspace allocation failed                                  */
+#define JD_ERR_HIP               -5   /* a HIP runtime call failed (no device, launch failure)        */
+
+/* ---- enums ----------------------------------------------------------------------- */
+#define JD_F32   0                    /* IEEE binary32                                                */
+#define JD_BF16  1                    /* bfloat16, 2 bytes                                            */
+
+#define JD_W_VD  0                    /* W_lm stored [V][d]: row v = vocabulary entry v (checkpoint)  */
+#define JD_W_DV  1                    /* W_lm stored [d][V]                                           */
+
+#define JD_DRAFT_LOGITS 0             /* draft tensor = fp32 logits; q = softmax at temperature 1     */
+#define JD_DRAFT_PROBS  1             /* draft tensor = the probability vectors q_i themselves        */
+
+#define JD_MODE_JUDGE    0            /* z = z_stand OR z_judge (Sec. 4.1)                            */
+#define JD_MODE_STANDARD 1            /* z = z_stand (plain speculative sampling, Eq. 4)              */
+
+/* per-sequence status bits written to d_status */
+#define JD_STATUS_BAD_TOKEN     1u    /* a draft token id outside [0,V): that slot is rejected        */
+#define JD_STATUS_NAN           2u    /* NaN met in target logits, a draft row or a judge logit       */
+#define JD_STATUS_ZERO_RESIDUAL 4u    /* max(0,p-q) had no mass; next_token was drawn from p instead  */
+
+/* kernels whose durations jd_verify_profile_end() reports */
+#define JD_K_LMHEAD    0              /* LM-head contraction + per-tile softmax partials              */
+#define JD_K_DRAFTSTAT 1              /* draft-logit row statistics                                   */
+#define JD_K_ACCEPT    2              /* combine, judge, accept tests, ballot, accepted prefix        */
+#define JD_K_SAMPLER   3              /* residual / bonus inverse-CDF sampler (both passes)           */
+#define JD_NUM_KERNELS 4
+
+typedef struct jd_verify_ctx jd_verify_ctx;   /* opaque, owned by the library */
+
+typedef struct {
+  int32_t d, V;                 /* hidden size, vocabulary size                                       */
+  int32_t max_B, max_M;         /* workspace is sized for these; 1 <= max_M <= 63                     */
+  int32_t w_dtype, emb_dtype;   /* JD_F32 | JD_BF16; must be equal (w_judge has the same type)        */
+  int32_t w_layout;             /* JD_W_VD | JD_W_DV                                                  */
+  int32_t draft_kind;           /* JD_DRAFT_LOGITS | JD_DRAFT_PROBS                                   */
+  int32_t mode;                 /* JD_MODE_JUDGE | JD_MODE_STANDARD                                   */
+  float   temperature;          /* target softmax temperature T > 0                                   */
+  float   delta;                /* judge threshold in [0.5, 1]; 1 never accepts (reduces to Eq. 4)    */
+  float   judge_bias;           /* scalar added to w_judge . e                                        */
+  int32_t device;               /* HIP device ordinal                                                 */
+} jd_verify_config;
+
+typedef struct {                /* device pointers; the first three are required, NULL skips the rest */
+  int32_t*  d_accept_len;       /* [B]        m*: accepted draft tokens, 0..M                         */
+  int32_t*  d_next_token;       /* [B]        replacement (m* < M) or bonus (m* == M) token           */
+  uint32_t* d_status;           /* [B]        JD_STATUS_* bits                                        */
+  uint8_t*  d_z_stand;          /* [B, M]     per-slot standard test, not prefix-conditioned          */
+  uint8_t*  d_z_judge;          /* [B, M]     per-slot judge test                                     */
+  float*    d_p_at_draft;       /* [B, M]     p_{j+1}[c_{j+1}]                                        */
+  float*    d_q_at_draft;       /* [B, M]     q_{j+1}[c_{j+1}]                                        */
+  float*    d_judge_logit;      /* [B, M]     w_judge . e[b, j+1] + bias                              */
+  float*    d_row_max;          /* [B, M+1]   max_v L[b,r,v]                                          */
+  float*    d_row_sumexp;       /* [B, M+1]   sum_v exp(L[b,r,v] - max)                               */
+  float*    d_probs;            /* [B, M+1, V] full softmax (debug / parity; costs an extra pass)     */
+} jd_verify_outputs;
+
+/*
+ * Create a context (Sec. 3.1 / 4.1 fix the operands: W_lm, f_judge, delta).
+ * Validates cfg, selects the device, allocates the workspace (fp32 logits
+ * [max_B*(max_M+1), V], reduction partials) and, for bf16 weights, builds a private
+ * copy of W_lm re-tiled into MFMA operand order (one extra W_lm-sized allocation,
+ * one-time cost).  d_W_lm and d_w_judge must stay valid and unchanged until destroy.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_DTYPE (checked before any HIP call), OOM, HIP.
+ * On error *out_ctx is set to NULL.
+ */
+int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void* d_w_judge,
+                     jd_verify_ctx** out_ctx);
+
+/*
+ * Verify one batch (steps 1-7 above).  1 <= B <= max_B, 1 <= M <= max_M.
+ *   d_emb          [B, M+1, d]   LM-head input, emb_dtype
+ *   d_emb_judge    [B, M+1, d]   judge input (the paper's judge reads the embedding before the
+ *                                final RMS norm, Sec. 4.1); NULL means use d_emb.  Row 0 is unused.
+ *   d_draft_tokens [B, M]        int32 ids in [0, V)
+ *   d_draft        [B, draft_rows, V] fp32 logits or probabilities (per draft_kind)
+ *   draft_rows     M or M+1 (a trailing row is ignored)
+ *   d_uniforms     [B, M+1]      fp32 in [0,1): M accept draws eps, then the sampler draw
+ *   out            struct of device output pointers (see above)
+ *   hip_stream     hipStream_t to enqueue on (NULL = the default stream)
+ * Never allocates, never synchronises, never reads tensor contents on the host.
+ * Errors: INVALID_ARG (NULL ctx / required pointer), SHAPE, HIP.
+ */
+int jd_verify_run(jd_verify_ctx* ctx, int32_t B, int32_t M,
+                  const void* d_emb, const void* d_emb_judge,
+                  const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
+                  const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream);
+
+/* Free the workspace and the context.  destroy(NULL) is a no-op returning JD_OK.
+ * Caller memory is never freed. */
+int jd_verify_destroy(jd_verify_ctx* ctx);
+
+/* Static, NUL-terminated description of an error code. */
+const char* jd_verify_strerror(int code);
+
+/*
+ * Per-kernel timing with HIP events on the stream passed to jd_verify_run.
+ * profile_begin arms the context: each of the next max_calls runs records an event
+ * before and after every kernel group.  profile_end synchronises on those events,
+ * writes the mean duration in milliseconds of each JD_K_* group into
+ * avg_ms[JD_NUM_KERNELS] (host pointer) and the number of profiled runs into *n_calls
+ * (host pointer), and disarms the context.  Errors: INVALID_ARG, HIP.
+ */
+int jd_verify_profile_begin(jd_verify_ctx* ctx, int32_t max_calls);
+int jd_verify_profile_end(jd_verify_ctx* ctx, float* avg_ms, int32_t* n_calls);
+
+/*
+ * Introspection (host pointers): bytes of device memory the context allocated
+ * (workspace + re-tiled weights), and the vocabulary stride of the fp32 logits scratch.
+ */
+int jd_verify_workspace_bytes(const jd_verify_ctx* ctx, uint64_t* out_bytes);
+
+/* Host-only validation of a config, exactly the checks create performs before touching
+ * the device.  Lets callers (and CPU-only tests) probe argument errors without a GPU. */
+int jd_verify_validate_config(const jd_verify_config* cfg);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JD_VERIFY_H */

@@ -159,6 +159,14 @@ def inverse_cdf(mass: np.ndarray, u: float):
     return v, margin
 
 
+def mass_neighbours(mass: np.ndarray, v: int):
+    """Nearest tokens below / above v that carry mass (-1 if none).  A sampler draw whose
+    threshold sits within rounding of a CDF edge can only move to one of these."""
+    below = np.nonzero(mass[:v] > 0)[0]
+    above = np.nonzero(mass[v + 1:] > 0)[0]
+    return (int(below[-1]) if below.size else -1), (int(above[0]) + v + 1 if above.size else -1)
+
+
 # --------------------------------------------------------------------------- main entry
 
 def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
@@ -198,6 +206,7 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
         "row_max": np.zeros((nb, M + 1)), "row_sumexp": np.zeros((nb, M + 1)),
         "accept_margin": np.full((nb, M), np.inf), "judge_margin": np.full((nb, M), np.inf),
         "sampler_margin": np.zeros(nb),
+        "next_below": np.full(nb, -1, np.int32), "next_above": np.full(nb, -1, np.int32),
     }
     if return_probs:
         out["probs"] = np.zeros((nb, M + 1, V))
@@ -240,7 +249,7 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
         m = accepted_prefix(z)                                     # step 6
         if m < M:                                                  # step 7
             mass = residual(P[m], Q[m])
-            if not (np.sum(mass) > 0):
+            if np.sum(mass) == 0:
                 status |= STATUS_ZERO_RESIDUAL
                 mass = P[m]
         else:
@@ -249,6 +258,7 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
         out["accept_len"][i], out["next_token"][i], out["status"][i] = m, tok, status
         out["row_max"][i], out["row_sumexp"][i] = rmax, rsum
         out["sampler_margin"][i] = smargin
+        out["next_below"][i], out["next_above"][i] = mass_neighbours(mass, tok)
         if return_probs:
             out["probs"][i] = P
     return out

@@ -1,0 +1,214 @@
+"""ctypes binding of libjdverify.so (argument marshalling only).
+
+Function names mirror the C ABI in include/jd_verify.h.  Every step of the
+verification path runs inside the HIP library; this module only hands over device
+pointers taken from torch tensors.  There is no CPU fallback: if the shared library
+is missing, importing the entry points raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libjdverify.so")
+
+JD_OK = 0
+JD_ERR_INVALID_ARG, JD_ERR_SHAPE, JD_ERR_UNSUPPORTED_DTYPE, JD_ERR_OOM, JD_ERR_HIP = -1, -2, -3, -4, -5
+JD_F32, JD_BF16 = 0, 1
+JD_W_VD, JD_W_DV = 0, 1
+JD_DRAFT_LOGITS, JD_DRAFT_PROBS = 0, 1
+JD_MODE_JUDGE, JD_MODE_STANDARD = 0, 1
+JD_STATUS_BAD_TOKEN, JD_STATUS_NAN, JD_STATUS_ZERO_RESIDUAL = 1, 2, 4
+JD_K_LMHEAD, JD_K_DRAFTSTAT, JD_K_ACCEPT, JD_K_SAMPLER, JD_NUM_KERNELS = 0, 1, 2, 3, 4
+KERNEL_NAMES = ("lmhead", "draftstat", "accept", "sampler")
+
+EXPORTED_SYMBOLS = (
+    "jd_verify_create", "jd_verify_run", "jd_verify_destroy", "jd_verify_strerror",
+    "jd_verify_profile_begin", "jd_verify_profile_end", "jd_verify_workspace_bytes",
+    "jd_verify_validate_config",
+)
+
+
+class jd_verify_config(ctypes.Structure):
+    _fields_ = [
+        ("d", ctypes.c_int32), ("V", ctypes.c_int32),
+        ("max_B", ctypes.c_int32), ("max_M", ctypes.c_int32),
+        ("w_dtype", ctypes.c_int32), ("emb_dtype", ctypes.c_int32),
+        ("w_layout", ctypes.c_int32), ("draft_kind", ctypes.c_int32), ("mode", ctypes.c_int32),
+        ("temperature", ctypes.c_float), ("delta", ctypes.c_float), ("judge_bias", ctypes.c_float),
+        ("device", ctypes.c_int32),
+    ]
+
+
+class jd_verify_outputs(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "d_accept_len", "d_next_token", "d_status", "d_z_stand", "d_z_judge", "d_p_at_draft",
+        "d_q_at_draft", "d_judge_logit", "d_row_max", "d_row_sumexp", "d_probs")]
+
+
+class JDError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libjdverify.so; fail loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2501_19309_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    lib.jd_verify_create.argtypes = [ctypes.POINTER(jd_verify_config), vp, vp, ctypes.POINTER(vp)]
+    lib.jd_verify_create.restype = ctypes.c_int
+    lib.jd_verify_run.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, vp, ctypes.POINTER(jd_verify_outputs), vp]
+    lib.jd_verify_run.restype = ctypes.c_int
+    lib.jd_verify_destroy.argtypes = [vp]
+    lib.jd_verify_destroy.restype = ctypes.c_int
+    lib.jd_verify_strerror.argtypes = [ctypes.c_int]
+    lib.jd_verify_strerror.restype = ctypes.c_char_p
+    lib.jd_verify_profile_begin.argtypes = [vp, i32]
+    lib.jd_verify_profile_begin.restype = ctypes.c_int
+    lib.jd_verify_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+    lib.jd_verify_profile_end.restype = ctypes.c_int
+    lib.jd_verify_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
+    lib.jd_verify_workspace_bytes.restype = ctypes.c_int
+    lib.jd_verify_validate_config.argtypes = [ctypes.POINTER(jd_verify_config)]
+    lib.jd_verify_validate_config.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().jd_verify_strerror(int(code)).decode()
+
+
+def make_config(d, V, max_B, max_M, *, w_dtype=JD_BF16, emb_dtype=None, w_layout=JD_W_VD,
+                draft_kind=JD_DRAFT_LOGITS, mode=JD_MODE_JUDGE, temperature=1.0, delta=0.5,
+                judge_bias=0.0, device=0) -> jd_verify_config:
+    return jd_verify_config(d, V, max_B, max_M, w_dtype, w_dtype if emb_dtype is None else emb_dtype,
+                            w_layout, draft_kind, mode, temperature, delta, judge_bias, device)
+
+
+def jd_verify_validate_config(cfg: jd_verify_config) -> int:
+    return load_library().jd_verify_validate_config(ctypes.byref(cfg))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+@dataclass
+class VerifyOutputs:
+    """Device tensors written by one jd_verify_run call."""
+    accept_len: "torch.Tensor"
+    next_token: "torch.Tensor"
+    status: "torch.Tensor"
+    z_stand: "torch.Tensor"
+    z_judge: "torch.Tensor"
+    p_at_draft: "torch.Tensor"
+    q_at_draft: "torch.Tensor"
+    judge_logit: "torch.Tensor"
+    row_max: "torch.Tensor"
+    row_sumexp: "torch.Tensor"
+    probs: Optional["torch.Tensor"] = None
+
+    def to_numpy(self) -> Dict[str, "numpy.ndarray"]:
+        out = {}
+        for k, v in self.__dict__.items():
+            if v is not None:
+                out[k] = v.detach().cpu().numpy()
+        return out
+
+
+class JDVerify:
+    """Owner of one jd_verify_ctx.  Tensors are torch CUDA(HIP) tensors."""
+
+    def __init__(self, cfg: jd_verify_config, W_lm, w_judge):
+        import torch  # device memory and streams only
+
+        self._torch = torch
+        self.lib = load_library()
+        self.cfg = cfg
+        self._keep = (W_lm, w_judge)  # borrowed by the library until destroy
+        handle = ctypes.c_void_p()
+        rc = self.lib.jd_verify_create(ctypes.byref(cfg), _ptr(W_lm), _ptr(w_judge), ctypes.byref(handle))
+        if rc != JD_OK:
+            raise JDError(rc, "jd_verify_create")
+        self.handle = handle
+
+    # -- jd_verify_run
+    def alloc_outputs(self, B: int, M: int, want_probs: bool = False) -> VerifyOutputs:
+        t = self._torch
+        dev = t.device("cuda", self.cfg.device)
+        f = lambda *s: t.zeros(*s, dtype=t.float32, device=dev)
+        return VerifyOutputs(
+            accept_len=t.zeros(B, dtype=t.int32, device=dev), next_token=t.zeros(B, dtype=t.int32, device=dev),
+            status=t.zeros(B, dtype=t.int32, device=dev),
+            z_stand=t.zeros(B, M, dtype=t.uint8, device=dev), z_judge=t.zeros(B, M, dtype=t.uint8, device=dev),
+            p_at_draft=f(B, M), q_at_draft=f(B, M), judge_logit=f(B, M), row_max=f(B, M + 1),
+            row_sumexp=f(B, M + 1), probs=f(B, M + 1, self.cfg.V) if want_probs else None)
+
+    def run(self, emb, draft_tokens, draft, uniforms, out: VerifyOutputs, *, emb_judge=None, stream=None) -> None:
+        B, Mp1 = emb.shape[0], emb.shape[1]
+        M = Mp1 - 1
+        o = jd_verify_outputs(*[_ptr(getattr(out, n)) for n in (
+            "accept_len", "next_token", "status", "z_stand", "z_judge", "p_at_draft", "q_at_draft",
+            "judge_logit", "row_max", "row_sumexp", "probs")])
+        if stream is None:
+            stream = self._torch.cuda.current_stream().cuda_stream
+        rc = self.lib.jd_verify_run(self.handle, B, M, _ptr(emb), _ptr(emb_judge), _ptr(draft_tokens), _ptr(draft),
+                                    draft.shape[1], _ptr(uniforms), ctypes.byref(o), ctypes.c_void_p(stream))
+        if rc != JD_OK:
+            raise JDError(rc, "jd_verify_run")
+
+    def run_raw(self, B, M, emb, emb_judge, draft_tokens, draft, draft_rows, uniforms, outputs: jd_verify_outputs,
+                stream=0) -> int:
+        """Direct call returning the error code (used by the error-path tests)."""
+        return self.lib.jd_verify_run(self.handle, B, M, emb, emb_judge, draft_tokens, draft, draft_rows, uniforms,
+                                      ctypes.byref(outputs) if outputs is not None else None, ctypes.c_void_p(stream))
+
+    # -- profiling
+    def profile_begin(self, max_calls: int) -> None:
+        rc = self.lib.jd_verify_profile_begin(self.handle, max_calls)
+        if rc != JD_OK:
+            raise JDError(rc, "jd_verify_profile_begin")
+
+    def profile_end(self):
+        ms = (ctypes.c_float * JD_NUM_KERNELS)()
+        n = ctypes.c_int32()
+        rc = self.lib.jd_verify_profile_end(self.handle, ms, ctypes.byref(n))
+        if rc != JD_OK:
+            raise JDError(rc, "jd_verify_profile_end")
+        return {KERNEL_NAMES[i]: float(ms[i]) for i in range(JD_NUM_KERNELS)}, int(n.value)
+
+    def workspace_bytes(self) -> int:
+        v = ctypes.c_uint64()
+        rc = self.lib.jd_verify_workspace_bytes(self.handle, ctypes.byref(v))
+        if rc != JD_OK:
+            raise JDError(rc, "jd_verify_workspace_bytes")
+        return int(v.value)
+
+    # -- jd_verify_destroy
+    def destroy(self) -> None:
+        if getattr(self, "handle", None) is not None:
+            self.lib.jd_verify_destroy(self.handle)
+            self.handle = None
+            self._keep = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

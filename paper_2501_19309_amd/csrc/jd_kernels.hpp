@@ -1,0 +1,120 @@
+// Internal launcher interface between the C-ABI dispatcher and the gfx950 kernels.
+// Not part of the public boundary (that is include/jd_verify.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace jd {
+
+// ---- packed W_lm geometry --------------------------------------------------------
+// The bf16 LM-head weight is re-tiled once, at context creation, into MFMA operand
+// order for v_mfma_f32_16x16x32_bf16:
+//
+//   Wp[vg][ks][sub][lane][8]      (bf16)
+//
+//   vg   : vocabulary group of 64 consecutive rows            (V padded to 64)
+//   ks   : K step of 32 consecutive hidden indices            (d padded to kKChunk)
+//   sub  : 16-row block inside the group, 0..3
+//   lane : 0..63; lane holds row  vg*64 + sub*16 + lane%16,
+//                 hidden indices  ks*32 + (lane/16)*8 + 0..7
+//
+// One (vg, ks, sub) fragment is 1 KiB and is exactly what one wavefront loads with a
+// single 128-bit-per-lane instruction; a wavefront that owns a group streams
+// 4 KiB per K step from one contiguous region.
+constexpr int kVocabGroup = 64;
+constexpr int kKStep = 32;
+constexpr int kKChunk = 256;                 // hidden indices per LDS-staged X chunk
+constexpr int kStepsPerChunk = kKChunk / kKStep;
+constexpr int kGroupAlloc = 8;               // Wp is allocated for a multiple of this many groups
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+struct Geometry {
+  int d, V;
+  int dpad;      // d rounded up to kKChunk
+  int Vpad;      // V rounded up to kVocabGroup; also the row stride of the fp32 logits scratch
+  int nVG;       // Vpad / 64
+  int nVGalloc;  // nVG rounded up to kGroupAlloc (zero-filled tail groups)
+  size_t packed_bytes() const { return (size_t)nVGalloc * kVocabGroup * (size_t)dpad * 2; }
+};
+
+inline Geometry make_geometry(int d, int V) {
+  Geometry g;
+  g.d = d; g.V = V;
+  g.dpad = round_up(d, kKChunk);
+  g.Vpad = round_up(V, kVocabGroup);
+  g.nVG = g.Vpad / kVocabGroup;
+  g.nVGalloc = round_up(g.nVG, kGroupAlloc);
+  return g;
+}
+
+// ---- launchers (all asynchronous on `st`) -----------------------------------------
+
+// Re-tile bf16 W_lm ([V][d] if layout==0, [d][V] if layout==1) into Wp, zero padded.
+hipError_t launch_pack_w(const void* W, int layout, const Geometry& g, void* Wp, hipStream_t st);
+
+// Small-row regime LM head (R <= 64): streams Wp once, MFMA, writes fp32 logits
+// L[r*Lld + v] = (x_r . w_v) * invT for r < R, v < Vpad, and one softmax partial
+// (max, sum exp) per (row, vocabulary group): part[r*nVG + vg].
+hipError_t launch_lmhead_skinny(const void* Wp, const void* X, int R, const Geometry& g, float invT,
+                                float* L, float2* part, int num_cus, hipStream_t st);
+
+// Large-row regime LM head (tiled GEMM); same outputs as the skinny launcher.
+hipError_t launch_lmhead_gemm(const void* Wp, const void* X, int R, const Geometry& g, float invT,
+                              float* L, float2* part, void* Xp_scratch, int num_cus, hipStream_t st);
+
+// fp32 LM head (any layout), plain FMA; writes logits only.
+hipError_t launch_lmhead_f32(const float* W, int layout, const float* X, int R, int d, int V, float invT,
+                             float* L, int Lld, hipStream_t st);
+
+// Row statistics of an fp32 matrix: for each of nRows rows (row i lives at
+// base + (i / rowsUsed) * seqStride + (i % rowsUsed) * rowStride, V columns) and each
+// of nSplit column ranges, part[i*nSplit + s] = (max, sum exp(x - max)).
+hipError_t launch_rowstats(const float* base, int nRows, int rowsUsed, size_t seqStride, size_t rowStride,
+                           int V, int nSplit, float2* part, hipStream_t st);
+
+struct AcceptArgs {
+  int B, M, d, V;
+  int emb_is_bf16;
+  int draft_is_logits, mode_judge;
+  float judge_threshold;   // logit(delta), +inf for delta == 1
+  float judge_bias;
+  const float* L; int Lld;             // target logits scratch
+  const float2* tpart; int nPartT;     // target softmax partials [R][nPartT]
+  const float2* dpart; int nPartD;     // draft partials [B*M][nPartD] (logits kind only)
+  const float* D; int draft_rows;      // draft tensor [B][draft_rows][V]
+  const int32_t* tokens;               // [B][M]
+  const float* uniforms;               // [B][M+1]
+  const void* emb_judge;               // [B][M+1][d]
+  const void* w_judge;                 // [d]
+  // workspace written for the sampler
+  float* t_max; float* t_sum;          // [R]
+  float* q_max; float* q_sum;          // [B*M]
+  float* g;                            // [B*M] judge logits
+  // outputs
+  int32_t* accept_len; uint32_t* status;
+  uint8_t* z_stand; uint8_t* z_judge;
+  float* p_at; float* q_at; float* judge_logit; float* row_max; float* row_sumexp;
+};
+hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);
+
+struct SamplerArgs {
+  int B, M, V;
+  int draft_is_logits;
+  const float* L; int Lld;
+  const float* D; int draft_rows;
+  const float* uniforms;
+  const float* t_max; const float* t_sum; const float* q_max; const float* q_sum;
+  const int32_t* accept_len;
+  double* chunk_mass; int nChunk;      // [B][nChunk]
+  int32_t* next_token; uint32_t* status;
+};
+constexpr int kSamplerChunk = 1024;     // tokens per sampler chunk
+hipError_t launch_sampler(const SamplerArgs& a, hipStream_t st);
+
+// probs[r*V + v] = exp(L[r*Lld + v] - t_max[r]) / t_sum[r]
+hipError_t launch_probs(const float* L, int Lld, const float* t_max, const float* t_sum, int R, int V,
+                        float* probs, hipStream_t st);
+
+}  // namespace jd

@@ -1,0 +1,273 @@
+// C-ABI dispatcher of the verification head: argument validation, workspace, kernel
+// selection by row count, optional per-kernel HIP-event timing.  See include/jd_verify.h
+// for the contract of every entry point.
+#include "../../include/jd_verify.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+#include "jd_kernels.hpp"
+
+using namespace jd;
+
+struct jd_verify_ctx {
+  jd_verify_config cfg;
+  Geometry geo;
+  int num_cus;
+  const void* W;
+  const void* wj;
+  void* Wp;             // re-tiled bf16 weights (bf16 path only)
+  float* L;             // [maxR][Vpad] fp32 logits
+  float2* tpart;        // [maxR][nPartT]
+  float2* dpart;        // [max_B*max_M][nPartD]
+  float* t_max; float* t_sum; float* q_max; float* q_sum; float* g;
+  double* chunk_mass;   // [max_B][nChunk]
+  void* Xp;             // packed embeddings for the GEMM regime
+  int nPartT, nPartD, nChunk;
+  uint64_t bytes;
+  float judge_threshold;
+  // profiling
+  bool prof_on;
+  int prof_max, prof_n;
+  std::vector<hipEvent_t> ev;  // (JD_NUM_KERNELS + 1) events per profiled call
+};
+
+static const int kDraftSplits = 16;   // column ranges per draft row in the statistics pass
+static const int kF32Splits = 8;      // same for target logits on the fp32 path
+
+extern "C" const char* jd_verify_strerror(int code) {
+  switch (code) {
+    case JD_OK: return "ok";
+    case JD_ERR_INVALID_ARG: return "invalid argument";
+    case JD_ERR_SHAPE: return "shape out of range";
+    case JD_ERR_UNSUPPORTED_DTYPE: return "unsupported dtype combination";
+    case JD_ERR_OOM: return "out of device memory";
+    case JD_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
+  if (!c) return JD_ERR_INVALID_ARG;
+  if (c->w_dtype != JD_F32 && c->w_dtype != JD_BF16) return JD_ERR_INVALID_ARG;
+  if (c->emb_dtype != JD_F32 && c->emb_dtype != JD_BF16) return JD_ERR_INVALID_ARG;
+  if (c->w_layout != JD_W_VD && c->w_layout != JD_W_DV) return JD_ERR_INVALID_ARG;
+  if (c->draft_kind != JD_DRAFT_LOGITS && c->draft_kind != JD_DRAFT_PROBS) return JD_ERR_INVALID_ARG;
+  if (c->mode != JD_MODE_JUDGE && c->mode != JD_MODE_STANDARD) return JD_ERR_INVALID_ARG;
+  if (!(c->temperature > 0.f) || !std::isfinite(c->temperature)) return JD_ERR_INVALID_ARG;
+  if (!(c->delta >= 0.5f && c->delta <= 1.0f)) return JD_ERR_INVALID_ARG;
+  if (!std::isfinite(c->judge_bias)) return JD_ERR_INVALID_ARG;
+  if (c->device < 0) return JD_ERR_INVALID_ARG;
+  if (c->d <= 0 || c->V <= 0 || c->max_B <= 0 || c->max_M <= 0) return JD_ERR_SHAPE;
+  if (c->max_M > 63) return JD_ERR_SHAPE;               // one wave64 ballot covers a sequence
+  if (c->V > (1 << 30) || c->d > (1 << 20)) return JD_ERR_SHAPE;
+  if ((int64_t)c->max_B * (c->max_M + 1) > (1 << 20)) return JD_ERR_SHAPE;
+  if (c->w_dtype != c->emb_dtype) return JD_ERR_UNSUPPORTED_DTYPE;
+  if (c->w_dtype == JD_BF16 && (c->d % 8) != 0) return JD_ERR_SHAPE;  // 128-bit operand loads
+  return JD_OK;
+}
+
+static void free_ctx(jd_verify_ctx* c) {
+  if (!c) return;
+  void* ptrs[] = {c->Wp, c->L, c->tpart, c->dpart, c->t_max, c->t_sum, c->q_max, c->q_sum, c->g, c->chunk_mass, c->Xp};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  delete c;
+}
+
+template <typename T>
+static int dev_alloc(jd_verify_ctx* c, T** p, size_t n) {
+  const size_t bytes = (n ? n : 1) * sizeof(T);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes);
+  if (e != hipSuccess) {
+    *p = nullptr;
+    (void)hipGetLastError();
+    return e == hipErrorOutOfMemory ? JD_ERR_OOM : JD_ERR_HIP;
+  }
+  c->bytes += bytes;
+  return JD_OK;
+}
+
+extern "C" int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void* d_w_judge,
+                                jd_verify_ctx** out_ctx) {
+  if (!out_ctx) return JD_ERR_INVALID_ARG;
+  *out_ctx = nullptr;
+  int rc = jd_verify_validate_config(cfg);
+  if (rc != JD_OK) return rc;
+  if (!d_W_lm || !d_w_judge) return JD_ERR_INVALID_ARG;
+
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device >= ndev) { (void)hipGetLastError(); return JD_ERR_HIP; }
+  if (hipSetDevice(cfg->device) != hipSuccess) return JD_ERR_HIP;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) return JD_ERR_HIP;
+
+  jd_verify_ctx* c = new (std::nothrow) jd_verify_ctx();
+  if (!c) return JD_ERR_OOM;
+  c->cfg = *cfg;
+  c->geo = make_geometry(cfg->d, cfg->V);
+  c->num_cus = prop.multiProcessorCount;
+  c->W = d_W_lm; c->wj = d_w_judge;
+  c->judge_threshold = (cfg->delta >= 1.0f) ? INFINITY : std::log(cfg->delta / (1.0f - cfg->delta));
+  c->prof_on = false; c->prof_max = c->prof_n = 0;
+  c->bytes = 0;
+
+  const size_t maxR = (size_t)cfg->max_B * (cfg->max_M + 1);
+  const size_t maxS = (size_t)cfg->max_B * cfg->max_M;
+  const bool bf16 = cfg->w_dtype == JD_BF16;
+  c->nPartT = bf16 ? c->geo.nVG : kF32Splits;
+  c->nPartD = kDraftSplits;
+  c->nChunk = (cfg->V + kSamplerChunk - 1) / kSamplerChunk;
+
+  rc = dev_alloc(c, &c->L, maxR * (size_t)c->geo.Vpad);
+  if (rc == JD_OK) rc = dev_alloc(c, &c->tpart, maxR * (size_t)c->nPartT);
+  if (rc == JD_OK) rc = dev_alloc(c, &c->dpart, maxS * (size_t)c->nPartD);
+  if (rc == JD_OK) rc = dev_alloc(c, &c->t_max, maxR);
+  if (rc == JD_OK) rc = dev_alloc(c, &c->t_sum, maxR);
+  if (rc == JD_OK) rc = dev_alloc(c, &c->q_max, maxS);
+  if (rc == JD_OK) rc = dev_alloc(c, &c->q_sum, maxS);
+  if (rc == JD_OK) rc = dev_alloc(c, &c->g, maxS);
+  if (rc == JD_OK) rc = dev_alloc(c, &c->chunk_mass, (size_t)cfg->max_B * c->nChunk);
+  if (rc == JD_OK && bf16) {
+    uint8_t* wp = nullptr;
+    rc = dev_alloc(c, &wp, c->geo.packed_bytes());
+    c->Wp = wp;
+    if (rc == JD_OK) {
+      if (launch_pack_w(d_W_lm, cfg->w_layout, c->geo, c->Wp, nullptr) != hipSuccess ||
+          hipDeviceSynchronize() != hipSuccess)
+        rc = JD_ERR_HIP;
+    }
+  }
+  if (rc != JD_OK) { free_ctx(c); return rc; }
+  *out_ctx = c;
+  return JD_OK;
+}
+
+extern "C" int jd_verify_destroy(jd_verify_ctx* ctx) {
+  if (!ctx) return JD_OK;
+  (void)hipSetDevice(ctx->cfg.device);
+  (void)hipDeviceSynchronize();
+  free_ctx(ctx);
+  return JD_OK;
+}
+
+extern "C" int jd_verify_workspace_bytes(const jd_verify_ctx* ctx, uint64_t* out_bytes) {
+  if (!ctx || !out_bytes) return JD_ERR_INVALID_ARG;
+  *out_bytes = ctx->bytes;
+  return JD_OK;
+}
+
+extern "C" int jd_verify_profile_begin(jd_verify_ctx* ctx, int32_t max_calls) {
+  if (!ctx || max_calls <= 0 || max_calls > 4096) return JD_ERR_INVALID_ARG;
+  const size_t need = (size_t)max_calls * (JD_NUM_KERNELS + 1);
+  while (ctx->ev.size() < need) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return JD_ERR_HIP;
+    ctx->ev.push_back(e);
+  }
+  ctx->prof_on = true; ctx->prof_max = max_calls; ctx->prof_n = 0;
+  return JD_OK;
+}
+
+extern "C" int jd_verify_profile_end(jd_verify_ctx* ctx, float* avg_ms, int32_t* n_calls) {
+  if (!ctx || !avg_ms || !n_calls) return JD_ERR_INVALID_ARG;
+  ctx->prof_on = false;
+  double sum[JD_NUM_KERNELS] = {0, 0, 0, 0};
+  for (int i = 0; i < ctx->prof_n; ++i) {
+    hipEvent_t* e = &ctx->ev[(size_t)i * (JD_NUM_KERNELS + 1)];
+    if (hipEventSynchronize(e[JD_NUM_KERNELS]) != hipSuccess) return JD_ERR_HIP;
+    for (int k = 0; k < JD_NUM_KERNELS; ++k) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, e[k], e[k + 1]) != hipSuccess) return JD_ERR_HIP;
+      sum[k] += ms;
+    }
+  }
+  for (int k = 0; k < JD_NUM_KERNELS; ++k) avg_ms[k] = ctx->prof_n ? (float)(sum[k] / ctx->prof_n) : 0.f;
+  *n_calls = ctx->prof_n;
+  ctx->prof_n = 0;
+  return JD_OK;
+}
+
+#define JD_HIP(expr) do { if ((expr) != hipSuccess) return JD_ERR_HIP; } while (0)
+
+extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, const void* d_emb_judge,
+                             const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
+                             const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream) {
+  if (!c || !d_emb || !d_draft_tokens || !d_draft || !d_uniforms || !out) return JD_ERR_INVALID_ARG;
+  if (!out->d_accept_len || !out->d_next_token || !out->d_status) return JD_ERR_INVALID_ARG;
+  if (B < 1 || M < 1 || B > c->cfg.max_B || M > c->cfg.max_M) return JD_ERR_SHAPE;
+  if (draft_rows != M && draft_rows != M + 1) return JD_ERR_SHAPE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const jd_verify_config& cfg = c->cfg;
+  const Geometry& g = c->geo;
+  const int R = B * (M + 1);
+  const float invT = 1.0f / cfg.temperature;
+  const bool bf16 = cfg.w_dtype == JD_BF16;
+  const bool logits = cfg.draft_kind == JD_DRAFT_LOGITS;
+
+  hipEvent_t* ev = nullptr;
+  if (c->prof_on && c->prof_n < c->prof_max) ev = &c->ev[(size_t)(c->prof_n++) * (JD_NUM_KERNELS + 1)];
+  if (ev) JD_HIP(hipEventRecord(ev[0], st));
+
+  // step 1: LM head (+ first softmax pass)
+  if (bf16) {
+    if (R <= 64) {
+      JD_HIP(launch_lmhead_skinny(c->Wp, d_emb, R, g, invT, c->L, c->tpart, c->num_cus, st));
+    } else {
+      // row blocks of 64 through the small-row kernel
+      for (int r0 = 0; r0 < R; r0 += 64) {
+        const int rows = (R - r0 < 64) ? (R - r0) : 64;
+        JD_HIP(launch_lmhead_skinny(c->Wp, static_cast<const uint16_t*>(d_emb) + (size_t)r0 * cfg.d, rows, g, invT,
+                                    c->L + (size_t)r0 * g.Vpad, c->tpart + (size_t)r0 * c->nPartT, c->num_cus, st));
+      }
+    }
+  } else {
+    JD_HIP(launch_lmhead_f32(static_cast<const float*>(c->W), cfg.w_layout, static_cast<const float*>(d_emb), R,
+                             cfg.d, cfg.V, invT, c->L, g.Vpad, st));
+    JD_HIP(launch_rowstats(c->L, R, 1, (size_t)g.Vpad, 0, cfg.V, c->nPartT, c->tpart, st));
+  }
+  if (ev) JD_HIP(hipEventRecord(ev[1], st));
+
+  // step 2: draft row statistics (softmax of the draft logits, first pass)
+  if (logits)
+    JD_HIP(launch_rowstats(d_draft, B * M, M, (size_t)draft_rows * cfg.V, (size_t)cfg.V, cfg.V, c->nPartD,
+                           c->dpart, st));
+  if (ev) JD_HIP(hipEventRecord(ev[2], st));
+
+  // steps 3-6: accept tests, judge, OR, accepted prefix
+  AcceptArgs a;
+  a.B = B; a.M = M; a.d = cfg.d; a.V = cfg.V;
+  a.emb_is_bf16 = cfg.emb_dtype == JD_BF16;
+  a.draft_is_logits = logits; a.mode_judge = cfg.mode == JD_MODE_JUDGE;
+  a.judge_threshold = c->judge_threshold; a.judge_bias = cfg.judge_bias;
+  a.L = c->L; a.Lld = g.Vpad;
+  a.tpart = c->tpart; a.nPartT = c->nPartT;
+  a.dpart = c->dpart; a.nPartD = c->nPartD;
+  a.D = d_draft; a.draft_rows = draft_rows;
+  a.tokens = d_draft_tokens; a.uniforms = d_uniforms;
+  a.emb_judge = d_emb_judge ? d_emb_judge : d_emb; a.w_judge = c->wj;
+  a.t_max = c->t_max; a.t_sum = c->t_sum; a.q_max = c->q_max; a.q_sum = c->q_sum; a.g = c->g;
+  a.accept_len = out->d_accept_len; a.status = out->d_status;
+  a.z_stand = out->d_z_stand; a.z_judge = out->d_z_judge;
+  a.p_at = out->d_p_at_draft; a.q_at = out->d_q_at_draft; a.judge_logit = out->d_judge_logit;
+  a.row_max = out->d_row_max; a.row_sumexp = out->d_row_sumexp;
+  JD_HIP(launch_accept(a, st));
+  if (ev) JD_HIP(hipEventRecord(ev[3], st));
+
+  // step 7: replacement / bonus token
+  SamplerArgs s;
+  s.B = B; s.M = M; s.V = cfg.V; s.draft_is_logits = logits;
+  s.L = c->L; s.Lld = g.Vpad; s.D = d_draft; s.draft_rows = draft_rows; s.uniforms = d_uniforms;
+  s.t_max = c->t_max; s.t_sum = c->t_sum; s.q_max = c->q_max; s.q_sum = c->q_sum;
+  s.accept_len = out->d_accept_len;
+  s.chunk_mass = c->chunk_mass; s.nChunk = c->nChunk;
+  s.next_token = out->d_next_token; s.status = out->d_status;
+  JD_HIP(launch_sampler(s, st));
+  if (ev) JD_HIP(hipEventRecord(ev[4], st));
+
+  if (out->d_probs) JD_HIP(launch_probs(c->L, g.Vpad, c->t_max, c->t_sum, R, cfg.V, out->d_probs, st));
+  return JD_OK;
+}

@@ -1,0 +1,441 @@
+// Everything after the LM-head contraction: vocabulary-softmax statistics of the draft
+// tensor, the accept tests, the judge, the mask combination, the accepted prefix and the
+// residual / bonus-token sampler.  All of it is streaming or per-slot work (no MFMA).
+#include "jd_kernels.hpp"
+
+namespace jd {
+
+// Online-softmax state: m = running max, s = sum exp(x - m).
+struct MS { float m, s; };
+
+__device__ __forceinline__ MS ms_combine(MS a, MS b) {
+  const float m = fmaxf(a.m, b.m);
+  if (m == -INFINITY) return MS{m, a.s + b.s};  // both empty (keeps NaN sums visible)
+  MS o;
+  o.m = m;
+  o.s = a.s * __expf(a.m - m) + b.s * __expf(b.m - m);
+  return o;
+}
+
+__device__ __forceinline__ MS ms_wave_reduce(MS v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    MS t;
+    t.m = __shfl_xor(v.m, o);
+    t.s = __shfl_xor(v.s, o);
+    v = ms_combine(v, t);
+  }
+  return v;
+}
+
+// ------------------------------------------------------------------------------- row stats
+
+// First pass of the vocabulary softmax over an fp32 matrix (the draft logits, Sec. 3.1
+// Eq. 3 handed over as logits; also the target logits on the fp32 path).
+// grid = (nRows, nSplit).  Each block reduces one contiguous column range of one row.
+__global__ __launch_bounds__(256) void rowstats_kernel(const float* __restrict__ base, int rowsUsed,
+                                                        size_t seqStride, size_t rowStride, int V, int nSplit,
+                                                        int splitLen, float2* __restrict__ part) {
+  const int row = blockIdx.x, split = blockIdx.y;
+  const float* p = base + (size_t)(row / rowsUsed) * seqStride + (size_t)(row % rowsUsed) * rowStride;
+  const int c0 = split * splitLen;
+  const int c1 = min(V, c0 + splitLen);
+  MS st{-INFINITY, 0.f};
+  const int tid = threadIdx.x;
+  if (((reinterpret_cast<uintptr_t>(p) & 15) == 0)) {  // splitLen is a multiple of 4
+    const int nvec = (c1 > c0) ? (c1 - c0) / 4 : 0;
+    const float4* p4 = reinterpret_cast<const float4*>(p + c0);
+    for (int i = tid; i < nvec; i += 256) {
+      const float4 x = p4[i];
+      const float m4 = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+      if (m4 > st.m) { st.s *= __expf(st.m - m4); st.m = m4; }
+      st.s += __expf(x.x - st.m) + __expf(x.y - st.m) + __expf(x.z - st.m) + __expf(x.w - st.m);
+    }
+    for (int c = c0 + nvec * 4 + tid; c < c1; c += 256) {
+      const float x = p[c];
+      if (x > st.m) { st.s *= __expf(st.m - x); st.m = x; }
+      st.s += __expf(x - st.m);
+    }
+  } else {
+    for (int c = c0 + tid; c < c1; c += 256) {
+      const float x = p[c];
+      if (x > st.m) { st.s *= __expf(st.m - x); st.m = x; }
+      st.s += __expf(x - st.m);
+    }
+  }
+  st = ms_wave_reduce(st);
+  __shared__ MS red[4];
+  if ((tid & 63) == 0) red[tid >> 6] = st;
+  __syncthreads();
+  if (tid == 0) {
+    MS o = ms_combine(ms_combine(red[0], red[1]), ms_combine(red[2], red[3]));
+    part[(size_t)row * nSplit + split] = make_float2(o.m, o.s);
+  }
+}
+
+hipError_t launch_rowstats(const float* base, int nRows, int rowsUsed, size_t seqStride, size_t rowStride, int V,
+                           int nSplit, float2* part, hipStream_t st) {
+  int splitLen = (V + nSplit - 1) / nSplit;
+  splitLen = (splitLen + 3) / 4 * 4;
+  hipLaunchKernelGGL(rowstats_kernel, dim3(nRows, nSplit), dim3(256), 0, st, base, rowsUsed, seqStride, rowStride,
+                     V, nSplit, splitLen, part);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------- accept
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+__device__ __forceinline__ float dot8_bf16(uint4 a, uint4 b, float acc) {
+  acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+  acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+  acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+  acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+  return acc;
+}
+
+__device__ __forceinline__ MS ms_block_reduce(MS st, MS* red /*[4]*/) {
+  st = ms_wave_reduce(st);
+  const int tid = threadIdx.x;
+  if ((tid & 63) == 0) red[tid >> 6] = st;
+  __syncthreads();
+  return ms_combine(ms_combine(red[0], red[1]), ms_combine(red[2], red[3]));
+}
+
+// Second pass of the two-pass vocabulary softmax and the judge head, one workgroup per
+// row so that the work spreads over the chip:
+//   blocks [0, R)        combine the LM-head partials of target row r  -> t_max, t_sum
+//   blocks [R, R+S)      combine the partials of draft row (b, j)      -> q_max, q_sum
+//   blocks [R+S, R+2S)   judge logit g = w_judge . e[b, j+1] + bias    (Sec. 4.1; App. B.1)
+// with R = B*(M+1), S = B*M.
+__global__ __launch_bounds__(256) void reduce_rows_kernel(AcceptArgs a) {
+  __shared__ MS red[4];
+  __shared__ float redf[4];
+  const int tid = threadIdx.x;
+  const int R = a.B * (a.M + 1), S = a.B * a.M;
+  int blk = blockIdx.x;
+  if (blk < R) {
+    const float2* p = a.tpart + (size_t)blk * a.nPartT;
+    MS st{-INFINITY, 0.f};
+    for (int i = tid; i < a.nPartT; i += 256) st = ms_combine(st, MS{p[i].x, p[i].y});
+    st = ms_block_reduce(st, red);
+    if (tid == 0) {
+      a.t_max[blk] = st.m; a.t_sum[blk] = st.s;
+      if (a.row_max) a.row_max[blk] = st.m;
+      if (a.row_sumexp) a.row_sumexp[blk] = st.s;
+    }
+    return;
+  }
+  blk -= R;
+  if (blk < S) {
+    if (!a.draft_is_logits) return;
+    const float2* p = a.dpart + (size_t)blk * a.nPartD;
+    MS st{-INFINITY, 0.f};
+    for (int i = tid; i < a.nPartD; i += 256) st = ms_combine(st, MS{p[i].x, p[i].y});
+    st = ms_block_reduce(st, red);
+    if (tid == 0) { a.q_max[blk] = st.m; a.q_sum[blk] = st.s; }
+    return;
+  }
+  blk -= S;
+  const int b = blk / a.M, j = blk % a.M;
+  const size_t e0 = ((size_t)b * (a.M + 1) + j + 1) * a.d;
+  float acc = 0.f;
+  if (a.emb_is_bf16) {  // d % 8 == 0 and 16-byte aligned rows on this path
+    const uint4* w = reinterpret_cast<const uint4*>(a.w_judge);
+    const uint4* e = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(a.emb_judge) + e0);
+    for (int i = tid; i < a.d / 8; i += 256) acc = dot8_bf16(w[i], e[i], acc);
+  } else {
+    const float* w = reinterpret_cast<const float*>(a.w_judge);
+    const float* e = reinterpret_cast<const float*>(a.emb_judge) + e0;
+    for (int k = tid; k < a.d; k += 256) acc = fmaf(w[k], e[k], acc);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if ((tid & 63) == 0) redf[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) a.g[blk] = (redf[0] + redf[1]) + (redf[2] + redf[3]) + a.judge_bias;
+}
+
+// One wavefront per sequence, lane j = draft slot j: standard test eps*q[c] < p[c] (Eq. 4),
+// judge test g > logit(delta), OR of the two masks (Sec. 4.1), then one wavefront ballot
+// whose trailing ones are the accepted prefix (Eq. 4; App. B.2, Fig. 8).
+__global__ __launch_bounds__(64) void accept_kernel(AcceptArgs a) {
+  const int b = blockIdx.x;
+  const int j = threadIdx.x;
+  const int M = a.M, Mp1 = a.M + 1;
+  bool z = false;
+  uint32_t flags = 0;
+  if (j < M) {
+    const int c = a.tokens[b * M + j];
+    const float g = a.g[b * M + j];
+    const float tm = a.t_max[b * Mp1 + j], ts = a.t_sum[b * Mp1 + j];
+    const float qm = a.draft_is_logits ? a.q_max[b * M + j] : 0.f;
+    const float qs = a.draft_is_logits ? a.q_sum[b * M + j] : 1.f;
+    bool zs = false, zj = false;
+    float p_c = 0.f, q_c = 0.f;
+    if (c >= 0 && c < a.V) {
+      const float l = a.L[(size_t)(b * Mp1 + j) * a.Lld + c];
+      p_c = expf(l - tm) / ts;
+      const float dv = a.D[((size_t)b * a.draft_rows + j) * a.V + c];
+      q_c = a.draft_is_logits ? expf(dv - qm) / qs : dv;
+      zs = a.uniforms[b * Mp1 + j] * q_c < p_c;
+      zj = g > a.judge_threshold;
+    } else {
+      flags |= 1u;  // bad token id
+    }
+    if (isnan(g) || isnan(ts) || isnan(qs) || isnan(q_c)) flags |= 2u;
+    z = zs || (a.mode_judge && zj);
+    if (a.z_stand) a.z_stand[b * M + j] = zs;
+    if (a.z_judge) a.z_judge[b * M + j] = zj;
+    if (a.p_at) a.p_at[b * M + j] = p_c;
+    if (a.q_at) a.q_at[b * M + j] = q_c;
+    if (a.judge_logit) a.judge_logit[b * M + j] = g;
+  }
+  if (j == M && isnan(a.t_sum[b * Mp1 + M])) flags |= 2u;
+  const unsigned long long mask = __ballot(z);
+  const int mstar = __ffsll((long long)~mask) - 1;  // lanes >= M vote 0, so mstar <= M
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) flags |= __shfl_xor(flags, o);
+  if (j == 0) {
+    a.accept_len[b] = mstar;
+    a.status[b] = flags;
+  }
+}
+
+hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
+  const int R = a.B * (a.M + 1), S = a.B * a.M;
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(R + 2 * S), dim3(256), 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(accept_kernel, dim3(a.B), dim3(64), 0, st, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------- sampler
+
+// Unnormalised mass of token v for sequence b given its accepted prefix m:
+//   m <  M : max(0, p_{m+1}[v] - q_{m+1}[v])      (first rejected position)
+//   m == M : p_{M+1}[v]                            (bonus token)
+// (Sec. 3.1, paragraph after Eq. 4.)  `plain` forces the second form.
+struct MassRow {
+  const float* l; const float* dq;
+  float tm, tinv, qm, qinv;
+  int use_q, q_is_logits;
+  __device__ __forceinline__ float operator()(int v) const {
+    const float p = __expf(l[v] - tm) * tinv;
+    if (!use_q) return p;
+    const float q = q_is_logits ? __expf(dq[v] - qm) * qinv : dq[v];
+    const float r = p - q;
+    return (r < 0.f) ? 0.f : r;  // not fmaxf: a NaN must stay visible in the sum
+  }
+};
+
+__device__ __forceinline__ MassRow make_mass_row(const SamplerArgs& a, int b, bool plain) {
+  const int Mp1 = a.M + 1;
+  const int m = a.accept_len[b];
+  MassRow r;
+  r.l = a.L + (size_t)(b * Mp1 + m) * a.Lld;
+  r.tm = a.t_max[b * Mp1 + m];
+  r.tinv = 1.f / a.t_sum[b * Mp1 + m];
+  r.use_q = (m < a.M) && !plain;
+  r.q_is_logits = a.draft_is_logits;
+  r.dq = a.D; r.qm = 0.f; r.qinv = 1.f;
+  if (m < a.M) {
+    r.dq = a.D + ((size_t)b * a.draft_rows + m) * a.V;
+    if (a.draft_is_logits) { r.qm = a.q_max[b * a.M + m]; r.qinv = 1.f / a.q_sum[b * a.M + m]; }
+  }
+  return r;
+}
+
+// Sum of the masses of one chunk in float64, fixed order: each thread adds its 4
+// consecutive tokens, then a fixed tree over the 256 threads.
+__device__ __forceinline__ double chunk_sum(const MassRow& row, int chunk, int V, double* red /*[256]*/) {
+  const int tid = threadIdx.x;
+  const int v0 = chunk * kSamplerChunk + tid * 4;
+  double s = 0.0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (v0 + i < V) s += (double)row(v0 + i);
+  red[tid] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) red[tid] += red[tid + o];
+    __syncthreads();
+  }
+  const double total = red[0];
+  __syncthreads();
+  return total;
+}
+
+__global__ __launch_bounds__(256) void sampler_mass_kernel(SamplerArgs a) {
+  __shared__ double red[256];
+  const int b = blockIdx.y, chunk = blockIdx.x;
+  const MassRow row = make_mass_row(a, b, false);
+  const double s = chunk_sum(row, chunk, a.V, red);
+  if (threadIdx.x == 0) a.chunk_mass[(size_t)b * a.nChunk + chunk] = s;
+}
+
+// Block-wide helpers over 256 threads in float64 (fixed order, deterministic).
+__device__ __forceinline__ double block_sum256(double v, double* red) {
+  const int tid = threadIdx.x;
+  red[tid] = v;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) red[tid] += red[tid + o];
+    __syncthreads();
+  }
+  const double total = red[0];
+  __syncthreads();
+  return total;
+}
+
+__device__ __forceinline__ double block_inclusive_scan256(double v, double* red) {
+  const int tid = threadIdx.x;
+  red[tid] = v;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {
+    const double add = (tid >= o) ? red[tid - o] : 0.0;
+    __syncthreads();
+    red[tid] += add;
+    __syncthreads();
+  }
+  const double r = red[tid];
+  __syncthreads();
+  return r;
+}
+
+__device__ __forceinline__ double total_chunk_mass(const double* cm, int nChunk, double* red) {
+  double v = 0.0;
+  for (int i = threadIdx.x; i < nChunk; i += 256) v += cm[i];
+  return block_sum256(v, red);
+}
+
+// Inverse CDF in ascending token id: next = min{ v : cdf[v] > u_s * S }.
+__global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
+  __shared__ double red[256];
+  __shared__ double s_base, s_carry;
+  __shared__ int s_chunk, s_lastchunk;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  double* cm = a.chunk_mass + (size_t)b * a.nChunk;
+
+  double S = total_chunk_mass(cm, a.nChunk, red);
+  const bool plain = !(S > 0.0);
+  if (tid == 0 && S == 0.0 && a.accept_len[b] < a.M) atomicOr(&a.status[b], 4u);
+  if (plain) {
+    // No residual mass (q == p at the cut), or NaN: recompute the chunk masses from p itself.
+    const MassRow prow = make_mass_row(a, b, true);
+    for (int ch = 0; ch < a.nChunk; ++ch) {
+      const double s = chunk_sum(prow, ch, a.V, red);
+      if (tid == 0) cm[ch] = s;
+    }
+    __syncthreads();
+    S = total_chunk_mass(cm, a.nChunk, red);
+    if (tid == 0 && !(S == S)) atomicOr(&a.status[b], 2u);
+  }
+  const MassRow row = make_mass_row(a, b, plain);
+  const double thresh = (double)a.uniforms[b * (a.M + 1) + a.M] * S;
+
+  // first chunk whose inclusive prefix exceeds the threshold
+  if (tid == 0) { s_chunk = 0x7fffffff; s_lastchunk = -1; s_carry = 0.0; s_base = 0.0; }
+  __syncthreads();
+  for (int base = 0; base < a.nChunk; base += 256) {
+    const int i = base + tid;
+    const double val = (i < a.nChunk) ? cm[i] : 0.0;
+    const double incl = s_carry + block_inclusive_scan256(val, red);
+    if (i < a.nChunk && val > 0.0) {
+      if (incl > thresh) atomicMin(&s_chunk, i);
+      atomicMax(&s_lastchunk, i);
+    }
+    __syncthreads();
+    if (s_chunk != 0x7fffffff) {
+      if (i == s_chunk) s_base = incl - val;
+      __syncthreads();
+      break;
+    }
+    if (tid == 255) s_carry = incl;
+    __syncthreads();
+  }
+  if (s_chunk == 0x7fffffff) {  // rounding left the threshold beyond the last edge (or S is NaN)
+    if (tid == 0) {
+      const int last = s_lastchunk < 0 ? 0 : s_lastchunk;
+      double run = 0.0;
+      for (int i = 0; i < last; ++i) run += cm[i];
+      s_chunk = last; s_base = run;
+    }
+    __syncthreads();
+  }
+  const double s_thresh = thresh;
+
+  // Scan inside the chosen chunk: thread t owns tokens 4t..4t+3 of the chunk.
+  const int chunk = s_chunk;
+  const int v0 = chunk * kSamplerChunk + tid * 4;
+  double mv[4];
+  double local = 0.0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    mv[i] = (v0 + i < a.V) ? (double)row(v0 + i) : 0.0;
+    local += mv[i];
+  }
+  red[tid] = local;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {  // inclusive scan over threads
+    const double add = (tid >= o) ? red[tid - o] : 0.0;
+    __syncthreads();
+    red[tid] += add;
+    __syncthreads();
+  }
+  const double before = s_base + ((tid > 0) ? red[tid - 1] : 0.0);
+  // first token in this thread whose cumulative mass exceeds the threshold
+  int cand = 0x7fffffff;
+  double run = before;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    run += mv[i];
+    if (cand == 0x7fffffff && mv[i] > 0.0 && run > s_thresh) cand = v0 + i;
+  }
+  // last token with mass (fallback when rounding leaves the threshold beyond the chunk)
+  int lastpos = -1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (mv[i] > 0.0) lastpos = v0 + i;
+  __shared__ int s_min, s_last;
+  if (tid == 0) { s_min = 0x7fffffff; s_last = -1; }
+  __syncthreads();
+  if (cand != 0x7fffffff) atomicMin(&s_min, cand);
+  if (lastpos >= 0) atomicMax(&s_last, lastpos);
+  __syncthreads();
+  if (tid == 0) {
+    int tok = (s_min != 0x7fffffff) ? s_min : s_last;
+    if (tok < 0) tok = 0;
+    a.next_token[b] = tok;
+  }
+}
+
+hipError_t launch_sampler(const SamplerArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(sampler_mass_kernel, dim3(a.nChunk, a.B), dim3(256), 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(sampler_pick_kernel, dim3(a.B), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------- probs
+
+__global__ __launch_bounds__(256) void probs_kernel(const float* __restrict__ L, int Lld,
+                                                     const float* __restrict__ t_max,
+                                                     const float* __restrict__ t_sum, int V,
+                                                     float* __restrict__ probs) {
+  const int r = blockIdx.y;
+  const int v = blockIdx.x * 256 + threadIdx.x;
+  if (v >= V) return;
+  probs[(size_t)r * V + v] = expf(L[(size_t)r * Lld + v] - t_max[r]) / t_sum[r];
+}
+
+hipError_t launch_probs(const float* L, int Lld, const float* t_max, const float* t_sum, int R, int V, float* probs,
+                        hipStream_t st) {
+  hipLaunchKernelGGL(probs_kernel, dim3((V + 255) / 256, R), dim3(256), 0, st, L, Lld, t_max, t_sum, V, probs);
+  return hipGetLastError();
+}
+
+}  // namespace jd
