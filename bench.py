@@ -44,6 +44,9 @@ def main() -> int:
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB before the timed region, so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the verification head is built and measured on a "
@@ -77,6 +80,15 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibration_copy_mib > 0:
+        n = args.calibration_copy_mib * 2**20 // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"[bench] calibration copy of {args.calibration_copy_mib} MiB done (reads and writes that many bytes)")
+        del src, dst
 
     # timed region: exactly K steps, HIP events around every kernel group on the same stream
     K = args.steps
