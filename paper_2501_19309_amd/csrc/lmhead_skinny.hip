@@ -24,20 +24,55 @@ namespace jd {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kPF = 2;  // K steps per weight prefetch group
+#ifndef JD_PF
+#define JD_PF 2
+#endif
+#ifndef JD_SKINNY_WAVES
+#define JD_SKINNY_WAVES 4
+#endif
+constexpr int kPF = JD_PF;  // K steps per weight prefetch group
 
 // ------------------------------------------------------------------------------- pack
 
+// Position of fragment block (vg, ks) in Wp, in units of 16 bytes; one (vg, ks) block is
+// 4 sub-fragments x 64 lanes = 256 units.
+#ifndef JD_KMAJOR
+#define JD_KMAJOR 1
+#endif
+#if JD_KMAJOR
+// [ks / kWpKG][vg][ks % kWpKG]: all groups' data for the same few K steps lie together,
+// so wavefronts that advance in step read one compact, moving window of memory.
+constexpr int kWpKG = 2;
+__host__ __device__ __forceinline__ size_t wp_group_offset(int vg, int, int) { return (size_t)vg * (kWpKG * 256); }
+__host__ __device__ __forceinline__ size_t wp_step_offset(int ks, int nVGalloc) {
+  return (size_t)(ks / kWpKG) * nVGalloc * (kWpKG * 256) + (size_t)(ks % kWpKG) * 256;
+}
+__host__ __device__ __forceinline__ void wp_decode(size_t blk, int, int nVGalloc, int* vg, int* ks) {
+  const int s = (int)(blk % kWpKG);
+  const size_t t = blk / kWpKG;
+  *vg = (int)(t % (size_t)nVGalloc);
+  *ks = (int)(t / (size_t)nVGalloc) * kWpKG + s;
+}
+#else
+// [vg][ks]: each vocabulary group is one contiguous stream along K.
+__host__ __device__ __forceinline__ size_t wp_group_offset(int vg, int KS, int) { return (size_t)vg * KS * 256; }
+__host__ __device__ __forceinline__ size_t wp_step_offset(int ks, int) { return (size_t)ks * 256; }
+__host__ __device__ __forceinline__ void wp_decode(size_t blk, int KS, int, int* vg, int* ks) {
+  *ks = (int)(blk % (size_t)KS);
+  *vg = (int)(blk / (size_t)KS);
+}
+#endif
+
 // One thread writes one 16-byte element of Wp (8 consecutive hidden indices of one row).
 __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int layout, int V, int d,
-                                                      int KS, size_t total, uint4* __restrict__ Wp) {
+                                                      int KS, int nVGalloc, size_t total, uint4* __restrict__ Wp) {
   size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   int lane = (int)(idx & 63);
   int sub = (int)((idx >> 6) & 3);
   size_t t = idx >> 8;
-  int ks = (int)(t % (size_t)KS);
-  int vg = (int)(t / (size_t)KS);
+  int ks, vg;
+  wp_decode(t, KS, nVGalloc, &vg, &ks);
   int v = vg * kVocabGroup + sub * 16 + (lane & 15);
   int k0 = ks * kKStep + (lane >> 4) * 8;
   union { uint4 q; uint16_t h[8]; } o;
@@ -64,7 +99,8 @@ hipError_t launch_pack_w(const void* W, int layout, const Geometry& g, void* Wp,
   const size_t blocks = (total + 255) / 256;
   if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(W), layout, g.V, g.d, KS, total, static_cast<uint4*>(Wp));
+                     static_cast<const uint16_t*>(W), layout, g.V, g.d, KS, g.nVGalloc, total,
+                     static_cast<uint4*>(Wp));
   return hipGetLastError();
 }
 
@@ -78,7 +114,7 @@ __device__ __forceinline__ int xs_index(int row, int c) { return row * (kKChunk 
 template <int NXB, int NWAVES>
 __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
     const uint4* __restrict__ Wp, const uint16_t* __restrict__ X, int R, int d, int nChunks, int V, int nVG,
-    float invT, float* __restrict__ L, int Lld, float2* __restrict__ part) {
+    int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part) {
   constexpr int T = NWAVES * 64;
   constexpr int ROWS = NXB * 16;
   constexpr int ITEMS = ROWS * (kKChunk / 8);  // 16-byte items per staged chunk
@@ -98,7 +134,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   const int KS = nChunks * kStepsPerChunk;
   const int nGroupsTotal = KS / kPF;
 
-  const uint4* wptr = Wp + (size_t)vg * KS * 256 + lane;
+  const uint4* wptr = Wp + wp_group_offset(vg, KS, nVGalloc) + lane;
 
   f32x4 acc[4][NXB];
 #pragma unroll
@@ -139,7 +175,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
 #pragma unroll
   for (int s = 0; s < kPF; ++s)
 #pragma unroll
-    for (int sub = 0; sub < 4; ++sub) wbuf[0][s][sub] = wptr[(size_t)s * 256 + sub * 64];
+    for (int sub = 0; sub < 4; ++sub) wbuf[0][s][sub] = wptr[wp_step_offset(s, nVGalloc) + sub * 64];
   store_x(0, 0);
   __syncthreads();
 
@@ -155,7 +191,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
       for (int s = 0; s < kPF; ++s)
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub)
-          wbuf[(gi + 1) & 1][s][sub] = wptr[(size_t)(gnext * kPF + s) * 256 + sub * 64];
+          wbuf[(gi + 1) & 1][s][sub] = wptr[wp_step_offset(gnext * kPF + s, nVGalloc) + sub * 64];
       // keep the prefetch ahead of this group's MFMAs: without the fence the machine
       // scheduler sinks the loads next to their uses and the stream loses its depth
       __builtin_amdgcn_sched_barrier(0);
@@ -225,16 +261,17 @@ static hipError_t launch_skinny_t(const void* Wp, const void* X, int R, const Ge
   const int grid = (g.nVG + NWAVES - 1) / NWAVES;  // grid*NWAVES <= nVGalloc since NWAVES divides kGroupAlloc
   hipLaunchKernelGGL((lmhead_skinny_kernel<NXB, NWAVES>), dim3(grid), dim3(NWAVES * 64), 0, st,
                      static_cast<const uint4*>(Wp), static_cast<const uint16_t*>(X), R, g.d, g.dpad / kKChunk, g.V,
-                     g.nVG, invT, L, g.Vpad, part);
+                     g.nVG, g.nVGalloc, invT, L, g.Vpad, part);
   return hipGetLastError();
 }
 
 hipError_t launch_lmhead_skinny(const void* Wp, const void* X, int R, const Geometry& g, float invT, float* L,
                                 float2* part, int /*num_cus*/, hipStream_t st) {
-  static_assert(kGroupAlloc % 4 == 0, "grid covers only allocated groups");
+  static_assert(kGroupAlloc % JD_SKINNY_WAVES == 0 && kGroupAlloc % 4 == 0, "grid covers only allocated groups");
   if (R <= 0 || R > 64) return hipErrorInvalidValue;
-  if (R <= 16) return launch_skinny_t<1, 4>(Wp, X, R, g, invT, L, part, st);
-  if (R <= 32) return launch_skinny_t<2, 4>(Wp, X, R, g, invT, L, part, st);
+  constexpr int NW = JD_SKINNY_WAVES;
+  if (R <= 16) return launch_skinny_t<1, NW>(Wp, X, R, g, invT, L, part, st);
+  if (R <= 32) return launch_skinny_t<2, NW>(Wp, X, R, g, invT, L, part, st);
   if (R <= 48) return launch_skinny_t<3, 4>(Wp, X, R, g, invT, L, part, st);
   return launch_skinny_t<4, 4>(Wp, X, R, g, invT, L, part, st);
 }
