@@ -141,6 +141,11 @@ extern "C" int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm,
         rc = JD_ERR_HIP;
     }
   }
+  if (rc == JD_OK && bf16 && maxR > 64) {
+    uint8_t* xp = nullptr;
+    rc = dev_alloc(c, &xp, gemm_xp_bytes((int)maxR, c->geo));
+    c->Xp = xp;
+  }
   if (rc != JD_OK) { free_ctx(c); return rc; }
   *out_ctx = c;
   return JD_OK;
@@ -217,12 +222,7 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
     if (R <= 64) {
       JD_HIP(launch_lmhead_skinny(c->Wp, d_emb, R, g, invT, c->L, c->tpart, c->num_cus, st));
     } else {
-      // row blocks of 64 through the small-row kernel
-      for (int r0 = 0; r0 < R; r0 += 64) {
-        const int rows = (R - r0 < 64) ? (R - r0) : 64;
-        JD_HIP(launch_lmhead_skinny(c->Wp, static_cast<const uint16_t*>(d_emb) + (size_t)r0 * cfg.d, rows, g, invT,
-                                    c->L + (size_t)r0 * g.Vpad, c->tpart + (size_t)r0 * c->nPartT, c->num_cus, st));
-      }
+      JD_HIP(launch_lmhead_gemm(c->Wp, d_emb, R, g, invT, c->L, c->tpart, c->Xp, c->num_cus, st));
     }
   } else {
     JD_HIP(launch_lmhead_f32(static_cast<const float*>(c->W), cfg.w_layout, static_cast<const float*>(d_emb), R,

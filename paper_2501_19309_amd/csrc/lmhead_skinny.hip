@@ -34,35 +34,6 @@ constexpr int kPF = JD_PF;  // K steps per weight prefetch group
 
 // ------------------------------------------------------------------------------- pack
 
-// Position of fragment block (vg, ks) in Wp, in units of 16 bytes; one (vg, ks) block is
-// 4 sub-fragments x 64 lanes = 256 units.
-#ifndef JD_KMAJOR
-#define JD_KMAJOR 1
-#endif
-#if JD_KMAJOR
-// [ks / kWpKG][vg][ks % kWpKG]: all groups' data for the same few K steps lie together,
-// so wavefronts that advance in step read one compact, moving window of memory.
-constexpr int kWpKG = 2;
-__host__ __device__ __forceinline__ size_t wp_group_offset(int vg, int, int) { return (size_t)vg * (kWpKG * 256); }
-__host__ __device__ __forceinline__ size_t wp_step_offset(int ks, int nVGalloc) {
-  return (size_t)(ks / kWpKG) * nVGalloc * (kWpKG * 256) + (size_t)(ks % kWpKG) * 256;
-}
-__host__ __device__ __forceinline__ void wp_decode(size_t blk, int, int nVGalloc, int* vg, int* ks) {
-  const int s = (int)(blk % kWpKG);
-  const size_t t = blk / kWpKG;
-  *vg = (int)(t % (size_t)nVGalloc);
-  *ks = (int)(t / (size_t)nVGalloc) * kWpKG + s;
-}
-#else
-// [vg][ks]: each vocabulary group is one contiguous stream along K.
-__host__ __device__ __forceinline__ size_t wp_group_offset(int vg, int KS, int) { return (size_t)vg * KS * 256; }
-__host__ __device__ __forceinline__ size_t wp_step_offset(int ks, int) { return (size_t)ks * 256; }
-__host__ __device__ __forceinline__ void wp_decode(size_t blk, int KS, int, int* vg, int* ks) {
-  *ks = (int)(blk % (size_t)KS);
-  *vg = (int)(blk / (size_t)KS);
-}
-#endif
-
 // One thread writes one 16-byte element of Wp (8 consecutive hidden indices of one row).
 __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int layout, int V, int d,
                                                       int KS, int nVGalloc, size_t total, uint4* __restrict__ Wp) {
@@ -72,7 +43,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
   int sub = (int)((idx >> 6) & 3);
   size_t t = idx >> 8;
   int ks, vg;
-  wp_decode(t, KS, nVGalloc, &vg, &ks);
+  wp_decode(t, nVGalloc, &vg, &ks);
   int v = vg * kVocabGroup + sub * 16 + (lane & 15);
   int k0 = ks * kKStep + (lane >> 4) * 8;
   union { uint4 q; uint16_t h[8]; } o;
@@ -134,7 +105,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   const int KS = nChunks * kStepsPerChunk;
   const int nGroupsTotal = KS / kPF;
 
-  const uint4* wptr = Wp + wp_group_offset(vg, KS, nVGalloc) + lane;
+  const uint4* wptr = Wp + wp_group_offset(vg) + lane;
 
   f32x4 acc[4][NXB];
 #pragma unroll
