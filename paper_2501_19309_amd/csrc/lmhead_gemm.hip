@@ -27,10 +27,25 @@ namespace jd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// acc += A * B with the accumulator tied in place in an accumulation register.  Written as
+// inline assembly because, left to the register allocator, the 44 accumulator tiles of a
+// wavefront get distinct destination and source registers and ~220 copy instructions per
+// loop iteration to move them back.  Hazards the compiler no longer sees are covered by
+// construction: operands come from loads (wait counts are still inserted per register),
+// two MFMAs on the same tile are 43 MFMAs apart, and the epilogue waits explicitly before
+// reading the tiles.
+__device__ __forceinline__ void mfma_16x16x32_bf16_inplace(f32x4& acc, const uint4& a, const bf16x8& b) {
+  const u32x4 av = __builtin_bit_cast(u32x4, a);
+  const u32x4 bv = __builtin_bit_cast(u32x4, b);
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(av), "v"(bv));
+}
 
 constexpr int kXcds = 8;
 constexpr int kGemmSteps = kGemmKChunk / kKStep;  // 4 K steps per staged chunk
 constexpr int kGemmPF = 2;                        // K steps per weight prefetch group
+constexpr int kGemmWBufs = 4;                     // register ring of weight groups: 3 groups (6 K steps) ahead
 
 // Xp[rt][chunk][xb][s][lane][8]: row rt*176 + xb*16 + lane%16, hidden index
 // chunk*128 + s*32 + (lane/16)*8 + 0..7; zero for rows >= R and indices >= d.
@@ -93,32 +108,29 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
 #pragma unroll
     for (int x = 0; x < NXB; ++x) acc[s][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  uint4 wbuf[2][kGemmPF][4];
+  uint4 wbuf[kGemmWBufs][kGemmPF][4];
 
-  // Staging of the next embedding chunk is spread over the K steps of the current one so that
-  // only a few registers are live at a time: portion p (items 4p .. 4p+3 of this thread's 11)
-  // is loaded during step p and written to the idle LDS buffer during step p+1.
-  constexpr int kPortion = 4;
-  constexpr int kPortions = (IPT + kPortion - 1) / kPortion;  // 3
-  static_assert(kPortions < kGemmSteps, "every portion needs a later step to be stored in");
-  static_assert(kPortion == 4 && IPT == 11, "portions are written out by hand below");
-  uint4 xr0, xr1, xr2, xr3;  // named registers, not an array: keeps them off the stack
+  // Staging of the embedding tile runs a whole chunk ahead: during chunk c, step p first
+  // writes portion p of chunk c+1 (loaded one chunk earlier) into the idle LDS buffer and
+  // then re-uses the same registers to load portion p of chunk c+2.  Every load therefore
+  // has four K steps (2816 MFMA cycles) to land.  Portions are items 4p .. 4p+3 of this
+  // thread's 11 sixteen-byte items; named registers, not an array, keep them off the stack,
+  // and portion / step numbers are compile-time constants.
+  constexpr int kPortions = 3;
+  static_assert(IPT == 11 && kPortions < kGemmSteps, "portions are written out by hand below");
+  uint4 xa0, xa1, xa2, xa3, xb0, xb1, xb2, xb3, xc0, xc1, xc2;
 
-  // (portion and step numbers are compile-time constants so that every register array below
-  // is indexed statically and stays in registers)
   auto load_portion = [&](const uint4* src, auto pc) {
     constexpr int p = decltype(pc)::value;
-    xr0 = src[tid + (p * 4 + 0) * 256];
-    xr1 = src[tid + (p * 4 + 1) * 256];
-    xr2 = src[tid + (p * 4 + 2) * 256];
-    if constexpr (p * 4 + 3 < IPT) xr3 = src[tid + (p * 4 + 3) * 256];
+    if constexpr (p == 0) { xa0 = src[tid]; xa1 = src[tid + 256]; xa2 = src[tid + 512]; xa3 = src[tid + 768]; }
+    if constexpr (p == 1) { xb0 = src[tid + 1024]; xb1 = src[tid + 1280]; xb2 = src[tid + 1536]; xb3 = src[tid + 1792]; }
+    if constexpr (p == 2) { xc0 = src[tid + 2048]; xc1 = src[tid + 2304]; xc2 = src[tid + 2560]; }
   };
   auto store_portion = [&](uint4* dst, auto pc) {
     constexpr int p = decltype(pc)::value;
-    dst[tid + (p * 4 + 0) * 256] = xr0;
-    dst[tid + (p * 4 + 1) * 256] = xr1;
-    dst[tid + (p * 4 + 2) * 256] = xr2;
-    if constexpr (p * 4 + 3 < IPT) dst[tid + (p * 4 + 3) * 256] = xr3;
+    if constexpr (p == 0) { dst[tid] = xa0; dst[tid + 256] = xa1; dst[tid + 512] = xa2; dst[tid + 768] = xa3; }
+    if constexpr (p == 1) { dst[tid + 1024] = xb0; dst[tid + 1280] = xb1; dst[tid + 1536] = xb2; dst[tid + 1792] = xb3; }
+    if constexpr (p == 2) { dst[tid + 2048] = xc0; dst[tid + 2304] = xc1; dst[tid + 2560] = xc2; }
   };
   auto load_wgroup = [&](const int buf, int g) {
     const uint4* src = wbase + (size_t)g * wGroupStride;
@@ -128,26 +140,43 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
       for (int sub = 0; sub < 4; ++sub) wbuf[buf][s2][sub] = src[s2 * 256 + sub * 64 + lane];
   };
 
-  // prologue: chunk 0 into LDS buffer 0, first weight group into registers
+  // prologue: chunk 0 into LDS buffer 0, chunk 1 into the staging registers
   load_portion(xbase, std::integral_constant<int, 0>{}); store_portion(xs[0], std::integral_constant<int, 0>{});
   load_portion(xbase, std::integral_constant<int, 1>{}); store_portion(xs[0], std::integral_constant<int, 1>{});
   load_portion(xbase, std::integral_constant<int, 2>{}); store_portion(xs[0], std::integral_constant<int, 2>{});
-  static_assert(kPortions == 3, "prologue and step schedule are written for three portions");
+  {
+    const uint4* x1 = xbase + (size_t)min(1, nChunks - 1) * ITEMS;
+    load_portion(x1, std::integral_constant<int, 0>{});
+    load_portion(x1, std::integral_constant<int, 1>{});
+    load_portion(x1, std::integral_constant<int, 2>{});
+  }
+  // weight groups 0 .. kGemmWBufs-2 in flight before the loop starts
+  static_assert(kGemmWBufs == 4 && GROUPS == 2, "ring index below assumes 2 groups per chunk, 4 buffers");
   load_wgroup(0, 0);
+  load_wgroup(1, min(1, nGroupsTotal - 1));
+  load_wgroup(2, min(2, nGroupsTotal - 1));
   __syncthreads();
 
-  for (int ch = 0; ch < nChunks; ++ch) {
-    // branch-free: the last iteration re-stages its own chunk into the idle buffer, unread
-    const uint4* xnext = xbase + (size_t)min(ch + 1, nChunks - 1) * ITEMS;
-    uint4* xdst = xs[(ch + 1) & 1];
-    const uint4* xcur = xs[ch & 1] + lane;
+  // One staged chunk.  `parity` (chunk index mod 2) is a compile-time constant: it selects the
+  // LDS buffer and, with the group number inside the chunk, the slot of the register ring.
+  auto chunk_body = [&](const int ch, auto parc) {
+    constexpr int parity = decltype(parc)::value;
+    // branch-free: past the end the last chunk is re-loaded and re-staged, unread
+    const uint4* xnext = xbase + (size_t)min(ch + 2, nChunks - 1) * ITEMS;
+    uint4* xdst = xs[parity ^ 1];
+    const uint4* xcur = xs[parity] + lane;
     auto k_step = [&](auto ksc) {
       constexpr int ks = decltype(ksc)::value;
       constexpr int gi = ks / kGemmPF, s = ks % kGemmPF;
-      if constexpr (ks > 0 && ks - 1 < kPortions) store_portion(xdst, std::integral_constant<int, (ks > 0 ? ks - 1 : 0)>{});
-      if constexpr (ks < kPortions) load_portion(xnext, std::integral_constant<int, (ks < kPortions ? ks : 0)>{});
-      // prefetch the next weight group (the very last one re-reads itself)
-      if constexpr (s == 0) load_wgroup((gi + 1) & 1, min(ch * GROUPS + gi + 1, nGroupsTotal - 1));
+      constexpr int slot = (parity * GROUPS + gi) % kGemmWBufs;
+      if constexpr (ks < kPortions) {
+        store_portion(xdst, std::integral_constant<int, (ks < kPortions ? ks : 0)>{});
+        load_portion(xnext, std::integral_constant<int, (ks < kPortions ? ks : 0)>{});
+      }
+      // prefetch the weight group three ahead into the slot freed by the previous group
+      // (past the end it re-reads the last group, unread)
+      if constexpr (s == 0)
+        load_wgroup((slot + kGemmWBufs - 1) % kGemmWBufs, min(ch * GROUPS + gi + kGemmWBufs - 1, nGroupsTotal - 1));
       // keep the loads above ahead of this step's MFMAs
       __builtin_amdgcn_sched_barrier(0);
       // operand reads run two row blocks ahead of the MFMAs that consume them
@@ -159,15 +188,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
         if (x + 2 < NXB) bfrag[(x + 2) % 3] = __builtin_bit_cast(bf16x8, xcur[((x + 2) * kGemmSteps + ks) * 64]);
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub)
-          acc[sub][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8, wbuf[gi & 1][s][sub]), bfrag[x % 3], acc[sub][x], 0, 0, 0);
-      }
-      // pin that interleaving: 2 LDS reads, then (1 LDS read, 4 MFMA) per row block
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-#pragma unroll
-      for (int x = 0; x < NXB; ++x) {
-        if (x + 2 < NXB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+          mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
       }
       __builtin_amdgcn_sched_barrier(0);
     };
@@ -177,7 +198,16 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     k_step(std::integral_constant<int, 3>{});
     static_assert(kGemmSteps == 4, "four K steps per staged chunk");
     __syncthreads();
+  };
+
+  for (int ch = 0; ch < nChunks; ch += 2) {  // nChunks is even: d is padded to 256
+    chunk_body(ch, std::integral_constant<int, 0>{});
+    chunk_body(ch + 1, std::integral_constant<int, 1>{});
   }
+
+  // the last MFMAs must have left the matrix pipeline before their tiles are read
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
 
   // epilogue: acc[sub][x][i] = logit of row rt*176 + x*16 + n, entry vg*64 + sub*16 + gq*4 + i
   if (vg >= nVG) return;
