@@ -165,32 +165,49 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     const uint4* xnext = xbase + (size_t)min(ch + 2, nChunks - 1) * ITEMS;
     uint4* xdst = xs[parity ^ 1];
     const uint4* xcur = xs[parity] + lane;
+    // Memory instructions are dealt out one per row block between the MFMAs, never in a
+    // burst: with one wavefront per SIMD nothing else can issue while a wavefront waits for
+    // the texture-address or LDS queue to take its instruction, and the four wavefronts of
+    // the workgroup together keep those queues busy for ~60 % of the MFMA time.
+    auto stage_item = [&](const int i) {  // write item i of chunk c+1 to LDS, reload it for chunk c+2
+      switch (i) {
+        case 0: xdst[tid] = xa0; xa0 = xnext[tid]; break;
+        case 1: xdst[tid + 256] = xa1; xa1 = xnext[tid + 256]; break;
+        case 2: xdst[tid + 512] = xa2; xa2 = xnext[tid + 512]; break;
+        case 3: xdst[tid + 768] = xa3; xa3 = xnext[tid + 768]; break;
+        case 4: xdst[tid + 1024] = xb0; xb0 = xnext[tid + 1024]; break;
+        case 5: xdst[tid + 1280] = xb1; xb1 = xnext[tid + 1280]; break;
+        case 6: xdst[tid + 1536] = xb2; xb2 = xnext[tid + 1536]; break;
+        case 7: xdst[tid + 1792] = xb3; xb3 = xnext[tid + 1792]; break;
+        case 8: xdst[tid + 2048] = xc0; xc0 = xnext[tid + 2048]; break;
+        case 9: xdst[tid + 2304] = xc1; xc1 = xnext[tid + 2304]; break;
+        case 10: xdst[tid + 2560] = xc2; xc2 = xnext[tid + 2560]; break;
+        default: break;
+      }
+    };
     auto k_step = [&](auto ksc) {
       constexpr int ks = decltype(ksc)::value;
       constexpr int gi = ks / kGemmPF, s = ks % kGemmPF;
       constexpr int slot = (parity * GROUPS + gi) % kGemmWBufs;
-      if constexpr (ks < kPortions) {
-        store_portion(xdst, std::integral_constant<int, (ks < kPortions ? ks : 0)>{});
-        load_portion(xnext, std::integral_constant<int, (ks < kPortions ? ks : 0)>{});
-      }
-      // prefetch the weight group three ahead into the slot freed by the previous group
-      // (past the end it re-reads the last group, unread)
-      if constexpr (s == 0)
-        load_wgroup((slot + kGemmWBufs - 1) % kGemmWBufs, min(ch * GROUPS + gi + kGemmWBufs - 1, nGroupsTotal - 1));
-      // keep the loads above ahead of this step's MFMAs
-      __builtin_amdgcn_sched_barrier(0);
+      constexpr int nslot = (slot + kGemmWBufs - 1) % kGemmWBufs;
+      // the weight group three ahead goes into the slot freed by the previous group, four
+      // fragments per K step (past the end it re-reads the last group, unread)
+      const uint4* wsrc =
+          wbase + (size_t)min(ch * GROUPS + gi + kGemmWBufs - 1, nGroupsTotal - 1) * wGroupStride + lane;
       // operand reads run two row blocks ahead of the MFMAs that consume them
       bf16x8 bfrag[3];
       bfrag[0] = __builtin_bit_cast(bf16x8, xcur[(0 * kGemmSteps + ks) * 64]);
       bfrag[1] = __builtin_bit_cast(bf16x8, xcur[(1 * kGemmSteps + ks) * 64]);
 #pragma unroll
       for (int x = 0; x < NXB; ++x) {
+        if (x % 2 == 0 && x / 2 < 4) wbuf[nslot][s][x / 2] = wsrc[s * 256 + (x / 2) * 64];
+        if (x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < IPT) stage_item(ks * 4 + x / 2);
         if (x + 2 < NXB) bfrag[(x + 2) % 3] = __builtin_bit_cast(bf16x8, xcur[((x + 2) * kGemmSteps + ks) * 64]);
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub)
           mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
+        __builtin_amdgcn_sched_barrier(0);  // keep this dealing-out as written
       }
-      __builtin_amdgcn_sched_barrier(0);
     };
     k_step(std::integral_constant<int, 0>{});
     k_step(std::integral_constant<int, 1>{});
