@@ -37,6 +37,31 @@ SMALL = [
 ]
 
 
+EDGE = [
+    VerifyShape("e_M63", 2, 63, 64, 300, "bf16", 1.0),          # ballot width: M = 63, R = 128 (GEMM regime)
+    VerifyShape("e_M63_single", 1, 63, 128, 512, "bf16", 1.5),   # R = 64 exactly (largest small-row launch)
+    VerifyShape("e_M1", 5, 1, 64, 200, "bf16", 1.0),             # one draft token
+    VerifyShape("e_V8_f32", 7, 3, 16, 8, "f32", 1.0),            # vocabulary of 8 (brute-force scale)
+    VerifyShape("e_V8_bf16", 7, 3, 16, 8, "bf16", 1.0),          # one partial vocabulary group
+    VerifyShape("e_V65", 3, 4, 32, 65, "bf16", 0.5),             # one entry into the second group
+    VerifyShape("e_d8", 2, 5, 8, 700, "bf16", 1.0),              # smallest hidden size the bf16 path takes
+    VerifyShape("e_B200", 200, 2, 64, 333, "bf16", 1.0),         # many sequences, R = 600
+    VerifyShape("e_R65", 5, 12, 96, 1024, "bf16", 1.0),          # first row count of the GEMM regime
+    VerifyShape("e_R177", 3, 58, 64, 640, "bf16", 1.0),          # one row into a second 176-row tile
+    VerifyShape("e_V1", 2, 2, 8, 1, "f32", 1.0),                 # single token vocabulary: everything is certain
+]
+
+
+@pytest.mark.parametrize("shape", EDGE, ids=lambda s: s.name)
+def test_edge_shapes_match_oracle(jd, shape):
+    print(f"[case] {shape.name}", flush=True)
+    x = make_inputs(shape, 4)
+    ref = oracle_for(x, return_probs=True)
+    got = jd.run_once(x, want_probs=True)
+    rep = compare(got, ref)
+    print(rep, flush=True)
+
+
 @pytest.mark.parametrize("shape", SMALL, ids=lambda s: s.name)
 @pytest.mark.parametrize("seed", [0, 1])
 def test_small_shapes_match_oracle(jd, shape, seed):
@@ -46,6 +71,63 @@ def test_small_shapes_match_oracle(jd, shape, seed):
     got = jd.run_once(x, want_probs=True)
     rep = compare(got, ref)
     print(rep, flush=True)
+
+
+def test_bruteforce_interval_edges_on_gpu(jd):
+    # the V = 8, M = 3 enumeration of tests/test_oracle_pins.py (every accept interval and every
+    # CDF interval probed 1e-6 inside both ends) through the HIP library, ~30 k sequences in one call
+    import itertools
+    import math
+    from paper_2501_19309_amd import binding as jb
+    from tests.test_oracle_pins import _brute_setup, _mass_after
+    V, M, P, Q, jbits, Pt, Qt = _brute_setup()
+    eps = 1e-6
+    toks, us, want_m, want_tok = [], [], [], []
+    for c in itertools.product(range(V), repeat=M):
+        a = [min(1.0, Pt[j][c[j]] / Qt[j][c[j]]) for j in range(M)]
+        for m in range(M + 1):
+            if m < M and (jbits[m] or a[m] >= 1.0 - 2 * eps):
+                continue
+            u, ok = [], True
+            for j in range(M):
+                if j < m:
+                    if not jbits[j] and a[j] - eps <= 0.0:
+                        ok = False
+                        break
+                    u.append(0.999 if jbits[j] else a[j] - eps)
+                elif j == m:
+                    u.append(a[j] + eps)
+                else:
+                    u.append(0.123)
+            if not ok:
+                continue
+            mass = _mass_after(m, M, Pt, Qt, V)
+            S = math.fsum(mass)
+            edge = 0.0
+            for v in range(V):
+                lo, hi = edge / S, (edge + mass[v]) / S
+                edge += mass[v]
+                if hi - lo < 4 * eps:
+                    continue
+                for us_ in (lo + eps, hi - eps):
+                    toks.append(c); us.append(u + [us_]); want_m.append(m); want_tok.append(v)
+    B = len(toks)
+    emb = np.broadcast_to(np.log(P).astype(np.float32), (B, M + 1, V)).copy()
+    ej = np.zeros((B, M + 1, V), dtype=np.float32)
+    ej[:, 1:, 0] = np.where(np.array(jbits) > 0, 1.0, -1.0)
+    wj = np.zeros(V, dtype=np.float32); wj[0] = 1.0
+    x = {"emb": emb, "W": np.eye(V, dtype=np.float32), "w_judge": wj, "emb_judge": ej,
+         "draft_tokens": np.asarray(toks, dtype=np.int32),
+         "draft_probs": np.broadcast_to(Q.astype(np.float32), (B, M, V)).copy(),
+         "uniforms": np.asarray(us, dtype=np.float32)}
+    got = jd.run_once(x, draft_kind=jb.JD_DRAFT_PROBS)
+    ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_probs"], x["uniforms"],
+                    emb_judge=ej, draft_kind=vo.DRAFT_PROBS)
+    assert np.array_equal(ref["accept_len"], np.array(want_m)) and np.array_equal(ref["next_token"], np.array(want_tok))
+    rep = compare(got, ref)
+    exact = (got["accept_len"] == np.array(want_m)) & (got["next_token"] == np.array(want_tok))
+    print("brute force on GPU:", B, "probes,", int((~exact).sum()), "inside the near-tie bands", rep, flush=True)
+    assert exact.mean() > 0.999
 
 
 def test_config_C1(jd):
