@@ -217,10 +217,26 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
   if (c->prof_on && c->prof_n < c->prof_max) ev = &c->ev[(size_t)(c->prof_n++) * (JD_NUM_KERNELS + 1)];
   if (ev) JD_HIP(hipEventRecord(ev[0], st));
 
+  // Draft row statistics (first pass of the draft softmax) and the judge dot products do not
+  // depend on the LM head.  In the small-row regime they ride in the LM-head launch as extra
+  // workgroups; otherwise the statistics get a launch of their own and the judge dots are done
+  // with the second softmax pass.
+  const bool fused_side = bf16 && R <= 64;
+  SideWork side;
+  side.nStatBlocks = 0; side.nJudgeBlocks = 0;
+  side.stats = make_rowstats_args(d_draft, M, (size_t)draft_rows * cfg.V, (size_t)cfg.V, cfg.V, c->nPartD, c->dpart);
+  side.judge.emb_judge = d_emb_judge ? d_emb_judge : d_emb; side.judge.w_judge = c->wj;
+  side.judge.emb_is_bf16 = cfg.emb_dtype == JD_BF16; side.judge.d = cfg.d; side.judge.M = M;
+  side.judge.bias = cfg.judge_bias; side.judge.g = c->g;
+  if (fused_side) {
+    side.nStatBlocks = logits ? B * M * c->nPartD : 0;
+    side.nJudgeBlocks = B * M;
+  }
+
   // step 1: LM head (+ first softmax pass)
   if (bf16) {
     if (R <= 64) {
-      JD_HIP(launch_lmhead_skinny(c->Wp, d_emb, R, g, invT, c->L, c->tpart, c->num_cus, st));
+      JD_HIP(launch_lmhead_skinny(c->Wp, d_emb, R, g, invT, c->L, c->tpart, side, st));
     } else {
       JD_HIP(launch_lmhead_gemm(c->Wp, d_emb, R, g, invT, c->L, c->tpart, c->Xp, c->num_cus, st));
     }
@@ -231,8 +247,8 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
   }
   if (ev) JD_HIP(hipEventRecord(ev[1], st));
 
-  // step 2: draft row statistics (softmax of the draft logits, first pass)
-  if (logits)
+  // step 2: draft row statistics, when they did not ride beside the LM head
+  if (logits && !fused_side)
     JD_HIP(launch_rowstats(d_draft, B * M, M, (size_t)draft_rows * cfg.V, (size_t)cfg.V, cfg.V, c->nPartD,
                            c->dpart, st));
   if (ev) JD_HIP(hipEventRecord(ev[2], st));
@@ -242,6 +258,7 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
   a.B = B; a.M = M; a.d = cfg.d; a.V = cfg.V;
   a.emb_is_bf16 = cfg.emb_dtype == JD_BF16;
   a.draft_is_logits = logits; a.mode_judge = cfg.mode == JD_MODE_JUDGE;
+  a.judge_done = fused_side;
   a.judge_threshold = c->judge_threshold; a.judge_bias = cfg.judge_bias;
   a.L = c->L; a.Lld = g.Vpad;
   a.tpart = c->tpart; a.nPartT = c->nPartT;

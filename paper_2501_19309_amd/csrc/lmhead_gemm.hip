@@ -96,8 +96,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   const int vg = vt * 4 + wave;  // < nVGalloc (allocated in multiples of 8 groups)
   const int KS = nChunks * kGemmSteps;
   const int nGroupsTotal = KS / kGemmPF;
-  static_assert(kGemmPF == kWpKG, "one prefetch group = one contiguous 8 KiB block of Wp");
-  const size_t wGroupStride = (size_t)nVGalloc * (kWpKG * 256);  // 16-byte units between K-step pairs
+  static_assert(kWpKG % kGemmPF == 0, "a prefetch group (8 KiB) never straddles two K-step blocks of Wp");
 
   const uint4* wbase = Wp + wp_group_offset(vg);
   const uint4* xbase = Xp + (size_t)rt * nChunks * ITEMS;
@@ -133,7 +132,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     if constexpr (p == 2) { dst[tid + 2048] = xc0; dst[tid + 2304] = xc1; dst[tid + 2560] = xc2; }
   };
   auto load_wgroup = [&](const int buf, int g) {
-    const uint4* src = wbase + (size_t)g * wGroupStride;
+    const uint4* src = wbase + wp_step_offset(g * kGemmPF, nVGalloc);
 #pragma unroll
     for (int s2 = 0; s2 < kGemmPF; ++s2)
 #pragma unroll
@@ -193,7 +192,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
       // the weight group three ahead goes into the slot freed by the previous group, four
       // fragments per K step (past the end it re-reads the last group, unread)
       const uint4* wsrc =
-          wbase + (size_t)min(ch * GROUPS + gi + kGemmWBufs - 1, nGroupsTotal - 1) * wGroupStride + lane;
+          wbase + wp_step_offset(min(ch * GROUPS + gi + kGemmWBufs - 1, nGroupsTotal - 1) * kGemmPF, nVGalloc) + lane;
       // operand reads run two row blocks ahead of the MFMAs that consume them
       bf16x8 bfrag[3];
       bfrag[0] = __builtin_bit_cast(bf16x8, xcur[(0 * kGemmSteps + ks) * 64]);

@@ -18,6 +18,7 @@
 //    row per sequence later) and reduced on the fly to one (max, sum exp) partial per
 //    (row, vocabulary group) - the first pass of the vocabulary softmax.
 #include "jd_kernels.hpp"
+#include "side_work.hpp"
 
 namespace jd {
 
@@ -26,9 +27,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #ifndef JD_PF
 #define JD_PF 2
-#endif
-#ifndef JD_SKINNY_WAVES
-#define JD_SKINNY_WAVES 4
 #endif
 constexpr int kPF = JD_PF;  // K steps per weight prefetch group
 
@@ -85,7 +83,8 @@ __device__ __forceinline__ int xs_index(int row, int c) { return row * (kKChunk 
 template <int NXB, int NWAVES>
 __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
     const uint4* __restrict__ Wp, const uint16_t* __restrict__ X, int R, int d, int nChunks, int V, int nVG,
-    int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part) {
+    int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part, int nLmBlocks,
+    SideWork side) {
   constexpr int T = NWAVES * 64;
   constexpr int ROWS = NXB * 16;
   constexpr int ITEMS = ROWS * (kKChunk / 8);  // 16-byte items per staged chunk
@@ -95,6 +94,14 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   static_assert(GROUPS % 2 == 0, "prefetch parity must be static");
 
   __shared__ uint4 xs[2][ITEMS];
+
+  // Workgroups past the LM-head tiles carry the work that does not depend on the LM head
+  // (draft row statistics, judge dot products); they fill slots the tiles leave free.
+  if ((int)blockIdx.x >= nLmBlocks) {
+    static_assert(NWAVES == 4, "side work is written for 256 threads");
+    side_work_block(side, blockIdx.x - nLmBlocks, xs);
+    return;
+  }
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -228,23 +235,23 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
 
 template <int NXB, int NWAVES>
 static hipError_t launch_skinny_t(const void* Wp, const void* X, int R, const Geometry& g, float invT, float* L,
-                                  float2* part, hipStream_t st) {
-  const int grid = (g.nVG + NWAVES - 1) / NWAVES;  // grid*NWAVES <= nVGalloc since NWAVES divides kGroupAlloc
+                                  float2* part, const SideWork& side, hipStream_t st) {
+  const int nLm = (g.nVG + NWAVES - 1) / NWAVES;  // nLm*NWAVES <= nVGalloc since NWAVES divides kGroupAlloc
+  const int grid = nLm + side.nStatBlocks + side.nJudgeBlocks;
   hipLaunchKernelGGL((lmhead_skinny_kernel<NXB, NWAVES>), dim3(grid), dim3(NWAVES * 64), 0, st,
                      static_cast<const uint4*>(Wp), static_cast<const uint16_t*>(X), R, g.d, g.dpad / kKChunk, g.V,
-                     g.nVG, g.nVGalloc, invT, L, g.Vpad, part);
+                     g.nVG, g.nVGalloc, invT, L, g.Vpad, part, nLm, side);
   return hipGetLastError();
 }
 
 hipError_t launch_lmhead_skinny(const void* Wp, const void* X, int R, const Geometry& g, float invT, float* L,
-                                float2* part, int /*num_cus*/, hipStream_t st) {
-  static_assert(kGroupAlloc % JD_SKINNY_WAVES == 0 && kGroupAlloc % 4 == 0, "grid covers only allocated groups");
+                                float2* part, const SideWork& side, hipStream_t st) {
+  static_assert(kGroupAlloc % 4 == 0, "grid covers only allocated groups");
   if (R <= 0 || R > 64) return hipErrorInvalidValue;
-  constexpr int NW = JD_SKINNY_WAVES;
-  if (R <= 16) return launch_skinny_t<1, NW>(Wp, X, R, g, invT, L, part, st);
-  if (R <= 32) return launch_skinny_t<2, NW>(Wp, X, R, g, invT, L, part, st);
-  if (R <= 48) return launch_skinny_t<3, 4>(Wp, X, R, g, invT, L, part, st);
-  return launch_skinny_t<4, 4>(Wp, X, R, g, invT, L, part, st);
+  if (R <= 16) return launch_skinny_t<1, 4>(Wp, X, R, g, invT, L, part, side, st);
+  if (R <= 32) return launch_skinny_t<2, 4>(Wp, X, R, g, invT, L, part, side, st);
+  if (R <= 48) return launch_skinny_t<3, 4>(Wp, X, R, g, invT, L, part, side, st);
+  return launch_skinny_t<4, 4>(Wp, X, R, g, invT, L, part, side, st);
 }
 
 // ------------------------------------------------------------------------------- fp32

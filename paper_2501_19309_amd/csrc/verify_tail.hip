@@ -2,112 +2,43 @@
 // tensor, the accept tests, the judge, the mask combination, the accepted prefix and the
 // residual / bonus-token sampler.  All of it is streaming or per-slot work (no MFMA).
 #include "jd_kernels.hpp"
+#include "side_work.hpp"
 
 namespace jd {
 
-// Online-softmax state: m = running max, s = sum exp(x - m).
-struct MS { float m, s; };
-
-__device__ __forceinline__ MS ms_combine(MS a, MS b) {
-  const float m = fmaxf(a.m, b.m);
-  if (m == -INFINITY) return MS{m, a.s + b.s};  // both empty (keeps NaN sums visible)
-  MS o;
-  o.m = m;
-  o.s = a.s * __expf(a.m - m) + b.s * __expf(b.m - m);
-  return o;
-}
-
-__device__ __forceinline__ MS ms_wave_reduce(MS v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    MS t;
-    t.m = __shfl_xor(v.m, o);
-    t.s = __shfl_xor(v.s, o);
-    v = ms_combine(v, t);
-  }
-  return v;
-}
-
 // ------------------------------------------------------------------------------- row stats
 
-// First pass of the vocabulary softmax over an fp32 matrix (the draft logits, Sec. 3.1
-// Eq. 3 handed over as logits; also the target logits on the fp32 path).
 // grid = (nRows, nSplit).  Each block reduces one contiguous column range of one row.
-__global__ __launch_bounds__(256) void rowstats_kernel(const float* __restrict__ base, int rowsUsed,
-                                                        size_t seqStride, size_t rowStride, int V, int nSplit,
-                                                        int splitLen, float2* __restrict__ part) {
-  const int row = blockIdx.x, split = blockIdx.y;
-  const float* p = base + (size_t)(row / rowsUsed) * seqStride + (size_t)(row % rowsUsed) * rowStride;
-  const int c0 = split * splitLen;
-  const int c1 = min(V, c0 + splitLen);
-  MS st{-INFINITY, 0.f};
-  const int tid = threadIdx.x;
-  if (((reinterpret_cast<uintptr_t>(p) & 15) == 0)) {  // splitLen is a multiple of 4
-    const int nvec = (c1 > c0) ? (c1 - c0) / 4 : 0;
-    const float4* p4 = reinterpret_cast<const float4*>(p + c0);
-    for (int i = tid; i < nvec; i += 256) {
-      const float4 x = p4[i];
-      const float m4 = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
-      if (m4 > st.m) { st.s *= __expf(st.m - m4); st.m = m4; }
-      st.s += __expf(x.x - st.m) + __expf(x.y - st.m) + __expf(x.z - st.m) + __expf(x.w - st.m);
-    }
-    for (int c = c0 + nvec * 4 + tid; c < c1; c += 256) {
-      const float x = p[c];
-      if (x > st.m) { st.s *= __expf(st.m - x); st.m = x; }
-      st.s += __expf(x - st.m);
-    }
-  } else {
-    for (int c = c0 + tid; c < c1; c += 256) {
-      const float x = p[c];
-      if (x > st.m) { st.s *= __expf(st.m - x); st.m = x; }
-      st.s += __expf(x - st.m);
-    }
-  }
-  st = ms_wave_reduce(st);
+__global__ __launch_bounds__(256) void rowstats_kernel(RowStatsArgs a) {
   __shared__ MS red[4];
-  if ((tid & 63) == 0) red[tid >> 6] = st;
-  __syncthreads();
-  if (tid == 0) {
-    MS o = ms_combine(ms_combine(red[0], red[1]), ms_combine(red[2], red[3]));
-    part[(size_t)row * nSplit + split] = make_float2(o.m, o.s);
-  }
+  rowstats_block(a, blockIdx.x, blockIdx.y, red);
+}
+
+RowStatsArgs make_rowstats_args(const float* base, int rowsUsed, size_t seqStride, size_t rowStride, int V,
+                                int nSplit, float2* part) {
+  RowStatsArgs a;
+  a.base = base; a.rowsUsed = rowsUsed; a.seqStride = seqStride; a.rowStride = rowStride;
+  a.V = V; a.nSplit = nSplit; a.part = part;
+  int splitLen = (V + nSplit - 1) / nSplit;
+  a.splitLen = (splitLen + 3) / 4 * 4;
+  return a;
 }
 
 hipError_t launch_rowstats(const float* base, int nRows, int rowsUsed, size_t seqStride, size_t rowStride, int V,
                            int nSplit, float2* part, hipStream_t st) {
-  int splitLen = (V + nSplit - 1) / nSplit;
-  splitLen = (splitLen + 3) / 4 * 4;
-  hipLaunchKernelGGL(rowstats_kernel, dim3(nRows, nSplit), dim3(256), 0, st, base, rowsUsed, seqStride, rowStride,
-                     V, nSplit, splitLen, part);
+  const RowStatsArgs a = make_rowstats_args(base, rowsUsed, seqStride, rowStride, V, nSplit, part);
+  hipLaunchKernelGGL(rowstats_kernel, dim3(nRows, nSplit), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------- accept
 
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-
-__device__ __forceinline__ float dot8_bf16(uint4 a, uint4 b, float acc) {
-  acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
-  acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
-  acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
-  acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
-  return acc;
-}
-
-__device__ __forceinline__ MS ms_block_reduce(MS st, MS* red /*[4]*/) {
-  st = ms_wave_reduce(st);
-  const int tid = threadIdx.x;
-  if ((tid & 63) == 0) red[tid >> 6] = st;
-  __syncthreads();
-  return ms_combine(ms_combine(red[0], red[1]), ms_combine(red[2], red[3]));
-}
-
 // Second pass of the two-pass vocabulary softmax and the judge head, one workgroup per
 // row so that the work spreads over the chip:
 //   blocks [0, R)        combine the LM-head partials of target row r  -> t_max, t_sum
 //   blocks [R, R+S)      combine the partials of draft row (b, j)      -> q_max, q_sum
-//   blocks [R+S, R+2S)   judge logit g = w_judge . e[b, j+1] + bias    (Sec. 4.1; App. B.1)
+//   blocks [R+S, R+2S)   judge logit g = w_judge . e[b, j+1] + bias    (Sec. 4.1; App. B.1),
+//                        unless they were already computed beside the LM head
 // with R = B*(M+1), S = B*M.
 __global__ __launch_bounds__(256) void reduce_rows_kernel(AcceptArgs a) {
   __shared__ MS red[4];
@@ -138,23 +69,11 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(AcceptArgs a) {
     return;
   }
   blk -= S;
-  const int b = blk / a.M, j = blk % a.M;
-  const size_t e0 = ((size_t)b * (a.M + 1) + j + 1) * a.d;
-  float acc = 0.f;
-  if (a.emb_is_bf16) {  // d % 8 == 0 and 16-byte aligned rows on this path
-    const uint4* w = reinterpret_cast<const uint4*>(a.w_judge);
-    const uint4* e = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(a.emb_judge) + e0);
-    for (int i = tid; i < a.d / 8; i += 256) acc = dot8_bf16(w[i], e[i], acc);
-  } else {
-    const float* w = reinterpret_cast<const float*>(a.w_judge);
-    const float* e = reinterpret_cast<const float*>(a.emb_judge) + e0;
-    for (int k = tid; k < a.d; k += 256) acc = fmaf(w[k], e[k], acc);
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-  if ((tid & 63) == 0) redf[tid >> 6] = acc;
-  __syncthreads();
-  if (tid == 0) a.g[blk] = (redf[0] + redf[1]) + (redf[2] + redf[3]) + a.judge_bias;
+  if (a.judge_done) return;  // judge logits were computed beside the LM head
+  JudgeArgs ja;
+  ja.emb_judge = a.emb_judge; ja.w_judge = a.w_judge; ja.emb_is_bf16 = a.emb_is_bf16;
+  ja.d = a.d; ja.M = a.M; ja.bias = a.judge_bias; ja.g = a.g;
+  judge_block(ja, blk, redf);
 }
 
 // One wavefront per sequence, lane j = draft slot j: standard test eps*q[c] < p[c] (Eq. 4),
@@ -205,7 +124,7 @@ __global__ __launch_bounds__(64) void accept_kernel(AcceptArgs a) {
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
   const int R = a.B * (a.M + 1), S = a.B * a.M;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(R + 2 * S), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(R + S + (a.judge_done ? 0 : S)), dim3(256), 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(accept_kernel, dim3(a.B), dim3(64), 0, st, a);
