@@ -22,14 +22,21 @@ from typing import Dict
 import numpy as np
 
 ACCEPT_BAND = 1e-5
+TOPK_BAND = 1e-4      # logit distance from the top-K boundary / between the two largest logits
 JUDGE_BAND = 1e-4
 SAMPLER_BAND = 1e-5
 REL_TOL = 2e-3
 JUDGE_ABS_TOL = 1e-3
 
 
-def compare(gpu: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], mode_judge: bool = True) -> Dict[str, int]:
-    """Raise AssertionError on any violation; return counts of excused near-ties."""
+def compare(gpu: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], mode_judge: bool = True,
+            rule_topk: bool = False) -> Dict[str, int]:
+    """Raise AssertionError on any violation; return counts of excused near-ties.
+
+    With ``rule_topk`` the oracle's accept_margin / sampler_margin are logit distances (top-K
+    boundary, gap between the two largest logits) and the band is TOPK_BAND for both."""
+    accept_band = TOPK_BAND if rule_topk else ACCEPT_BAND
+    sampler_band = TOPK_BAND if rule_topk else SAMPLER_BAND
     B, M = ref["z_stand"].shape
     rep = {"slots": B * M, "sequences": B, "near_tie_stand": 0, "near_tie_judge": 0, "near_tie_sampler": 0,
            "excluded_sequences": 0, "mismatch": 0}
@@ -39,7 +46,7 @@ def compare(gpu: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], mode_judge: 
 
     zs_diff = gpu["z_stand"].astype(bool) != ref["z_stand"].astype(bool)
     zj_diff = gpu["z_judge"].astype(bool) != ref["z_judge"].astype(bool)
-    bad_s = zs_diff & ~(ref["accept_margin"] < ACCEPT_BAND)
+    bad_s = zs_diff & ~(ref["accept_margin"] < accept_band)
     bad_j = zj_diff & ~(ref["judge_margin"] < JUDGE_BAND)
     assert not bad_s.any(), f"z_stand differs outside the band at {np.argwhere(bad_s).tolist()}"
     assert not bad_j.any(), f"z_judge differs outside the band at {np.argwhere(bad_j).tolist()}"
@@ -58,7 +65,7 @@ def compare(gpu: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], mode_judge: 
         assert int(gpu["accept_len"][b]) == int(ref["accept_len"][b]), (b, gpu["accept_len"][b], ref["accept_len"][b])
         g, r = int(gpu["next_token"][b]), int(ref["next_token"][b])
         if g != r:
-            near = ref["sampler_margin"][b] < SAMPLER_BAND and g in (int(ref["next_below"][b]), int(ref["next_above"][b]))
+            near = ref["sampler_margin"][b] < sampler_band and g in (int(ref["next_below"][b]), int(ref["next_above"][b]))
             assert near, f"next_token differs at b={b}: {g} vs {r}, margin {ref['sampler_margin'][b]:.3e}"
             rep["near_tie_sampler"] += 1
 

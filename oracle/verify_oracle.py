@@ -37,6 +37,14 @@ Readings taken where the paper is silent (each is listed in the design notes):
     next = min{ v : cumsum(res)[v] > u_s * sum(res) };
   * token ids outside [0, V) reject the slot and raise a status bit.
 
+Variants of the rule that the paper itself uses (selected by ``rule`` / ``resample``):
+  * top-K verification, the training-free baseline of Sec. 5: c is accepted iff it is among
+    the K most probable tokens of p (K = V accepts every draft token, K = 1 is greedy
+    matching as in Sec. 3.2); the target then decodes greedily, so the replacement or bonus
+    token is argmax p.  Ties are ordered by token id (lower id ranks first).
+  * ``resample = RESAMPLE_TARGET``: the literal "sample a correct token from p_i" of
+    Sec. 3.1, i.e. the replacement is drawn from p_i itself instead of the residual.
+
 Parity pins for every function here live in tests/test_oracle_pins.py: the
 paper's rule on hand cases, brute-force enumeration at V = 8 / M = 3, a
 Monte-Carlo chi-square that standard-only verification emits the target
@@ -56,6 +64,12 @@ STATUS_ZERO_RESIDUAL = 4  # residual mass was exactly zero; fell back to samplin
 
 MODE_JUDGE = 0     # z = z_stand OR z_judge
 MODE_STANDARD = 1  # z = z_stand
+
+RULE_SAMPLING = 0  # Eq. 4 with residual resampling
+RULE_TOPK = 1      # accept iff c is among the K most probable target tokens; new token = argmax
+
+RESAMPLE_RESIDUAL = 0  # replacement drawn from norm(max(0, p - q))
+RESAMPLE_TARGET = 1    # replacement drawn from p itself
 
 DRAFT_LOGITS = 0   # draft tensor holds fp32 logits (softmaxed here at temperature 1)
 DRAFT_PROBS = 1    # draft tensor holds the probability vectors q_i themselves
@@ -159,6 +173,33 @@ def inverse_cdf(mass: np.ndarray, u: float):
     return v, margin
 
 
+def rank_of(logits_row: np.ndarray, c: int) -> int:
+    """Number of tokens that rank before c: strictly larger logit, or equal logit and lower id."""
+    lc = logits_row[c]
+    return int(np.sum(logits_row > lc) + np.sum(logits_row[:c] == lc))
+
+
+def topk_margin(logits_row: np.ndarray, c: int, k: int) -> float:
+    """Distance (in logit units) of c from the top-K boundary: how far L[c] is from the logit
+    that would have to overtake it (accepted) or that it would have to overtake (rejected)."""
+    V = logits_row.shape[0]
+    others = np.delete(logits_row, c)
+    srt = np.sort(others)[::-1]                 # the other V-1 logits, descending
+    if rank_of(logits_row, c) < k:              # accepted: the k-th largest of the others must pass it
+        return float(logits_row[c] - srt[k - 1]) if k - 1 < V - 1 else math.inf
+    return float(srt[k - 1] - logits_row[c])    # rejected: it must pass the k-th largest of the others
+
+
+def argmax_lowest_id(logits_row: np.ndarray):
+    """(argmax with lowest id among ties, runner-up id, gap between the two largest logits)."""
+    v = int(np.argmax(logits_row))              # numpy returns the first maximum
+    if logits_row.shape[0] == 1:
+        return v, -1, math.inf
+    rest = logits_row.copy(); rest[v] = -np.inf
+    r = int(np.argmax(rest))
+    return v, r, float(logits_row[v] - logits_row[r])
+
+
 def mass_neighbours(mass: np.ndarray, v: int):
     """Nearest tokens below / above v that carry mass (-1 if none).  A sampler draw whose
     threshold sits within rounding of a CDF edge can only move to one of these."""
@@ -175,7 +216,8 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
            mode: int = MODE_JUDGE, draft_kind: int = DRAFT_LOGITS,
            temperature: float = 1.0, delta: float = 0.5, judge_bias: float = 0.0,
            w_layout: str = "vd", seqs: Optional[Iterable[int]] = None,
-           return_probs: bool = False) -> Dict[str, np.ndarray]:
+           return_probs: bool = False, rule: int = RULE_SAMPLING, top_k: int = 1,
+           resample: int = RESAMPLE_RESIDUAL) -> Dict[str, np.ndarray]:
     """Verify one batch of drafts.  See the module docstring for the steps.
 
     emb          [B, M+1, d]  LM-head input (bf16 bits as uint16, or float32)
@@ -186,6 +228,12 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
     uniforms     [B, M+1]
     seqs         optional subset of sequence indices to evaluate (sequences are
                  independent, so a subset is exact); outputs then have len(seqs) rows
+    rule, top_k  RULE_SAMPLING (Eq. 4) or RULE_TOPK with 1 <= top_k <= V (Sec. 5 baseline)
+    resample     RESAMPLE_RESIDUAL or RESAMPLE_TARGET (only read under RULE_SAMPLING)
+
+    Under RULE_TOPK ``accept_margin`` holds the logit distance from the top-K boundary,
+    ``sampler_margin`` the gap between the two largest logits of the decoded row and
+    ``next_above`` the runner-up token.
     """
     emb = np.asarray(emb)
     B, Mp1, d = emb.shape
@@ -196,6 +244,8 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
     thr = judge_threshold(delta)
     wj = widen(w_judge)
     ej_src = emb if emb_judge is None else np.asarray(emb_judge)
+    if rule == RULE_TOPK and not (1 <= top_k <= V):
+        raise ValueError("top_k must lie in [1, V]")
 
     out = {
         "accept_len": np.zeros(nb, np.int32), "next_token": np.zeros(nb, np.int32),
@@ -236,10 +286,14 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
             if 0 <= c < V:
                 p_c, q_c = float(P[j, c]), float(Q[j, c])
                 u = float(uniforms[b, j])
-                zs = accept_standard(u, p_c, q_c)                  # step 3
+                if rule == RULE_TOPK:                              # Sec. 5: among the K most probable
+                    zs = rank_of(L[j], c) < top_k
+                    out["accept_margin"][i, j] = topk_margin(L[j], c, top_k)
+                else:
+                    zs = accept_standard(u, p_c, q_c)              # step 3
+                    out["accept_margin"][i, j] = abs(p_c / q_c - u) if q_c > 0 else math.inf
                 zj = bool(g > thr)
                 out["p_at_draft"][i, j], out["q_at_draft"][i, j] = p_c, q_c
-                out["accept_margin"][i, j] = abs(p_c / q_c - u) if q_c > 0 else math.inf
                 out["judge_margin"][i, j] = abs(g - thr)
             else:                                                  # invalid id: reject outright
                 status |= STATUS_BAD_TOKEN
@@ -247,18 +301,23 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
             out["z_stand"][i, j], out["z_judge"][i, j] = zs, zj
             z.append(zs or (mode == MODE_JUDGE and zj))            # step 5
         m = accepted_prefix(z)                                     # step 6
-        if m < M:                                                  # step 7
-            mass = residual(P[m], Q[m])
-            if np.sum(mass) == 0:
-                status |= STATUS_ZERO_RESIDUAL
-                mass = P[m]
+        if rule == RULE_TOPK:                                      # greedy target: argmax of row m
+            tok, runner_up, smargin = argmax_lowest_id(L[m])
+            below, above = -1, runner_up
         else:
-            mass = P[M]
-        tok, smargin = inverse_cdf(mass, float(uniforms[b, M]))
+            if m < M and resample == RESAMPLE_RESIDUAL:            # step 7
+                mass = residual(P[m], Q[m])
+                if np.sum(mass) == 0:
+                    status |= STATUS_ZERO_RESIDUAL
+                    mass = P[m]
+            else:
+                mass = P[m]                                        # bonus row, or "sample from p_i"
+            tok, smargin = inverse_cdf(mass, float(uniforms[b, M]))
+            below, above = mass_neighbours(mass, tok)
         out["accept_len"][i], out["next_token"][i], out["status"][i] = m, tok, status
         out["row_max"][i], out["row_sumexp"][i] = rmax, rsum
         out["sampler_margin"][i] = smargin
-        out["next_below"][i], out["next_above"][i] = mass_neighbours(mass, tok)
+        out["next_below"][i], out["next_above"][i] = below, above
         if return_probs:
             out["probs"][i] = P
     return out

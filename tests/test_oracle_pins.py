@@ -499,3 +499,74 @@ def test_synthetic_acceptance_rate_matches_closed_form(sigma, want):
     assert abs(scipy.stats.norm.cdf(-0.5) * 2 - 0.617) < 1e-3
     # the synthetic judge is a fair coin per slot
     assert abs(jacc / n - 0.5) < 0.05
+
+
+# ----------------------------------------------------------------------------- top-K rule, plain-p resampling
+
+def test_topk_rule_against_python_sort():
+    # Sec. 5 "Training-free baseline": accept c iff it is among the K most probable target tokens.
+    # Integer logits on a small vocabulary, with exact ties; rank by an independent Python sort.
+    rng = np.random.default_rng(21)
+    V, M, B = 6, 3, 40
+    W = np.eye(V, dtype=np.float32)
+    emb = rng.integers(-2, 3, size=(B, M + 1, V)).astype(np.float32)   # logits = emb rows (many ties)
+    wj = np.zeros(V, dtype=np.float32)
+    tokens = rng.integers(0, V, size=(B, M)).astype(np.int32)
+    D = rng.normal(size=(B, M, V)).astype(np.float32)
+    u = rng.random((B, M + 1)).astype(np.float32)
+    prev = None
+    for K in range(1, V + 1):
+        out = vo.verify(emb, W, wj, tokens, D, u, mode=vo.MODE_STANDARD, rule=vo.RULE_TOPK, top_k=K)
+        for b in range(B):
+            zs = []
+            for j in range(M):
+                order = sorted(range(V), key=lambda v: (-float(emb[b, j, v]), v))  # ties: lower id first
+                zs.append(int(order.index(int(tokens[b, j])) < K))
+            assert out["z_stand"][b].tolist() == zs
+            m = vo.accepted_prefix(zs)
+            assert int(out["accept_len"][b]) == m
+            row = [float(x) for x in emb[b, m]]
+            assert int(out["next_token"][b]) == row.index(max(row))       # greedy target, lowest id on ties
+        if prev is not None:                                              # acceptance is monotone in K
+            assert (out["z_stand"] >= prev).all()
+        prev = out["z_stand"].copy()
+    # K = V: every draft token is accepted (the paper: "reduces to running just the fast draft model")
+    assert (out["accept_len"] == M).all() and out["z_stand"].all()
+    with pytest.raises(ValueError):
+        vo.verify(emb, W, wj, tokens, D, u, rule=vo.RULE_TOPK, top_k=V + 1)
+
+
+def test_top1_is_greedy_matching_and_judge_still_ors():
+    shape = VerifyShape("t", 16, 6, 32, 200, "f32", 0.5)
+    x = make_inputs(shape, 2)
+    args = (x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"])
+    L = vo.target_logits(x["emb"].reshape(-1, 32), x["W"]).reshape(16, 7, 200)
+    out = vo.verify(*args, mode=vo.MODE_STANDARD, rule=vo.RULE_TOPK, top_k=1)
+    greedy = (x["draft_tokens"] == np.argmax(L[:, :6], axis=-1))
+    assert np.array_equal(out["z_stand"].astype(bool), greedy)            # Sec. 3.2: greedy matching
+    assert greedy.any() and not greedy.all()
+    jud = vo.verify(*args, mode=vo.MODE_JUDGE, rule=vo.RULE_TOPK, top_k=1)
+    assert np.array_equal(jud["z_stand"], out["z_stand"]) and (jud["accept_len"] >= out["accept_len"]).all()
+    # margins: distance to the top-K boundary is the logit gap to the best other token
+    b, j = 0, 0
+    c = int(x["draft_tokens"][b, j]); others = np.delete(L[b, j], c)
+    assert abs(out["accept_margin"][b, j] - abs(L[b, j, c] - others.max())) < 1e-12
+    srt = np.sort(L[b, int(out["accept_len"][b])])
+    assert abs(out["sampler_margin"][b] - (srt[-1] - srt[-2])) < 1e-12
+
+
+def test_resample_from_target_reading():
+    # the literal reading of Sec. 3.1: after a rejection the token is drawn from p_i itself
+    shape = VerifyShape("t", 24, 4, 16, 64, "f32", 2.0)
+    x = make_inputs(shape, 5)
+    args = (x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"])
+    res = vo.verify(*args, mode=vo.MODE_STANDARD)
+    tgt = vo.verify(*args, mode=vo.MODE_STANDARD, resample=vo.RESAMPLE_TARGET, return_probs=True)
+    assert np.array_equal(res["accept_len"], tgt["accept_len"]) and np.array_equal(res["z_stand"], tgt["z_stand"])
+    assert (tgt["accept_len"] < 4).any()
+    for b in range(24):
+        p = tgt["probs"][b, int(tgt["accept_len"][b])]
+        want = int(np.searchsorted(np.cumsum(p), float(x["uniforms"][b, 4]) * p.sum(), side="right"))
+        assert int(tgt["next_token"][b]) == want
+    assert (res["next_token"] != tgt["next_token"]).any()
+    assert (tgt["status"] == 0).all()
