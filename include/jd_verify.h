@@ -9,6 +9,7 @@
  *   1. LM head: L[b,r,:] = (x[b,r,:] . W_lm) / T, p_{r+1} = softmax(L[b,r,:])   (Sec. 3.1, Eq. 2)
  *   2. draft probabilities q_{j+1}[c_{j+1}] from the draft tensor                 (Sec. 3.1, Eq. 3)
  *   3. standard test   z_stand[j] = ( eps_j * q[c] < p[c] )                       (Sec. 3.1, Eq. 4)
+ *      (or, under JD_RULE_TOPK, c among the top_k most probable tokens of p       Sec. 5)
  *   4. judge test      z_judge[j] = ( w_judge . e[b,j+1,:] + bias > logit(delta) )
  *      i.e. sigmoid(f_judge(e)) > delta on the embedding of the judged token      (Sec. 4.1; App. B.1)
  *   5. z = z_stand OR z_judge                                                     (Sec. 4.1, "Inference")
@@ -57,6 +58,14 @@ extern "C" {
 #define JD_MODE_JUDGE    0            /* z = z_stand OR z_judge (Sec. 4.1)                            */
 #define JD_MODE_STANDARD 1            /* z = z_stand (plain speculative sampling, Eq. 4)              */
 
+#define JD_RULE_SAMPLING 0            /* z_stand by Eq. 4; new token by inverse CDF (residual / bonus) */
+#define JD_RULE_TOPK     1            /* z_stand = c is among the top_k most probable tokens of p      */
+                                      /* (Sec. 5 training-free baseline; top_k = 1 is the greedy      */
+                                      /* matching of Sec. 3.2); new token = argmax p, lowest id on ties */
+
+#define JD_RESAMPLE_RESIDUAL 0        /* replacement drawn from norm(max(0, p - q))                   */
+#define JD_RESAMPLE_TARGET   1        /* replacement drawn from p itself (literal Sec. 3.1 wording)   */
+
 /* per-sequence status bits written to d_status */
 #define JD_STATUS_BAD_TOKEN     1u    /* a draft token id outside [0,V): that slot is rejected        */
 #define JD_STATUS_NAN           2u    /* NaN met in target logits, a draft row or a judge logit       */
@@ -82,6 +91,9 @@ typedef struct {
   float   delta;                /* judge threshold in [0.5, 1]; 1 never accepts (reduces to Eq. 4)    */
   float   judge_bias;           /* scalar added to w_judge . e                                        */
   int32_t device;               /* HIP device ordinal                                                 */
+  int32_t rule;                 /* JD_RULE_SAMPLING | JD_RULE_TOPK                                    */
+  int32_t top_k;                /* 1 <= top_k <= V, read only under JD_RULE_TOPK                      */
+  int32_t resample;             /* JD_RESAMPLE_RESIDUAL | JD_RESAMPLE_TARGET (JD_RULE_SAMPLING only)  */
 } jd_verify_config;
 
 typedef struct {                /* device pointers; the first three are required, NULL skips the rest */

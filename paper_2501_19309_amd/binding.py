@@ -22,6 +22,8 @@ JD_F32, JD_BF16 = 0, 1
 JD_W_VD, JD_W_DV = 0, 1
 JD_DRAFT_LOGITS, JD_DRAFT_PROBS = 0, 1
 JD_MODE_JUDGE, JD_MODE_STANDARD = 0, 1
+JD_RULE_SAMPLING, JD_RULE_TOPK = 0, 1
+JD_RESAMPLE_RESIDUAL, JD_RESAMPLE_TARGET = 0, 1
 JD_STATUS_BAD_TOKEN, JD_STATUS_NAN, JD_STATUS_ZERO_RESIDUAL = 1, 2, 4
 JD_K_LMHEAD, JD_K_DRAFTSTAT, JD_K_ACCEPT, JD_K_SAMPLER, JD_NUM_KERNELS = 0, 1, 2, 3, 4
 KERNEL_NAMES = ("lmhead", "draftstat", "accept", "sampler")
@@ -41,6 +43,7 @@ class jd_verify_config(ctypes.Structure):
         ("w_layout", ctypes.c_int32), ("draft_kind", ctypes.c_int32), ("mode", ctypes.c_int32),
         ("temperature", ctypes.c_float), ("delta", ctypes.c_float), ("judge_bias", ctypes.c_float),
         ("device", ctypes.c_int32),
+        ("rule", ctypes.c_int32), ("top_k", ctypes.c_int32), ("resample", ctypes.c_int32),
     ]
 
 
@@ -96,9 +99,11 @@ def strerror(code: int) -> str:
 
 def make_config(d, V, max_B, max_M, *, w_dtype=JD_BF16, emb_dtype=None, w_layout=JD_W_VD,
                 draft_kind=JD_DRAFT_LOGITS, mode=JD_MODE_JUDGE, temperature=1.0, delta=0.5,
-                judge_bias=0.0, device=0) -> jd_verify_config:
+                judge_bias=0.0, device=0, rule=JD_RULE_SAMPLING, top_k=1,
+                resample=JD_RESAMPLE_RESIDUAL) -> jd_verify_config:
     return jd_verify_config(d, V, max_B, max_M, w_dtype, w_dtype if emb_dtype is None else emb_dtype,
-                            w_layout, draft_kind, mode, temperature, delta, judge_bias, device)
+                            w_layout, draft_kind, mode, temperature, delta, judge_bias, device,
+                            rule, top_k, resample)
 
 
 def jd_verify_validate_config(cfg: jd_verify_config) -> int:

@@ -120,6 +120,8 @@ struct AcceptArgs {
   int emb_is_bf16;
   int draft_is_logits, mode_judge;
   int judge_done;          // g[] already holds the judge logits
+  int rule_topk, top_k;    // top-K rule: z_stand = rank(c) < top_k, rank from rankpart
+  const int* rankpart; int nRankSplit;  // [B*M][nRankSplit] partial rank counts
   float judge_threshold;   // logit(delta), +inf for delta == 1
   float judge_bias;
   const float* L; int Lld;             // target logits scratch
@@ -144,6 +146,7 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);
 struct SamplerArgs {
   int B, M, V;
   int draft_is_logits;
+  int resample_target;   // draw the replacement from p itself, not from the residual
   const float* L; int Lld;
   const float* D; int draft_rows;
   const float* uniforms;
@@ -154,6 +157,17 @@ struct SamplerArgs {
 };
 constexpr int kSamplerChunk = 1024;     // tokens per sampler chunk
 hipError_t launch_sampler(const SamplerArgs& a, hipStream_t st);
+
+// Top-K rule (Sec. 5): partial counts of the tokens that rank before the drafted one in its
+// target row (larger logit, or equal logit and lower id): rankpart[(b*M+j)*nSplit + s].
+constexpr int kRankSplits = 16;
+hipError_t launch_rank(const float* L, int Lld, const int32_t* tokens, int B, int M, int V, int* rankpart,
+                       hipStream_t st);
+
+// Greedy new token for the top-K rule: next_token[b] = lowest id attaining the maximum of row
+// accept_len[b] of the target logits.  `chunk_arg` is [B][nChunk] ints of scratch.
+hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const int32_t* accept_len, int B, int M,
+                         int V, int* chunk_arg, int nChunk, int32_t* next_token, hipStream_t st);
 
 // probs[r*V + v] = exp(L[r*Lld + v] - t_max[r]) / t_sum[r]
 hipError_t launch_probs(const float* L, int Lld, const float* t_max, const float* t_sum, int R, int V,

@@ -23,7 +23,8 @@ struct jd_verify_ctx {
   float2* tpart;        // [maxR][nPartT]
   float2* dpart;        // [max_B*max_M][nPartD]
   float* t_max; float* t_sum; float* q_max; float* q_sum; float* g;
-  double* chunk_mass;   // [max_B][nChunk]
+  double* chunk_mass;   // [max_B][nChunk] (the top-K rule reuses it as ints)
+  int* rankpart;        // [max_B*max_M][kRankSplits], top-K rule only
   void* Xp;             // packed embeddings for the GEMM regime
   int nPartT, nPartD, nChunk;
   uint64_t bytes;
@@ -60,10 +61,13 @@ extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
   if (!(c->delta >= 0.5f && c->delta <= 1.0f)) return JD_ERR_INVALID_ARG;
   if (!std::isfinite(c->judge_bias)) return JD_ERR_INVALID_ARG;
   if (c->device < 0) return JD_ERR_INVALID_ARG;
+  if (c->rule != JD_RULE_SAMPLING && c->rule != JD_RULE_TOPK) return JD_ERR_INVALID_ARG;
+  if (c->resample != JD_RESAMPLE_RESIDUAL && c->resample != JD_RESAMPLE_TARGET) return JD_ERR_INVALID_ARG;
   if (c->d <= 0 || c->V <= 0 || c->max_B <= 0 || c->max_M <= 0) return JD_ERR_SHAPE;
   if (c->max_M > 63) return JD_ERR_SHAPE;               // one wave64 ballot covers a sequence
   if (c->V > (1 << 30) || c->d > (1 << 20)) return JD_ERR_SHAPE;
   if ((int64_t)c->max_B * (c->max_M + 1) > (1 << 20)) return JD_ERR_SHAPE;
+  if (c->rule == JD_RULE_TOPK && (c->top_k < 1 || c->top_k > c->V)) return JD_ERR_SHAPE;
   if (c->w_dtype != c->emb_dtype) return JD_ERR_UNSUPPORTED_DTYPE;
   if (c->w_dtype == JD_BF16 && (c->d % 8) != 0) return JD_ERR_SHAPE;  // 128-bit operand loads
   return JD_OK;
@@ -71,7 +75,7 @@ extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
 
 static void free_ctx(jd_verify_ctx* c) {
   if (!c) return;
-  void* ptrs[] = {c->Wp, c->L, c->tpart, c->dpart, c->t_max, c->t_sum, c->q_max, c->q_sum, c->g, c->chunk_mass, c->Xp};
+  void* ptrs[] = {c->Wp, c->L, c->tpart, c->dpart, c->t_max, c->t_sum, c->q_max, c->q_sum, c->g, c->chunk_mass, c->Xp, c->rankpart};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -131,6 +135,7 @@ extern "C" int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm,
   if (rc == JD_OK) rc = dev_alloc(c, &c->q_sum, maxS);
   if (rc == JD_OK) rc = dev_alloc(c, &c->g, maxS);
   if (rc == JD_OK) rc = dev_alloc(c, &c->chunk_mass, (size_t)cfg->max_B * c->nChunk);
+  if (rc == JD_OK && cfg->rule == JD_RULE_TOPK) rc = dev_alloc(c, &c->rankpart, maxS * (size_t)kRankSplits);
   if (rc == JD_OK && bf16) {
     uint8_t* wp = nullptr;
     rc = dev_alloc(c, &wp, c->geo.packed_bytes());
@@ -254,7 +259,10 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
   if (ev) JD_HIP(hipEventRecord(ev[2], st));
 
   // steps 3-6: accept tests, judge, OR, accepted prefix
+  const bool topk = cfg.rule == JD_RULE_TOPK;
+  if (topk) JD_HIP(launch_rank(c->L, g.Vpad, d_draft_tokens, B, M, cfg.V, c->rankpart, st));
   AcceptArgs a;
+  a.rule_topk = topk; a.top_k = cfg.top_k; a.rankpart = c->rankpart; a.nRankSplit = kRankSplits;
   a.B = B; a.M = M; a.d = cfg.d; a.V = cfg.V;
   a.emb_is_bf16 = cfg.emb_dtype == JD_BF16;
   a.draft_is_logits = logits; a.mode_judge = cfg.mode == JD_MODE_JUDGE;
@@ -282,7 +290,13 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
   s.accept_len = out->d_accept_len;
   s.chunk_mass = c->chunk_mass; s.nChunk = c->nChunk;
   s.next_token = out->d_next_token; s.status = out->d_status;
-  JD_HIP(launch_sampler(s, st));
+  s.resample_target = cfg.resample == JD_RESAMPLE_TARGET;
+  if (topk) {
+    JD_HIP(launch_argmax(c->L, g.Vpad, c->t_max, out->d_accept_len, B, M, cfg.V,
+                         reinterpret_cast<int*>(c->chunk_mass), c->nChunk, out->d_next_token, st));
+  } else {
+    JD_HIP(launch_sampler(s, st));
+  }
   if (ev) JD_HIP(hipEventRecord(ev[4], st));
 
   if (out->d_probs) JD_HIP(launch_probs(c->L, g.Vpad, c->t_max, c->t_sum, R, cfg.V, out->d_probs, st));

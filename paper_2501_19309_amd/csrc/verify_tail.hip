@@ -98,7 +98,13 @@ __global__ __launch_bounds__(64) void accept_kernel(AcceptArgs a) {
       p_c = expf(l - tm) / ts;
       const float dv = a.D[((size_t)b * a.draft_rows + j) * a.V + c];
       q_c = a.draft_is_logits ? expf(dv - qm) / qs : dv;
-      zs = a.uniforms[b * Mp1 + j] * q_c < p_c;
+      if (a.rule_topk) {  // Sec. 5: among the top_k most probable tokens of p
+        int rank = 0;
+        for (int s = 0; s < a.nRankSplit; ++s) rank += a.rankpart[(size_t)(b * M + j) * a.nRankSplit + s];
+        zs = rank < a.top_k;
+      } else {
+        zs = a.uniforms[b * Mp1 + j] * q_c < p_c;
+      }
       zj = g > a.judge_threshold;
     } else {
       flags |= 1u;  // bad token id
@@ -157,7 +163,7 @@ __device__ __forceinline__ MassRow make_mass_row(const SamplerArgs& a, int b, bo
   r.l = a.L + (size_t)(b * Mp1 + m) * a.Lld;
   r.tm = a.t_max[b * Mp1 + m];
   r.tinv = 1.f / a.t_sum[b * Mp1 + m];
-  r.use_q = (m < a.M) && !plain;
+  r.use_q = (m < a.M) && !plain && !a.resample_target;
   r.q_is_logits = a.draft_is_logits;
   r.dq = a.D; r.qm = 0.f; r.qinv = 1.f;
   if (m < a.M) {
@@ -240,7 +246,7 @@ __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
 
   double S = total_chunk_mass(cm, a.nChunk, red);
   const bool plain = !(S > 0.0);
-  if (tid == 0 && S == 0.0 && a.accept_len[b] < a.M) atomicOr(&a.status[b], 4u);
+  if (tid == 0 && S == 0.0 && a.accept_len[b] < a.M && !a.resample_target) atomicOr(&a.status[b], 4u);
   if (plain) {
     // No residual mass (q == p at the cut), or NaN: recompute the chunk masses from p itself.
     const MassRow prow = make_mass_row(a, b, true);
@@ -336,6 +342,87 @@ hipError_t launch_sampler(const SamplerArgs& a, hipStream_t st) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(sampler_pick_kernel, dim3(a.B), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------- top-K rule
+
+// grid = (B*M, kRankSplits).  Counts, over one column range of target row j of sequence b, the
+// tokens that rank before the drafted token c: larger logit, or equal logit and lower id.
+__global__ __launch_bounds__(256) void rank_kernel(const float* __restrict__ L, int Lld,
+                                                    const int32_t* __restrict__ tokens, int M, int V, int splitLen,
+                                                    int* __restrict__ rankpart) {
+  __shared__ int red[4];
+  const int slot = blockIdx.x, split = blockIdx.y, tid = threadIdx.x;
+  const int b = slot / M, j = slot % M;
+  const int c = tokens[slot];
+  int cnt = 0;
+  if (c >= 0 && c < V) {
+    const float* row = L + (size_t)(b * (M + 1) + j) * Lld;
+    const float lc = row[c];
+    const int c0 = split * splitLen, c1 = min(V, c0 + splitLen);
+    for (int v = c0 + tid; v < c1; v += 256) {
+      const float l = row[v];
+      cnt += (l > lc) || (l == lc && v < c);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+  if ((tid & 63) == 0) red[tid >> 6] = cnt;
+  __syncthreads();
+  if (tid == 0) rankpart[(size_t)slot * gridDim.y + split] = red[0] + red[1] + red[2] + red[3];
+}
+
+hipError_t launch_rank(const float* L, int Lld, const int32_t* tokens, int B, int M, int V, int* rankpart,
+                       hipStream_t st) {
+  const int splitLen = (V + kRankSplits - 1) / kRankSplits;
+  hipLaunchKernelGGL(rank_kernel, dim3(B * M, kRankSplits), dim3(256), 0, st, L, Lld, tokens, M, V, splitLen,
+                     rankpart);
+  return hipGetLastError();
+}
+
+// grid = (nChunk, B): lowest id in the chunk whose logit equals the row maximum (INT_MAX if none).
+__global__ __launch_bounds__(256) void argmax_chunk_kernel(const float* __restrict__ L, int Lld,
+                                                            const float* __restrict__ t_max,
+                                                            const int32_t* __restrict__ accept_len, int M, int V,
+                                                            int* __restrict__ chunk_arg) {
+  __shared__ int s_min;
+  const int b = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x;
+  const int r = b * (M + 1) + accept_len[b];
+  const float tm = t_max[r];
+  const float* row = L + (size_t)r * Lld;
+  if (tid == 0) s_min = 0x7fffffff;
+  __syncthreads();
+  int cand = 0x7fffffff;
+  const int v0 = chunk * kSamplerChunk + tid * 4;
+#pragma unroll
+  for (int i = 3; i >= 0; --i)
+    if (v0 + i < V && row[v0 + i] == tm) cand = v0 + i;
+  if (cand != 0x7fffffff) atomicMin(&s_min, cand);
+  __syncthreads();
+  if (tid == 0) chunk_arg[(size_t)b * gridDim.x + chunk] = s_min;
+}
+
+__global__ __launch_bounds__(256) void argmax_pick_kernel(const int* __restrict__ chunk_arg, int nChunk,
+                                                           int32_t* __restrict__ next_token) {
+  __shared__ int s_min;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (tid == 0) s_min = 0x7fffffff;
+  __syncthreads();
+  int cand = 0x7fffffff;
+  for (int i = tid; i < nChunk; i += 256) cand = min(cand, chunk_arg[(size_t)b * nChunk + i]);
+  if (cand != 0x7fffffff) atomicMin(&s_min, cand);
+  __syncthreads();
+  if (tid == 0) next_token[b] = (s_min == 0x7fffffff) ? 0 : s_min;  // no finite maximum (NaN row): token 0
+}
+
+hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const int32_t* accept_len, int B, int M,
+                         int V, int* chunk_arg, int nChunk, int32_t* next_token, hipStream_t st) {
+  hipLaunchKernelGGL(argmax_chunk_kernel, dim3(nChunk, B), dim3(256), 0, st, L, Lld, t_max, accept_len, M, V,
+                     chunk_arg);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(argmax_pick_kernel, dim3(B), dim3(256), 0, st, chunk_arg, nChunk, next_token);
   return hipGetLastError();
 }
 

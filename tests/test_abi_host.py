@@ -36,7 +36,7 @@ def test_header_constants_match_binding(repo_root):
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(jb.jd_verify_config) == 13 * 4
+    assert ctypes.sizeof(jb.jd_verify_config) == 16 * 4
     assert ctypes.sizeof(jb.jd_verify_outputs) == 11 * 8
 
 
@@ -57,11 +57,15 @@ def test_validate_config_error_paths(lib):
         assert jb.jd_verify_validate_config(jb.make_config(**kw)) == jb.JD_ERR_SHAPE, kw
     bad_arg = [dict(delta=0.4), dict(delta=1.1), dict(delta=float("nan")), dict(temperature=0.0),
                dict(temperature=-1.0), dict(w_dtype=7), dict(w_layout=2), dict(draft_kind=3), dict(mode=-1),
-               dict(device=-1), dict(judge_bias=float("inf"))]
+               dict(device=-1), dict(judge_bias=float("inf")), dict(rule=2), dict(resample=-1)]
     for kw in bad_arg:
         assert jb.jd_verify_validate_config(jb.make_config(**ok, **kw)) == jb.JD_ERR_INVALID_ARG, kw
     assert jb.jd_verify_validate_config(jb.make_config(**ok, w_dtype=jb.JD_BF16, emb_dtype=jb.JD_F32)) \
         == jb.JD_ERR_UNSUPPORTED_DTYPE
+    for k in (0, -3, 128257):
+        assert jb.jd_verify_validate_config(jb.make_config(**ok, rule=jb.JD_RULE_TOPK, top_k=k)) == jb.JD_ERR_SHAPE
+    assert jb.jd_verify_validate_config(jb.make_config(**ok, rule=jb.JD_RULE_TOPK, top_k=128256)) == jb.JD_OK
+    assert jb.jd_verify_validate_config(jb.make_config(**ok, top_k=0)) == jb.JD_OK  # ignored under Eq. 4
     # fp32 has no 8-element alignment requirement
     assert jb.jd_verify_validate_config(jb.make_config(100, 1000, 1, 5, w_dtype=jb.JD_F32)) == jb.JD_OK
 

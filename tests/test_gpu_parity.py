@@ -172,6 +172,54 @@ def test_probs_draft_and_dv_layout(jd):
             assert np.array_equal(a[k], b[k]), k
 
 
+def test_topk_rule_and_target_resampling(jd):
+    # Sec. 5 top-K verification (K = 1: greedy matching of Sec. 3.2) with greedy replacement, and the
+    # literal "sample from p_i" replacement, against the oracle
+    from paper_2501_19309_amd import binding as jb
+    for kind, V in (("bf16", 3000), ("f32", 700)):
+        shape = VerifyShape("t", 6, 8, 128, V, kind, 0.7)
+        x = make_inputs(shape, 13)
+        for K in (1, 4, 50, V):
+            for mode, vmode in ((jb.JD_MODE_STANDARD, vo.MODE_STANDARD), (jb.JD_MODE_JUDGE, vo.MODE_JUDGE)):
+                got = jd.run_once(x, rule=jb.JD_RULE_TOPK, top_k=K, mode=mode)
+                ref = oracle_for(x, rule=vo.RULE_TOPK, top_k=K, mode=vmode)
+                rep = compare(got, ref, mode_judge=(mode == jb.JD_MODE_JUDGE), rule_topk=True)
+            if K == V:
+                assert got["z_stand"].all()
+        got = jd.run_once(x, resample=jb.JD_RESAMPLE_TARGET, mode=jb.JD_MODE_STANDARD)
+        ref = oracle_for(x, resample=vo.RESAMPLE_TARGET, mode=vo.MODE_STANDARD)
+        compare(got, ref, mode_judge=False)
+        assert (ref["accept_len"] < 8).any()
+    # exact ties: small-integer embeddings and weights give many equal logits; order is by token id
+    rng = np.random.default_rng(3)
+    for kind in ("bf16", "f32"):
+        B, M, d, V = 5, 6, 32, 400
+        emb = rng.integers(-2, 3, size=(B, M + 1, d)).astype(np.float32)
+        W = rng.integers(-1, 2, size=(V, d)).astype(np.float32)
+        Lint = np.einsum("brk,vk->brv", emb, W)                        # exact small integers
+        top = Lint[:, :M].max(-1, keepdims=True)
+        # draft the HIGHEST id among the tokens tied for the row maximum: whether it is accepted
+        # at K = 1 depends only on the tie order (lower id ranks first)
+        toks = (V - 1 - np.argmax((Lint[:, :M] == top)[..., ::-1], axis=-1)).astype(np.int32)
+        assert ((Lint[:, :M] == top).sum(-1) > 1).any()
+        x = {"emb": emb, "W": W, "w_judge": rng.integers(-1, 2, size=d).astype(np.float32),
+             "draft_tokens": toks,
+             "draft_logits": rng.normal(size=(B, M + 1, V)).astype(np.float32),
+             "uniforms": rng.random((B, M + 1)).astype(np.float32)}
+        if kind == "bf16":
+            from synth import bf16_bits_from_f32
+            for k in ("emb", "W", "w_judge"):
+                x[k] = bf16_bits_from_f32(x[k]).reshape(x[k].shape)
+        for K in (1, 3, 40):
+            got = jd.run_once(x, rule=jb.JD_RULE_TOPK, top_k=K, mode=jb.JD_MODE_STANDARD)
+            ref = oracle_for(x, rule=vo.RULE_TOPK, top_k=K, mode=vo.MODE_STANDARD)
+            # logits are exact integers on both sides: no band is needed, everything must agree
+            assert np.array_equal(got["z_stand"], ref["z_stand"]) and np.array_equal(got["accept_len"], ref["accept_len"])
+            assert np.array_equal(got["next_token"], ref["next_token"])
+            if K == 1:                                  # the case really contains ties at the boundary,
+                assert (ref["accept_margin"] == 0).any() and not ref["z_stand"].all()   # decided by token id
+
+
 def test_separate_judge_embedding(jd):
     shape = VerifyShape("t", 3, 6, 256, 900, "bf16", 1.0)
     x = make_inputs(shape, 7)
