@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rule", default="sampling", choices=["sampling", "topk"],
+                    help="acceptance rule: Eq. 4 speculative sampling, or top-K verification (Sec. 5 baseline)")
+    ap.add_argument("--top-k", type=int, default=1)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the timed region, so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
@@ -70,7 +73,8 @@ def main() -> int:
     x = make_inputs(shape, args.seed)
     log(f"[bench] inputs for {shape.name} drawn in {time.time() - t0:.1f}s")
     dev = harness.to_device(x)
-    ver = harness.make_verifier(dev)
+    rule_kw = {} if args.rule == "sampling" else {"rule": jb.JD_RULE_TOPK, "top_k": args.top_k}
+    ver = harness.make_verifier(dev, **rule_kw)
     out = ver.alloc_outputs(B, M)
     torch.cuda.synchronize()
     log(f"[bench] context ready, workspace {ver.workspace_bytes() / 2**30:.2f} GiB")
@@ -144,6 +148,7 @@ def main() -> int:
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": f"{shape.name}: B={B} M={M} (+1 bonus row) d={d} V={V} {shape.dtype} W_lm, "
                                f"fp32 draft logits; {shape.note}", "seed": args.seed,
+                   "rule": args.rule if args.rule == "sampling" else f"topk(K={args.top_k})",
                    "rows": R, "W_lm_bytes": w_bytes,
                    "W_lm_retiled_copy": shape.dtype == "bf16"},
         "roofline": roofline,
@@ -165,8 +170,9 @@ def main() -> int:
         # bounded sample: whole call when B == 1, else the first sequences up to ~26 rows
         seqs = list(range(B)) if R <= 32 else list(range(max(1, 26 // (M + 1))))
         t0 = time.perf_counter()
+        okw = {} if args.rule == "sampling" else {"rule": vo.RULE_TOPK, "top_k": args.top_k}
         ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
-                        seqs=seqs)
+                        seqs=seqs, **okw)
         t_cpu = time.perf_counter() - t0
         record["cpu_baseline"] = {
             "value": len(seqs) * M / t_cpu, "unit": "positions/s", "cores": min(cores, blas_threads),
@@ -176,7 +182,7 @@ def main() -> int:
         }
         sub = {k: v[seqs] for k, v in got.items()}
         try:
-            rep = compare(sub, ref)
+            rep = compare(sub, ref, rule_topk=(args.rule == "topk"))
             record["parity"] = {"ok": True, **{k: v for k, v in rep.items()}}
         except AssertionError as e:
             record["parity"] = {"ok": False, "error": str(e)[:300]}
