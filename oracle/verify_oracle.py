@@ -37,6 +37,11 @@ Readings taken where the paper is silent (each is listed in the design notes):
     next = min{ v : cumsum(res)[v] > u_s * sum(res) };
   * token ids outside [0, V) reject the slot and raise a status bit.
 
+8-bit weights (the paper runs its targets with 8-bit weights: Table 1, App. B.3): ``W`` may hold FP8
+E4M3 codes (uint8, the OCP "e4m3fn" format: 4 exponent bits with bias 7, 3 mantissa bits, no
+infinities, 0x7f / 0xff = NaN) with one float32 scale per vocabulary entry; the effective weight is
+scale[v] * decode(code), exactly, and everything downstream is unchanged.
+
 Variants of the rule that the paper itself uses (selected by ``rule`` / ``resample``):
   * top-K verification, the training-free baseline of Sec. 5: c is accepted iff it is among
     the K most probable tokens of p (K = V accepts every draft token, K = 1 is greedy
@@ -79,9 +84,30 @@ _W_CHUNK_ROWS = 2048  # vocabulary rows widened to float64 at a time (memory bou
 
 # --------------------------------------------------------------------------- helpers
 
+def _e4m3fn_table() -> np.ndarray:
+    """The 256 values of the FP8 E4M3 ("fn") format, written out from its definition."""
+    t = np.empty(256, dtype=np.float64)
+    for code in range(256):
+        sign = -1.0 if code & 0x80 else 1.0
+        e, m = (code >> 3) & 0xF, code & 0x7
+        if e == 0xF and m == 0x7:
+            t[code] = np.nan
+        elif e == 0:
+            t[code] = sign * m * 2.0 ** -9            # subnormal: (m / 8) * 2^(1 - 7)
+        else:
+            t[code] = sign * (1.0 + m / 8.0) * 2.0 ** (e - 7)
+    return t
+
+
+E4M3FN = _e4m3fn_table()
+
+
 def widen(x: np.ndarray) -> np.ndarray:
-    """Exact float64 view of an input tensor: uint16 arrays are bf16 bit patterns."""
+    """Exact float64 view of an input tensor: uint16 arrays are bf16 bit patterns, uint8 arrays
+    are FP8 E4M3 codes."""
     x = np.asarray(x)
+    if x.dtype == np.uint8:
+        return E4M3FN[x]
     if x.dtype == np.uint16:
         return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     if x.dtype in (np.float32, np.float64):
@@ -107,8 +133,8 @@ def softmax_rows(L: np.ndarray):
 
 
 def target_logits(emb_rows: np.ndarray, W: np.ndarray, temperature: float = 1.0,
-                  w_layout: str = "vd") -> np.ndarray:
-    """L[r, v] = sum_k x[r, k] * W[k, v] / T in float64.
+                  w_layout: str = "vd", w_scale: Optional[np.ndarray] = None) -> np.ndarray:
+    """L[r, v] = sum_k x[r, k] * W[k, v] / T in float64 (W[k, v] scaled by w_scale[v] if given).
 
     ``W`` is stored [V, d] ("vd": row v is the vocabulary entry v) or [d, V] ("dv").
     The product is formed vocabulary-chunk by vocabulary-chunk only so that the
@@ -127,6 +153,8 @@ def target_logits(emb_rows: np.ndarray, W: np.ndarray, temperature: float = 1.0,
         v1 = min(V, v0 + _W_CHUNK_ROWS)
         Wc = widen(W[v0:v1]) if w_layout == "vd" else widen(W[:, v0:v1]).T
         L[:, v0:v1] = X @ Wc.T
+    if w_scale is not None:
+        L *= np.asarray(w_scale, dtype=np.float64)[None, :]
     if temperature != 1.0:
         L /= float(temperature)
     return L
@@ -217,11 +245,12 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
            temperature: float = 1.0, delta: float = 0.5, judge_bias: float = 0.0,
            w_layout: str = "vd", seqs: Optional[Iterable[int]] = None,
            return_probs: bool = False, rule: int = RULE_SAMPLING, top_k: int = 1,
-           resample: int = RESAMPLE_RESIDUAL) -> Dict[str, np.ndarray]:
+           resample: int = RESAMPLE_RESIDUAL, w_scale: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """Verify one batch of drafts.  See the module docstring for the steps.
 
     emb          [B, M+1, d]  LM-head input (bf16 bits as uint16, or float32)
-    W            [V, d] / [d, V]
+    W            [V, d] / [d, V]  (float32, bf16 bits as uint16, or FP8 E4M3 codes as uint8)
+    w_scale      [V] float32 per-vocabulary-entry scale of W (None = 1), meant for FP8 weights
     w_judge      [d]
     draft_tokens [B, M] int
     draft        [B, rows >= M, V] float32 logits or probabilities (rows beyond M unused)
@@ -262,7 +291,7 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
         out["probs"] = np.zeros((nb, M + 1, V))
 
     # step 1 for all selected rows at once (one float64 matmul per vocabulary chunk)
-    L_all = target_logits(emb[seq_ids].reshape(nb * (M + 1), d), W, temperature, w_layout)
+    L_all = target_logits(emb[seq_ids].reshape(nb * (M + 1), d), W, temperature, w_layout, w_scale)
     L_all = L_all.reshape(nb, M + 1, V)
 
     for i, b in enumerate(seq_ids):

@@ -1,8 +1,8 @@
 """Seeded synthetic workloads shaped like the paper's Llama-3.1 target models.
 
 The paper evaluates Llama-3.1-8B drafting for Llama-3.1-70B / 405B targets
-(Sec. 4.2, Table 1; judge width 8192 / 16384 in App. B.1; M = 25 judge drafts and
-M = 10 standard drafts in Sec. 4.2).  None of those weights or prompts exist here,
+(Sec. 5, Table 1; judge width 8192 / 16384 in App. B.1; M = 25 judge drafts and
+M = 10 standard drafts in Sec. 5; 8-bit target weights in Table 1 and App. B.3).  None of those weights or prompts exist here,
 so these generators stand in for them: same shapes, Gaussian statistics chosen so
 that logits have unit variance and the draft is a noisy copy of the target.
 
@@ -12,9 +12,10 @@ vocabulary chunk), so chunks can be drawn in parallel threads and the result doe
 not depend on the thread count.
 
 Nothing in this file is part of the verification method: the only arithmetic is
-drawing numbers, rounding to bf16, one single-precision matmul to make the draft
-logits a perturbed copy of the target logits, and a Gumbel arg-max to draw the
-draft tokens from the draft distribution.
+drawing numbers, rounding to bf16 (or quantising the drawn weights to FP8 E4M3 with
+one scale per row), one single-precision matmul to make the draft logits a perturbed
+copy of the target logits, and a Gumbel arg-max to draw the draft tokens from the
+draft distribution.
 """
 
 from __future__ import annotations
@@ -41,7 +42,8 @@ class VerifyShape:
     M: int
     d: int
     V: int
-    dtype: str  # "f32" | "bf16": storage type of embeddings, W_lm and w_judge
+    dtype: str  # "f32" | "bf16": storage type of embeddings, W_lm and w_judge;
+                # "fp8": bf16 embeddings and w_judge, W_lm as FP8 E4M3 codes + one fp32 scale per row
     noise: Union[float, Tuple[float, float]]  # std of draft-logit noise, or U(lo, hi) per sequence
     note: str = ""
 
@@ -56,6 +58,10 @@ CONFIGS: Dict[str, VerifyShape] = {
     "C3": VerifyShape("C3", 1, 25, 8192, 128256, "bf16", 1.0, "Llama-3.1-70B-shaped head, long drafts"),
     "C4": VerifyShape("C4", 1, 25, 16384, 128256, "bf16", 2.0, "Llama-3.1-405B-shaped head (headline, HBM bound)"),
     "C5": VerifyShape("C5", 64, 10, 8192, 128256, "bf16", (0.5, 2.5), "batched verification (MFMA bound)"),
+    # 8-bit weight variants (the paper's runs quantise the target to 8 bits): same shapes, FP8 E4M3 W_lm
+    "C2q": VerifyShape("C2q", 1, 5, 4096, 128256, "fp8", 1.5, "Llama-3.1-8B-shaped head, FP8 W_lm"),
+    "C3q": VerifyShape("C3q", 1, 25, 8192, 128256, "fp8", 1.0, "Llama-3.1-70B-shaped head, FP8 W_lm"),
+    "C4q": VerifyShape("C4q", 1, 25, 16384, 128256, "fp8", 2.0, "Llama-3.1-405B-shaped head, FP8 W_lm"),
 }
 
 
@@ -69,6 +75,34 @@ def bf16_bits_from_f32(x: np.ndarray) -> np.ndarray:
 def f32_from_bf16_bits(b: np.ndarray) -> np.ndarray:
     """Widen bfloat16 bit patterns to float32 (exact)."""
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _e4m3fn_positive_values() -> np.ndarray:
+    """The 127 finite non-negative FP8 E4M3 ("fn") values, code order (code = index)."""
+    vals = []
+    for code in range(127):
+        e, m = (code >> 3) & 0xF, code & 0x7
+        vals.append(m * 2.0 ** -9 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7))
+    return np.asarray(vals, dtype=np.float32)
+
+
+_E4M3_POS = _e4m3fn_positive_values()
+_E4M3_MID = ((_E4M3_POS[:-1].astype(np.float64) + _E4M3_POS[1:].astype(np.float64)) / 2).astype(np.float32)
+
+
+def fp8_e4m3_quantize_rows(w: np.ndarray):
+    """Per-row symmetric quantisation of float32 rows to FP8 E4M3 codes.
+
+    scale[v] = max|w[v,:]| / 448 (float32); code = nearest representable value of w / scale.
+    Returns (codes uint8 [rows, d], scale float32 [rows], dequantised float32 [rows, d]).
+    """
+    amax = np.max(np.abs(w), axis=1).astype(np.float32)
+    scale = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    q = w / scale[:, None]
+    mag = np.searchsorted(_E4M3_MID, np.abs(q)).astype(np.uint8)      # nearest code of |q| (0..126)
+    codes = mag | (np.signbit(q).astype(np.uint8) << 7)
+    deq = _E4M3_POS[mag] * np.where(np.signbit(q), np.float32(-1), np.float32(1)) * scale[:, None]
+    return codes, scale, deq.astype(np.float32)
 
 
 def _stream(seed: int, tag: int, chunk: int = 0) -> np.random.Generator:
@@ -88,7 +122,8 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
 
     Returns a dict with
       emb           [B, M+1, d]  float32, or uint16 bf16 bit patterns
-      W             [V, d]       same storage type; row v is vocabulary entry v (K contiguous)
+      W             [V, d]       same storage type; row v is vocabulary entry v (K contiguous);
+                                 for dtype "fp8": uint8 FP8 E4M3 codes, plus  w_scale [V] float32
       w_judge       [d]          same storage type
       draft_logits  [B, M+1, V]  float32 (row M is present but unused by verification)
       draft_tokens  [B, M]       int32, token j drawn from softmax(draft_logits[:, j])
@@ -96,8 +131,9 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
     """
     B, M, d, V = shape.B, shape.M, shape.d, shape.V
     R = B * (M + 1)
-    is_bf16 = shape.dtype == "bf16"
-    if shape.dtype not in ("f32", "bf16"):
+    is_fp8 = shape.dtype == "fp8"
+    is_bf16 = shape.dtype == "bf16" or is_fp8   # storage of embeddings and w_judge
+    if shape.dtype not in ("f32", "bf16", "fp8"):
         raise ValueError(f"unknown dtype {shape.dtype!r}")
 
     # embeddings: N(0,1), each row rescaled to unit rms, then stored
@@ -119,7 +155,8 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
         sigma_b = np.full(B, shape.noise, dtype=np.float32)
     sigma_r = np.repeat(sigma_b, M + 1)[:, None]  # [R, 1]
 
-    W_store = np.empty((V, d), dtype=np.uint16 if is_bf16 else np.float32)
+    W_store = np.empty((V, d), dtype=np.uint8 if is_fp8 else (np.uint16 if is_bf16 else np.float32))
+    W_scale = np.ones(V, dtype=np.float32)
     D = np.empty((R, V), dtype=np.float32)
     best_val = np.full(R, -np.inf, dtype=np.float32)
     best_idx = np.zeros(R, dtype=np.int64)
@@ -130,10 +167,13 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
         rows = min(_VOCAB_CHUNK, V - v0)
         w = _stream(seed, _TAG_W, ci).standard_normal((rows, d), dtype=np.float32)
         w *= inv_sqrt_d
-        w_bits = bf16_bits_from_f32(w) if is_bf16 else None
         noise = _stream(seed, _TAG_NOISE, ci).standard_normal((R, rows), dtype=np.float32)
         gumbel = _stream(seed, _TAG_GUMBEL, ci).gumbel(size=(R, rows)).astype(np.float32)
-        return ci, (w_bits if is_bf16 else w), noise, gumbel
+        if is_fp8:
+            codes, scale, deq = fp8_e4m3_quantize_rows(w)
+            return ci, codes, noise, gumbel, scale, deq
+        w_bits = bf16_bits_from_f32(w) if is_bf16 else None
+        return ci, (w_bits if is_bf16 else w), noise, gumbel, None, None
 
     n_chunks = (V + _VOCAB_CHUNK - 1) // _VOCAB_CHUNK
     nthreads = _n_threads()
@@ -150,12 +190,16 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
 
         top_up()
         while pending:
-            ci, w_chunk, noise, gumbel = pending.pop(0).result()
+            ci, w_chunk, noise, gumbel, scale, deq = pending.pop(0).result()
             top_up()
             v0 = ci * _VOCAB_CHUNK
             rows = w_chunk.shape[0]
             W_store[v0:v0 + rows] = w_chunk
-            w32 = f32_from_bf16_bits(w_chunk) if is_bf16 else w_chunk
+            if is_fp8:
+                W_scale[v0:v0 + rows] = scale
+                w32 = deq
+            else:
+                w32 = f32_from_bf16_bits(w_chunk) if is_bf16 else w_chunk
             # draft logits = (single-precision) target logits + Gaussian noise
             Dc = h @ w32.T
             Dc += sigma_r * noise
@@ -171,7 +215,7 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
     tokens = best_idx.reshape(B, M + 1)[:, :M].astype(np.int32)
     uniforms = _stream(seed, _TAG_UNIF).random((B, M + 1), dtype=np.float32)
 
-    return {
+    out = {
         "emb": emb_store.reshape(B, M + 1, d),
         "W": W_store,
         "w_judge": wj_store,
@@ -180,3 +224,6 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
         "uniforms": uniforms,
         "sigma_b": sigma_b,
     }
+    if is_fp8:
+        out["w_scale"] = W_scale
+    return out

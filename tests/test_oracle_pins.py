@@ -570,3 +570,39 @@ def test_resample_from_target_reading():
         assert int(tgt["next_token"][b]) == want
     assert (res["next_token"] != tgt["next_token"]).any()
     assert (tgt["status"] == 0).all()
+
+
+# ----------------------------------------------------------------------------- FP8 weights
+
+def test_fp8_e4m3_decode_table():
+    t = vo.E4M3FN
+    # values fixed by the format: bias 7, 3 mantissa bits, no infinities, max 448
+    known = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0, 0x3C: 1.5, 0x40: 2.0,
+             0x7E: 448.0, 0xB8: -1.0, 0xFE: -448.0, 0x30: 0.5, 0x39: 1.125}
+    for code, val in known.items():
+        assert t[code] == val, hex(code)
+    assert np.isnan(t[0x7F]) and np.isnan(t[0xFF]) and np.isfinite(t[:0x7F]).all()
+    assert (np.diff(t[:0x7F]) > 0).all() and np.array_equal(t[0x80:0xFF], -t[0x00:0x7F])
+    # independent library decode
+    import torch
+    ref = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.nan_to_num(ref, nan=-7.0), np.nan_to_num(t, nan=-7.0))
+    # every finite code is exactly representable in bf16 (what the kernel converts to)
+    f32 = t[np.isfinite(t)].astype(np.float32)
+    assert np.array_equal(f32.view(np.uint32) & 0xFFFF, np.zeros(f32.size, dtype=np.uint32))
+
+
+def test_fp8_weights_are_scaled_rows():
+    from synth import CONFIGS
+    shape = VerifyShape("t", 2, 4, 64, 300, "fp8", 1.0)
+    x = make_inputs(shape, 1)
+    assert x["W"].dtype == np.uint8 and x["w_scale"].shape == (300,) and x["emb"].dtype == np.uint16
+    Weff = vo.E4M3FN[x["W"]] * x["w_scale"][:, None].astype(np.float64)
+    X = vo.widen(x["emb"]).reshape(-1, 64)
+    got = vo.target_logits(x["emb"].reshape(-1, 64), x["W"], w_scale=x["w_scale"])
+    assert np.allclose(got, X @ Weff.T, rtol=1e-13, atol=1e-13)
+    # quantisation error of the generator is what E4M3 allows: half a mantissa step at most
+    out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+                    w_scale=x["w_scale"])
+    assert (out["status"] == 0).all()
+    assert {"C2q", "C3q", "C4q"} <= set(CONFIGS)
