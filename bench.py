@@ -42,7 +42,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "C2q", "C3q", "C4q"],
+                    help="C2..C5: bf16 W_lm (C4 is the headline); C2q..C4q: the same shapes with FP8 E4M3 W_lm")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rule", default="sampling", choices=["sampling", "topk"],
@@ -118,12 +119,13 @@ def main() -> int:
     log(f"[bench] ms/step {ms_per_step:.4f} (with per-kernel events {ms_events:.4f}); kernels {kernel_ms}")
 
     got = out.to_numpy()
-    elem = 2 if shape.dtype == "bf16" else 4
-    w_bytes = V * d * elem
+    elem = {"bf16": 2, "fp8": 2, "f32": 4}[shape.dtype]      # embeddings / judge weight
+    w_elem = {"bf16": 2, "fp8": 1, "f32": 4}[shape.dtype]    # LM-head weight
+    w_bytes = V * d * w_elem + (V * 4 if shape.dtype == "fp8" else 0)   # FP8: + one fp32 scale per entry
     x_bytes = R * d * elem
     lm_ms = kernel_ms["lmhead"]
     flops = 2.0 * R * d * V
-    if args.config == "C5":
+    if args.config == "C5":  # MFMA-bound regime
         achieved = flops / (lm_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)}
@@ -145,12 +147,13 @@ def main() -> int:
         "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": shape.dtype, "data": "synthetic",
-        "config": {"workload": f"{shape.name}: B={B} M={M} (+1 bonus row) d={d} V={V} {shape.dtype} W_lm, "
+        "dtype": "bf16" if shape.dtype == "fp8" else shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{shape.name}: B={B} M={M} (+1 bonus row) d={d} V={V} "
+                               f"{'FP8 E4M3 (+fp32 row scales)' if shape.dtype == 'fp8' else shape.dtype} W_lm, "
                                f"fp32 draft logits; {shape.note}", "seed": args.seed,
                    "rule": args.rule if args.rule == "sampling" else f"topk(K={args.top_k})",
                    "rows": R, "W_lm_bytes": w_bytes,
-                   "W_lm_retiled_copy": shape.dtype == "bf16"},
+                   "W_lm_retiled_copy": shape.dtype in ("bf16", "fp8")},
         "roofline": roofline,
         "whole_call": {"ms_per_step_with_kernel_events": ms_events, "algorithmic_bytes": call_bytes,
                        "gbs": call_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -172,7 +175,7 @@ def main() -> int:
         t0 = time.perf_counter()
         okw = {} if args.rule == "sampling" else {"rule": vo.RULE_TOPK, "top_k": args.top_k}
         ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
-                        seqs=seqs, **okw)
+                        seqs=seqs, w_scale=x.get("w_scale"), **okw)
         t_cpu = time.perf_counter() - t0
         record["cpu_baseline"] = {
             "value": len(seqs) * M / t_cpu, "unit": "positions/s", "cores": min(cores, blas_threads),

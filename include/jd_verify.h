@@ -48,6 +48,9 @@ extern "C" {
 /* ---- enums ----------------------------------------------------------------------- */
 #define JD_F32   0                    /* IEEE binary32                                                */
 #define JD_BF16  1                    /* bfloat16, 2 bytes                                            */
+#define JD_FP8_E4M3 2                 /* W_lm only: OCP FP8 E4M3 ("e4m3fn") codes, 1 byte, with one   */
+                                      /* fp32 scale per vocabulary entry (jd_verify_create_scaled);   */
+                                      /* the paper runs its targets with 8-bit weights (Table 1)      */
 
 #define JD_W_VD  0                    /* W_lm stored [V][d]: row v = vocabulary entry v (checkpoint)  */
 #define JD_W_DV  1                    /* W_lm stored [d][V]                                           */
@@ -83,7 +86,8 @@ typedef struct jd_verify_ctx jd_verify_ctx;   /* opaque, owned by the library */
 typedef struct {
   int32_t d, V;                 /* hidden size, vocabulary size                                       */
   int32_t max_B, max_M;         /* workspace is sized for these; 1 <= max_M <= 63                     */
-  int32_t w_dtype, emb_dtype;   /* JD_F32 | JD_BF16; must be equal (w_judge has the same type)        */
+  int32_t w_dtype, emb_dtype;   /* JD_F32 | JD_BF16, equal; or w_dtype JD_FP8_E4M3 with emb_dtype JD_BF16 */
+                                /* (w_judge always has emb_dtype)                                      */
   int32_t w_layout;             /* JD_W_VD | JD_W_DV                                                  */
   int32_t draft_kind;           /* JD_DRAFT_LOGITS | JD_DRAFT_PROBS                                   */
   int32_t mode;                 /* JD_MODE_JUDGE | JD_MODE_STANDARD                                   */
@@ -121,6 +125,18 @@ typedef struct {                /* device pointers; the first three are required
  */
 int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void* d_w_judge,
                      jd_verify_ctx** out_ctx);
+
+/*
+ * Same as jd_verify_create for quantised weights (w_dtype JD_FP8_E4M3; the paper's targets run with
+ * 8-bit weights, Table 1 / App. B.3): the effective LM head is W[v,:] = d_w_scale[v] * decode(code[v,:]).
+ *   d_w_scale   [V] fp32 device pointer, borrowed for the lifetime of the context; NULL means all ones.
+ *               Must be NULL for JD_F32 / JD_BF16 weights (INVALID_ARG otherwise).
+ * The library builds a re-tiled FP8 copy (V*d bytes) for the small-row regime and, if
+ * max_B*(max_M+1) > 64, a re-tiled bf16 copy (exact conversion) for the large-row regime.
+ * d must be a multiple of 16.  Other errors as jd_verify_create.
+ */
+int jd_verify_create_scaled(const jd_verify_config* cfg, const void* d_W_lm, const float* d_w_scale,
+                            const void* d_w_judge, jd_verify_ctx** out_ctx);
 
 /*
  * Verify one batch (steps 1-7 above).  1 <= B <= max_B, 1 <= M <= max_M.

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libjdverify.so")
 
 JD_OK = 0
 JD_ERR_INVALID_ARG, JD_ERR_SHAPE, JD_ERR_UNSUPPORTED_DTYPE, JD_ERR_OOM, JD_ERR_HIP = -1, -2, -3, -4, -5
-JD_F32, JD_BF16 = 0, 1
+JD_F32, JD_BF16, JD_FP8_E4M3 = 0, 1, 2
 JD_W_VD, JD_W_DV = 0, 1
 JD_DRAFT_LOGITS, JD_DRAFT_PROBS = 0, 1
 JD_MODE_JUDGE, JD_MODE_STANDARD = 0, 1
@@ -29,7 +29,7 @@ JD_K_LMHEAD, JD_K_DRAFTSTAT, JD_K_ACCEPT, JD_K_SAMPLER, JD_NUM_KERNELS = 0, 1, 2
 KERNEL_NAMES = ("lmhead", "draftstat", "accept", "sampler")
 
 EXPORTED_SYMBOLS = (
-    "jd_verify_create", "jd_verify_run", "jd_verify_destroy", "jd_verify_strerror",
+    "jd_verify_create", "jd_verify_create_scaled", "jd_verify_run", "jd_verify_destroy", "jd_verify_strerror",
     "jd_verify_profile_begin", "jd_verify_profile_end", "jd_verify_workspace_bytes",
     "jd_verify_validate_config",
 )
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     vp, i32 = ctypes.c_void_p, ctypes.c_int32
     lib.jd_verify_create.argtypes = [ctypes.POINTER(jd_verify_config), vp, vp, ctypes.POINTER(vp)]
     lib.jd_verify_create.restype = ctypes.c_int
+    lib.jd_verify_create_scaled.argtypes = [ctypes.POINTER(jd_verify_config), vp, vp, vp, ctypes.POINTER(vp)]
+    lib.jd_verify_create_scaled.restype = ctypes.c_int
     lib.jd_verify_run.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, vp, ctypes.POINTER(jd_verify_outputs), vp]
     lib.jd_verify_run.restype = ctypes.c_int
     lib.jd_verify_destroy.argtypes = [vp]
@@ -101,7 +103,9 @@ def make_config(d, V, max_B, max_M, *, w_dtype=JD_BF16, emb_dtype=None, w_layout
                 draft_kind=JD_DRAFT_LOGITS, mode=JD_MODE_JUDGE, temperature=1.0, delta=0.5,
                 judge_bias=0.0, device=0, rule=JD_RULE_SAMPLING, top_k=1,
                 resample=JD_RESAMPLE_RESIDUAL) -> jd_verify_config:
-    return jd_verify_config(d, V, max_B, max_M, w_dtype, w_dtype if emb_dtype is None else emb_dtype,
+    if emb_dtype is None:
+        emb_dtype = JD_BF16 if w_dtype == JD_FP8_E4M3 else w_dtype
+    return jd_verify_config(d, V, max_B, max_M, w_dtype, emb_dtype,
                             w_layout, draft_kind, mode, temperature, delta, judge_bias, device,
                             rule, top_k, resample)
 
@@ -140,15 +144,19 @@ class VerifyOutputs:
 class JDVerify:
     """Owner of one jd_verify_ctx.  Tensors are torch CUDA(HIP) tensors."""
 
-    def __init__(self, cfg: jd_verify_config, W_lm, w_judge):
+    def __init__(self, cfg: jd_verify_config, W_lm, w_judge, w_scale=None):
         import torch  # device memory and streams only
 
         self._torch = torch
         self.lib = load_library()
         self.cfg = cfg
-        self._keep = (W_lm, w_judge)  # borrowed by the library until destroy
+        self._keep = (W_lm, w_judge, w_scale)  # borrowed by the library until destroy
         handle = ctypes.c_void_p()
-        rc = self.lib.jd_verify_create(ctypes.byref(cfg), _ptr(W_lm), _ptr(w_judge), ctypes.byref(handle))
+        if w_scale is None:
+            rc = self.lib.jd_verify_create(ctypes.byref(cfg), _ptr(W_lm), _ptr(w_judge), ctypes.byref(handle))
+        else:
+            rc = self.lib.jd_verify_create_scaled(ctypes.byref(cfg), _ptr(W_lm), _ptr(w_scale), _ptr(w_judge),
+                                                  ctypes.byref(handle))
         if rc != JD_OK:
             raise JDError(rc, "jd_verify_create")
         self.handle = handle

@@ -54,6 +54,7 @@ struct Geometry {
   int nVG;       // Vpad / 64
   int nVGalloc;  // nVG rounded up to kGroupAlloc (zero-filled tail groups)
   size_t packed_bytes() const { return (size_t)nVGalloc * kVocabGroup * (size_t)dpad * 2; }
+  size_t packed8_bytes() const { return (size_t)nVGalloc * kVocabGroup * (size_t)dpad; }
 };
 
 inline Geometry make_geometry(int d, int V) {
@@ -64,6 +65,28 @@ inline Geometry make_geometry(int d, int V) {
   g.nVG = g.Vpad / kVocabGroup;
   g.nVGalloc = round_up(g.nVG, kGroupAlloc);
   return g;
+}
+
+// ---- packed FP8 W_lm --------------------------------------------------------------
+// FP8 E4M3 weights (one byte per weight, one fp32 scale per vocabulary entry) are re-tiled into
+//
+//   Wp8[ks / 8][vg][(ks % 8) / 2][sub][lane][16]      (bytes)
+//
+// where the 16 bytes of a lane are its eight codes for K step 2*kp (hidden indices
+// (2kp)*32 + (lane/16)*8 + 0..7) followed by its eight codes for K step 2*kp+1: one 128-bit load
+// feeds the MFMA A operands of two K steps after conversion to bf16 (exact: every E4M3 value
+// is a bf16 value).  Eight K steps are adjacent per group so that a wavefront still reads 16 KiB
+// of consecutive memory, as in the bf16 layout.
+constexpr int kW8KG = 8;  // K steps kept adjacent per group in Wp8
+__host__ __device__ __forceinline__ size_t wp8_group_offset(int vg) { return (size_t)vg * (kW8KG / 2 * 256); }
+__host__ __device__ __forceinline__ size_t wp8_pair_offset(int kp, int nVGalloc) {
+  return (size_t)(kp / (kW8KG / 2)) * nVGalloc * (kW8KG / 2 * 256) + (size_t)(kp % (kW8KG / 2)) * 256;
+}
+__host__ __device__ __forceinline__ void wp8_decode(size_t blk, int nVGalloc, int* vg, int* kp) {
+  const int s = (int)(blk % (kW8KG / 2));
+  const size_t t = blk / (kW8KG / 2);
+  *vg = (int)(t % (size_t)nVGalloc);
+  *kp = (int)(t / (size_t)nVGalloc) * (kW8KG / 2) + s;
 }
 
 // ---- work that can ride beside the LM head -------------------------------------------
@@ -83,15 +106,21 @@ RowStatsArgs make_rowstats_args(const float* base, int rowsUsed, size_t seqStrid
 
 // ---- launchers (all asynchronous on `st`) -----------------------------------------
 
-// Re-tile bf16 W_lm ([V][d] if layout==0, [d][V] if layout==1) into Wp, zero padded.
-hipError_t launch_pack_w(const void* W, int layout, const Geometry& g, void* Wp, hipStream_t st);
+// Re-tile W_lm ([V][d] if layout==0, [d][V] if layout==1) into bf16 Wp, zero padded.  The source
+// holds bf16 values, or (src_fp8) FP8 E4M3 codes that are converted exactly.
+hipError_t launch_pack_w(const void* W, int layout, int src_fp8, const Geometry& g, void* Wp, hipStream_t st);
+
+// Re-tile FP8 E4M3 W_lm into Wp8 (see above), zero padded.
+hipError_t launch_pack_w8(const void* W8, int layout, const Geometry& g, void* Wp8, hipStream_t st);
 
 // Small-row regime LM head (R <= 64): streams Wp once, MFMA, writes fp32 logits
 // L[r*Lld + v] = (x_r . w_v) * invT for r < R, v < Vpad, and one softmax partial
 // (max, sum exp) per (row, vocabulary group): part[r*nVG + vg].
 // `side` (may be empty) is executed by extra workgroups of the same launch.
-hipError_t launch_lmhead_skinny(const void* Wp, const void* X, int R, const Geometry& g, float invT,
-                                float* L, float2* part, const SideWork& side, hipStream_t st);
+// w_fp8: Wp is Wp8; vscale (fp32 per vocabulary entry, or NULL = 1) multiplies the logits.
+hipError_t launch_lmhead_skinny(const void* Wp, int w_fp8, const float* vscale, const void* X, int R,
+                                const Geometry& g, float invT, float* L, float2* part, const SideWork& side,
+                                hipStream_t st);
 
 // Large-row regime LM head (R > 64): row tiles of kGemmRows rows x 256 vocabulary entries per
 // workgroup; same outputs as the skinny launcher.  Xp is scratch for the re-tiled embeddings,
@@ -102,8 +131,8 @@ constexpr int kGemmKChunk = 128;                   // hidden indices per LDS-sta
 inline size_t gemm_xp_bytes(int R, const Geometry& g) {
   return (size_t)((R + kGemmRows - 1) / kGemmRows) * kGemmRows * (size_t)g.dpad * 2;
 }
-hipError_t launch_lmhead_gemm(const void* Wp, const void* X, int R, const Geometry& g, float invT,
-                              float* L, float2* part, void* Xp, int num_cus, hipStream_t st);
+hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
+                              float invT, float* L, float2* part, void* Xp, int num_cus, hipStream_t st);
 
 // fp32 LM head (any layout), plain FMA; writes logits only.
 hipError_t launch_lmhead_f32(const float* W, int layout, const float* X, int R, int d, int V, float invT,

@@ -18,7 +18,9 @@ struct jd_verify_ctx {
   int num_cus;
   const void* W;
   const void* wj;
-  void* Wp;             // re-tiled bf16 weights (bf16 path only)
+  void* Wp;             // re-tiled bf16 weights (bf16 path; FP8 path only for the large-row regime)
+  void* Wp8;            // re-tiled FP8 weights (FP8 path)
+  const float* wscale;  // per-vocabulary-entry weight scale (FP8 path, may be NULL)
   float* L;             // [maxR][Vpad] fp32 logits
   float2* tpart;        // [maxR][nPartT]
   float2* dpart;        // [max_B*max_M][nPartD]
@@ -52,7 +54,7 @@ extern "C" const char* jd_verify_strerror(int code) {
 
 extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
   if (!c) return JD_ERR_INVALID_ARG;
-  if (c->w_dtype != JD_F32 && c->w_dtype != JD_BF16) return JD_ERR_INVALID_ARG;
+  if (c->w_dtype != JD_F32 && c->w_dtype != JD_BF16 && c->w_dtype != JD_FP8_E4M3) return JD_ERR_INVALID_ARG;
   if (c->emb_dtype != JD_F32 && c->emb_dtype != JD_BF16) return JD_ERR_INVALID_ARG;
   if (c->w_layout != JD_W_VD && c->w_layout != JD_W_DV) return JD_ERR_INVALID_ARG;
   if (c->draft_kind != JD_DRAFT_LOGITS && c->draft_kind != JD_DRAFT_PROBS) return JD_ERR_INVALID_ARG;
@@ -68,14 +70,19 @@ extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
   if (c->V > (1 << 30) || c->d > (1 << 20)) return JD_ERR_SHAPE;
   if ((int64_t)c->max_B * (c->max_M + 1) > (1 << 20)) return JD_ERR_SHAPE;
   if (c->rule == JD_RULE_TOPK && (c->top_k < 1 || c->top_k > c->V)) return JD_ERR_SHAPE;
-  if (c->w_dtype != c->emb_dtype) return JD_ERR_UNSUPPORTED_DTYPE;
+  if (c->w_dtype == JD_FP8_E4M3) {
+    if (c->emb_dtype != JD_BF16) return JD_ERR_UNSUPPORTED_DTYPE;
+    if ((c->d % 16) != 0) return JD_ERR_SHAPE;
+  } else if (c->w_dtype != c->emb_dtype) {
+    return JD_ERR_UNSUPPORTED_DTYPE;
+  }
   if (c->w_dtype == JD_BF16 && (c->d % 8) != 0) return JD_ERR_SHAPE;  // 128-bit operand loads
   return JD_OK;
 }
 
 static void free_ctx(jd_verify_ctx* c) {
   if (!c) return;
-  void* ptrs[] = {c->Wp, c->L, c->tpart, c->dpart, c->t_max, c->t_sum, c->q_max, c->q_sum, c->g, c->chunk_mass, c->Xp, c->rankpart};
+  void* ptrs[] = {c->Wp, c->Wp8, c->L, c->tpart, c->dpart, c->t_max, c->t_sum, c->q_max, c->q_sum, c->g, c->chunk_mass, c->Xp, c->rankpart};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -97,11 +104,17 @@ static int dev_alloc(jd_verify_ctx* c, T** p, size_t n) {
 
 extern "C" int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void* d_w_judge,
                                 jd_verify_ctx** out_ctx) {
+  return jd_verify_create_scaled(cfg, d_W_lm, nullptr, d_w_judge, out_ctx);
+}
+
+extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* d_W_lm, const float* d_w_scale,
+                                       const void* d_w_judge, jd_verify_ctx** out_ctx) {
   if (!out_ctx) return JD_ERR_INVALID_ARG;
   *out_ctx = nullptr;
   int rc = jd_verify_validate_config(cfg);
   if (rc != JD_OK) return rc;
   if (!d_W_lm || !d_w_judge) return JD_ERR_INVALID_ARG;
+  if (d_w_scale && cfg->w_dtype != JD_FP8_E4M3) return JD_ERR_INVALID_ARG;
 
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device >= ndev) { (void)hipGetLastError(); return JD_ERR_HIP; }
@@ -114,14 +127,15 @@ extern "C" int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm,
   c->cfg = *cfg;
   c->geo = make_geometry(cfg->d, cfg->V);
   c->num_cus = prop.multiProcessorCount;
-  c->W = d_W_lm; c->wj = d_w_judge;
+  c->W = d_W_lm; c->wj = d_w_judge; c->wscale = d_w_scale;
   c->judge_threshold = (cfg->delta >= 1.0f) ? INFINITY : std::log(cfg->delta / (1.0f - cfg->delta));
   c->prof_on = false; c->prof_max = c->prof_n = 0;
   c->bytes = 0;
 
   const size_t maxR = (size_t)cfg->max_B * (cfg->max_M + 1);
   const size_t maxS = (size_t)cfg->max_B * cfg->max_M;
-  const bool bf16 = cfg->w_dtype == JD_BF16;
+  const bool fp8 = cfg->w_dtype == JD_FP8_E4M3;
+  const bool bf16 = cfg->w_dtype == JD_BF16 || fp8;   // MFMA path (bf16 embeddings)
   c->nPartT = bf16 ? c->geo.nVG : kF32Splits;
   c->nPartD = kDraftSplits;
   c->nChunk = (cfg->V + kSamplerChunk - 1) / kSamplerChunk;
@@ -136,12 +150,20 @@ extern "C" int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm,
   if (rc == JD_OK) rc = dev_alloc(c, &c->g, maxS);
   if (rc == JD_OK) rc = dev_alloc(c, &c->chunk_mass, (size_t)cfg->max_B * c->nChunk);
   if (rc == JD_OK && cfg->rule == JD_RULE_TOPK) rc = dev_alloc(c, &c->rankpart, maxS * (size_t)kRankSplits);
-  if (rc == JD_OK && bf16) {
+  if (rc == JD_OK && fp8) {
+    uint8_t* wp8 = nullptr;
+    rc = dev_alloc(c, &wp8, c->geo.packed8_bytes());
+    c->Wp8 = wp8;
+    if (rc == JD_OK && (launch_pack_w8(d_W_lm, cfg->w_layout, c->geo, c->Wp8, nullptr) != hipSuccess ||
+                        hipDeviceSynchronize() != hipSuccess))
+      rc = JD_ERR_HIP;
+  }
+  if (rc == JD_OK && bf16 && (!fp8 || maxR > 64)) {  // FP8 contexts need the bf16 copy only for the GEMM regime
     uint8_t* wp = nullptr;
     rc = dev_alloc(c, &wp, c->geo.packed_bytes());
     c->Wp = wp;
     if (rc == JD_OK) {
-      if (launch_pack_w(d_W_lm, cfg->w_layout, c->geo, c->Wp, nullptr) != hipSuccess ||
+      if (launch_pack_w(d_W_lm, cfg->w_layout, fp8 ? 1 : 0, c->geo, c->Wp, nullptr) != hipSuccess ||
           hipDeviceSynchronize() != hipSuccess)
         rc = JD_ERR_HIP;
     }
@@ -215,7 +237,8 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
   const Geometry& g = c->geo;
   const int R = B * (M + 1);
   const float invT = 1.0f / cfg.temperature;
-  const bool bf16 = cfg.w_dtype == JD_BF16;
+  const bool fp8 = cfg.w_dtype == JD_FP8_E4M3;
+  const bool bf16 = cfg.w_dtype == JD_BF16 || fp8;
   const bool logits = cfg.draft_kind == JD_DRAFT_LOGITS;
 
   hipEvent_t* ev = nullptr;
@@ -241,9 +264,11 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
   // step 1: LM head (+ first softmax pass)
   if (bf16) {
     if (R <= 64) {
-      JD_HIP(launch_lmhead_skinny(c->Wp, d_emb, R, g, invT, c->L, c->tpart, side, st));
+      JD_HIP(launch_lmhead_skinny(fp8 ? c->Wp8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart,
+                                  side, st));
     } else {
-      JD_HIP(launch_lmhead_gemm(c->Wp, d_emb, R, g, invT, c->L, c->tpart, c->Xp, c->num_cus, st));
+      JD_HIP(launch_lmhead_gemm(c->Wp, fp8 ? c->wscale : nullptr, d_emb, R, g, invT, c->L, c->tpart, c->Xp,
+                                c->num_cus, st));
     }
   } else {
     JD_HIP(launch_lmhead_f32(static_cast<const float*>(c->W), cfg.w_layout, static_cast<const float*>(d_emb), R,

@@ -67,8 +67,9 @@ __global__ __launch_bounds__(256) void pack_x_kernel(const uint16_t* __restrict_
 }
 
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
-    const uint4* __restrict__ Wp, const uint4* __restrict__ Xp, int R, int nChunks, int V, int nVG, int nVGalloc,
-    int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part) {
+    const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
+    int nChunks, int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L,
+    int Lld, float2* __restrict__ part) {
   constexpr int NXB = kGemmRowBlocks;
   constexpr int ITEMS = NXB * kGemmSteps * 64;  // 16-byte items per staged chunk (44 KiB)
   constexpr int IPT = ITEMS / 256;              // = NXB
@@ -227,6 +228,14 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
 
   // epilogue: acc[sub][x][i] = logit of row rt*176 + x*16 + n, entry vg*64 + sub*16 + gq*4 + i
   if (vg >= nVG) return;
+  float osc[4][4];  // (per-entry weight scale, FP8 weights only) / T for this lane's 16 vocabulary entries
+#pragma unroll
+  for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = vg * kVocabGroup + sub * 16 + gq * 4 + i;
+      osc[sub][i] = (vscale != nullptr && v < V) ? vscale[v] * invT : invT;
+    }
 #pragma unroll
   for (int x = 0; x < NXB; ++x) {
     const int r = rt * kGemmRows + x * 16 + n;
@@ -237,7 +246,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int v = vg * kVocabGroup + sub * 16 + gq * 4 + i;
-        const float l = acc[sub][x][i] * invT;
+        const float l = acc[sub][x][i] * osc[sub][i];
         vals[sub][i] = l;
         if (v < V) mx = fmaxf(mx, l);
       }
@@ -265,8 +274,8 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   }
 }
 
-hipError_t launch_lmhead_gemm(const void* Wp, const void* X, int R, const Geometry& g, float invT, float* L,
-                              float2* part, void* Xp, int /*num_cus*/, hipStream_t st) {
+hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
+                              float invT, float* L, float2* part, void* Xp, int /*num_cus*/, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
   if (R <= 0 || !Xp) return hipErrorInvalidValue;
   const int nRowTiles = (R + kGemmRows - 1) / kGemmRows;
@@ -286,7 +295,7 @@ hipError_t launch_lmhead_gemm(const void* Wp, const void* X, int R, const Geomet
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(lmhead_gemm_kernel, dim3(grid), dim3(256), kLds, st, static_cast<const uint4*>(Wp),
+  hipLaunchKernelGGL(lmhead_gemm_kernel, dim3(grid), dim3(256), kLds, st, static_cast<const uint4*>(Wp), vscale,
                      static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG, g.nVGalloc, nRowTiles, nVocabTiles, invT,
                      L, g.Vpad, part);
   return hipGetLastError();

@@ -33,8 +33,20 @@ constexpr int kPF = JD_PF;  // K steps per weight prefetch group
 // ------------------------------------------------------------------------------- pack
 
 // One thread writes one 16-byte element of Wp (8 consecutive hidden indices of one row).
-__global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int layout, int V, int d,
-                                                      int KS, int nVGalloc, size_t total, uint4* __restrict__ Wp) {
+// Eight FP8 E4M3 codes (two dwords, ascending hidden index) to eight bf16 values.  The hardware
+// converts two codes to two floats at a time; an E4M3 value has 3 mantissa bits, so the upper
+// half of its float is exactly its bf16.
+__device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)lo, true);
+  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)hi, false), e = __builtin_amdgcn_cvt_pk_f32_fp8((int)hi, true);
+  auto pack = [](float x, float y) { return (__float_as_uint(x) >> 16) | (__float_as_uint(y) & 0xffff0000u); };
+  return make_uint4(pack(a[0], a[1]), pack(b[0], b[1]), pack(c[0], c[1]), pack(e[0], e[1]));
+}
+
+__global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int layout, int src_fp8, int V,
+                                                      int d, int KS, int nVGalloc, size_t total,
+                                                      uint4* __restrict__ Wp) {
   size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   int lane = (int)(idx & 63);
@@ -46,7 +58,14 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
   int k0 = ks * kKStep + (lane >> 4) * 8;
   union { uint4 q; uint16_t h[8]; } o;
   o.q = make_uint4(0u, 0u, 0u, 0u);
-  if (v < V) {
+  if (v < V && src_fp8) {
+    const uint8_t* W8 = reinterpret_cast<const uint8_t*>(W);
+    union { uint32_t w[2]; uint8_t b[8]; } c8;
+    c8.w[0] = c8.w[1] = 0u;
+    for (int e = 0; e < 8; ++e)
+      if (k0 + e < d) c8.b[e] = (layout == 0) ? W8[(size_t)v * d + k0 + e] : W8[(size_t)(k0 + e) * V + v];
+    o.q = fp8x8_to_bf16x8(c8.w[0], c8.w[1]);
+  } else if (v < V) {
     if (layout == 0) {
       if (k0 + 8 <= d && (d & 7) == 0) {
         o.q = *reinterpret_cast<const uint4*>(W + (size_t)v * d + k0);
@@ -62,14 +81,46 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
   Wp[idx] = o.q;
 }
 
-hipError_t launch_pack_w(const void* W, int layout, const Geometry& g, void* Wp, hipStream_t st) {
+hipError_t launch_pack_w(const void* W, int layout, int src_fp8, const Geometry& g, void* Wp, hipStream_t st) {
   const int KS = g.dpad / kKStep;
   const size_t total = (size_t)g.nVGalloc * KS * 256;
   const size_t blocks = (total + 255) / 256;
   if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(W), layout, g.V, g.d, KS, g.nVGalloc, total,
+                     static_cast<const uint16_t*>(W), layout, src_fp8, g.V, g.d, KS, g.nVGalloc, total,
                      static_cast<uint4*>(Wp));
+  return hipGetLastError();
+}
+
+// One thread writes one 16-byte element of Wp8: a row's codes for two consecutive K steps.
+__global__ __launch_bounds__(256) void pack_w8_kernel(const uint8_t* __restrict__ W8, int layout, int V, int d,
+                                                       int nVGalloc, size_t total, uint4* __restrict__ Wp8) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const int sub = (int)((idx >> 6) & 3);
+  int vg, kp;
+  wp8_decode(idx >> 8, nVGalloc, &vg, &kp);
+  const int v = vg * kVocabGroup + sub * 16 + (lane & 15);
+  union { uint4 q; uint8_t b[16]; } o;
+  o.q = make_uint4(0u, 0u, 0u, 0u);
+  if (v < V) {
+    for (int s = 0; s < 2; ++s) {
+      const int k0 = (2 * kp + s) * kKStep + (lane >> 4) * 8;
+      for (int e = 0; e < 8; ++e)
+        if (k0 + e < d) o.b[s * 8 + e] = (layout == 0) ? W8[(size_t)v * d + k0 + e] : W8[(size_t)(k0 + e) * V + v];
+    }
+  }
+  Wp8[idx] = o.q;
+}
+
+hipError_t launch_pack_w8(const void* W8, int layout, const Geometry& g, void* Wp8, hipStream_t st) {
+  const int KP = g.dpad / kKStep / 2;
+  const size_t total = (size_t)g.nVGalloc * KP * 256;
+  const size_t blocks = (total + 255) / 256;
+  if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(pack_w8_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const uint8_t*>(W8),
+                     layout, g.V, g.d, g.nVGalloc, total, static_cast<uint4*>(Wp8));
   return hipGetLastError();
 }
 
@@ -80,11 +131,14 @@ hipError_t launch_pack_w(const void* W, int layout, const Geometry& g, void* Wp,
 // and for the operand reads (consecutive lanes, consecutive rows, same column).
 __device__ __forceinline__ int xs_index(int row, int c) { return row * (kKChunk / 8) + (c ^ (row & 15)); }
 
-template <int NXB, int NWAVES>
+// W8 = false: Wp holds bf16 fragments.  W8 = true: Wp holds FP8 E4M3 fragments (Wp8 layout), which
+// are converted to bf16 in registers right before the MFMAs, and the logits are multiplied by the
+// per-vocabulary-entry scale in the epilogue.  Everything else is shared.
+template <int NXB, int NWAVES, bool W8>
 __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
-    const uint4* __restrict__ Wp, const uint16_t* __restrict__ X, int R, int d, int nChunks, int V, int nVG,
-    int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part, int nLmBlocks,
-    SideWork side) {
+    const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint16_t* __restrict__ X, int R, int d,
+    int nChunks, int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld,
+    float2* __restrict__ part, int nLmBlocks, SideWork side) {
   constexpr int T = NWAVES * 64;
   constexpr int ROWS = NXB * 16;
   constexpr int ITEMS = ROWS * (kKChunk / 8);  // 16-byte items per staged chunk
@@ -112,7 +166,14 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   const int KS = nChunks * kStepsPerChunk;
   const int nGroupsTotal = KS / kPF;
 
-  const uint4* wptr = Wp + wp_group_offset(vg) + lane;
+  const uint4* wptr = Wp + (W8 ? wp8_group_offset(vg) : wp_group_offset(vg)) + lane;
+  static_assert(kPF == 2, "an FP8 fragment load carries exactly one prefetch group (two K steps)");
+  // 16-byte units: position of prefetch group g (K steps 2g, 2g+1), sub-fragment `sub`, step s
+  auto w_offset = [&](int g, int s, int sub) -> size_t {
+    if constexpr (W8) return wp8_pair_offset(g, nVGalloc) + sub * 64;  // one load holds both steps
+    return wp_step_offset(g * kPF + s, nVGalloc) + sub * 64;
+  };
+  constexpr int WS = W8 ? 1 : kPF;  // loads per (group, sub)
 
   f32x4 acc[4][NXB];
 #pragma unroll
@@ -120,7 +181,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
 #pragma unroll
     for (int x = 0; x < NXB; ++x) acc[s][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  uint4 wbuf[2][kPF][4];
+  uint4 wbuf[2][WS][4];
   uint4 xreg[IPT];
 
   auto load_x = [&](int ch) {
@@ -151,9 +212,9 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   // prologue: X chunk 0 into LDS, first weight group into registers
   load_x(0);
 #pragma unroll
-  for (int s = 0; s < kPF; ++s)
+  for (int s = 0; s < WS; ++s)
 #pragma unroll
-    for (int sub = 0; sub < 4; ++sub) wbuf[0][s][sub] = wptr[wp_step_offset(s, nVGalloc) + sub * 64];
+    for (int sub = 0; sub < 4; ++sub) wbuf[0][s][sub] = wptr[w_offset(0, s, sub)];
   store_x(0, 0);
   __syncthreads();
 
@@ -166,10 +227,9 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
       // unconditional prefetch of the next group (the very last one re-reads itself)
       const int gnext = min(ch * GROUPS + gi + 1, nGroupsTotal - 1);
 #pragma unroll
-      for (int s = 0; s < kPF; ++s)
+      for (int s = 0; s < WS; ++s)
 #pragma unroll
-        for (int sub = 0; sub < 4; ++sub)
-          wbuf[(gi + 1) & 1][s][sub] = wptr[wp_step_offset(gnext * kPF + s, nVGalloc) + sub * 64];
+        for (int sub = 0; sub < 4; ++sub) wbuf[(gi + 1) & 1][s][sub] = wptr[w_offset(gnext, s, sub)];
       // keep the prefetch ahead of this group's MFMAs: without the fence the machine
       // scheduler sinks the loads next to their uses and the stream loses its depth
       __builtin_amdgcn_sched_barrier(0);
@@ -181,7 +241,13 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
         for (int x = 0; x < NXB; ++x) bfrag[x] = __builtin_bit_cast(bf16x8, xcur[xs_index(x * 16 + n, c)]);
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub) {
-          const bf16x8 afrag = __builtin_bit_cast(bf16x8, wbuf[gi & 1][s][sub]);
+          bf16x8 afrag;
+          if constexpr (W8) {
+            const uint4 w = wbuf[gi & 1][0][sub];
+            afrag = __builtin_bit_cast(bf16x8, s == 0 ? fp8x8_to_bf16x8(w.x, w.y) : fp8x8_to_bf16x8(w.z, w.w));
+          } else {
+            afrag = __builtin_bit_cast(bf16x8, wbuf[gi & 1][s][sub]);
+          }
 #pragma unroll
           for (int x = 0; x < NXB; ++x)
             acc[sub][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag[x], acc[sub][x], 0, 0, 0);
@@ -195,6 +261,14 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   // epilogue.  acc[sub][x][i] is logit of embedding row x*16 + n and vocabulary entry
   // vg*64 + sub*16 + gq*4 + i.
   if (vg >= nVG) return;
+  float osc[4][4];  // output scale of this lane's 16 vocabulary entries: (per-entry scale) / T
+#pragma unroll
+  for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = vg * kVocabGroup + sub * 16 + gq * 4 + i;
+      osc[sub][i] = (W8 && vscale != nullptr && v < V) ? vscale[v] * invT : invT;
+    }
 #pragma unroll
   for (int x = 0; x < NXB; ++x) {
     const int r = x * 16 + n;
@@ -205,7 +279,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int v = vg * kVocabGroup + sub * 16 + gq * 4 + i;
-        const float l = acc[sub][x][i] * invT;
+        const float l = acc[sub][x][i] * osc[sub][i];
         vals[sub][i] = l;
         if (v < V) mx = fmaxf(mx, l);
       }
@@ -233,25 +307,32 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   }
 }
 
-template <int NXB, int NWAVES>
-static hipError_t launch_skinny_t(const void* Wp, const void* X, int R, const Geometry& g, float invT, float* L,
-                                  float2* part, const SideWork& side, hipStream_t st) {
+template <int NXB, int NWAVES, bool W8>
+static hipError_t launch_skinny_t(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
+                                  float invT, float* L, float2* part, const SideWork& side, hipStream_t st) {
   const int nLm = (g.nVG + NWAVES - 1) / NWAVES;  // nLm*NWAVES <= nVGalloc since NWAVES divides kGroupAlloc
   const int grid = nLm + side.nStatBlocks + side.nJudgeBlocks;
-  hipLaunchKernelGGL((lmhead_skinny_kernel<NXB, NWAVES>), dim3(grid), dim3(NWAVES * 64), 0, st,
-                     static_cast<const uint4*>(Wp), static_cast<const uint16_t*>(X), R, g.d, g.dpad / kKChunk, g.V,
-                     g.nVG, g.nVGalloc, invT, L, g.Vpad, part, nLm, side);
+  hipLaunchKernelGGL((lmhead_skinny_kernel<NXB, NWAVES, W8>), dim3(grid), dim3(NWAVES * 64), 0, st,
+                     static_cast<const uint4*>(Wp), vscale, static_cast<const uint16_t*>(X), R, g.d,
+                     g.dpad / kKChunk, g.V, g.nVG, g.nVGalloc, invT, L, g.Vpad, part, nLm, side);
   return hipGetLastError();
 }
 
-hipError_t launch_lmhead_skinny(const void* Wp, const void* X, int R, const Geometry& g, float invT, float* L,
-                                float2* part, const SideWork& side, hipStream_t st) {
+hipError_t launch_lmhead_skinny(const void* Wp, int w_fp8, const float* vscale, const void* X, int R,
+                                const Geometry& g, float invT, float* L, float2* part, const SideWork& side,
+                                hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "grid covers only allocated groups");
   if (R <= 0 || R > 64) return hipErrorInvalidValue;
-  if (R <= 16) return launch_skinny_t<1, 4>(Wp, X, R, g, invT, L, part, side, st);
-  if (R <= 32) return launch_skinny_t<2, 4>(Wp, X, R, g, invT, L, part, side, st);
-  if (R <= 48) return launch_skinny_t<3, 4>(Wp, X, R, g, invT, L, part, side, st);
-  return launch_skinny_t<4, 4>(Wp, X, R, g, invT, L, part, side, st);
+  if (w_fp8) {
+    if (R <= 16) return launch_skinny_t<1, 4, true>(Wp, vscale, X, R, g, invT, L, part, side, st);
+    if (R <= 32) return launch_skinny_t<2, 4, true>(Wp, vscale, X, R, g, invT, L, part, side, st);
+    if (R <= 48) return launch_skinny_t<3, 4, true>(Wp, vscale, X, R, g, invT, L, part, side, st);
+    return launch_skinny_t<4, 4, true>(Wp, vscale, X, R, g, invT, L, part, side, st);
+  }
+  if (R <= 16) return launch_skinny_t<1, 4, false>(Wp, nullptr, X, R, g, invT, L, part, side, st);
+  if (R <= 32) return launch_skinny_t<2, 4, false>(Wp, nullptr, X, R, g, invT, L, part, side, st);
+  if (R <= 48) return launch_skinny_t<3, 4, false>(Wp, nullptr, X, R, g, invT, L, part, side, st);
+  return launch_skinny_t<4, 4, false>(Wp, nullptr, X, R, g, invT, L, part, side, st);
 }
 
 // ------------------------------------------------------------------------------- fp32

@@ -66,6 +66,10 @@ def test_validate_config_error_paths(lib):
         assert jb.jd_verify_validate_config(jb.make_config(**ok, rule=jb.JD_RULE_TOPK, top_k=k)) == jb.JD_ERR_SHAPE
     assert jb.jd_verify_validate_config(jb.make_config(**ok, rule=jb.JD_RULE_TOPK, top_k=128256)) == jb.JD_OK
     assert jb.jd_verify_validate_config(jb.make_config(**ok, top_k=0)) == jb.JD_OK  # ignored under Eq. 4
+    fp8 = dict(ok, w_dtype=jb.JD_FP8_E4M3)
+    assert jb.jd_verify_validate_config(jb.make_config(**fp8)) == jb.JD_OK
+    assert jb.jd_verify_validate_config(jb.make_config(**fp8, emb_dtype=jb.JD_F32)) == jb.JD_ERR_UNSUPPORTED_DTYPE
+    assert jb.jd_verify_validate_config(jb.make_config(**dict(fp8, d=4104))) == jb.JD_ERR_SHAPE
     # fp32 has no 8-element alignment requirement
     assert jb.jd_verify_validate_config(jb.make_config(100, 1000, 1, 5, w_dtype=jb.JD_F32)) == jb.JD_OK
 
@@ -78,6 +82,8 @@ def test_create_rejects_before_touching_the_device(lib):
     cfg = jb.make_config(4096, 128256, 1, 5)
     assert lib.jd_verify_create(ctypes.byref(cfg), None, 1, ctypes.byref(h)) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_verify_create(ctypes.byref(cfg), 1, 1, None) == jb.JD_ERR_INVALID_ARG
+    # a weight scale is only meaningful for quantised weights
+    assert lib.jd_verify_create_scaled(ctypes.byref(cfg), 1, 1, 1, ctypes.byref(h)) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_verify_destroy(None) == jb.JD_OK
     assert lib.jd_verify_run(None, 1, 1, None, None, None, None, 1, None, None, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_verify_profile_begin(None, 4) == jb.JD_ERR_INVALID_ARG

@@ -21,6 +21,8 @@ def jd():
 
 
 def oracle_for(x, **kw):
+    if "w_scale" in x:
+        kw.setdefault("w_scale", x["w_scale"])
     return vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"], **kw)
 
 
@@ -220,6 +222,54 @@ def test_topk_rule_and_target_resampling(jd):
                 assert (ref["accept_margin"] == 0).any() and not ref["z_stand"].all()   # decided by token id
 
 
+FP8 = [
+    VerifyShape("q_1blk", 1, 5, 256, 1024, "fp8", 1.0),
+    VerifyShape("q_2blk", 1, 25, 512, 2048, "fp8", 1.0),
+    VerifyShape("q_ragged", 2, 9, 272, 1000, "fp8", 2.0),        # d % 256 != 0, V % 64 != 0
+    VerifyShape("q_4blk", 4, 15, 768, 3000, "fp8", 1.5),         # R = 64
+    VerifyShape("q_gemm", 9, 10, 512, 5000, "fp8", (0.5, 2.5)),  # R = 99: large-row regime, bf16 copy + scales
+    VerifyShape("q_d16", 2, 3, 16, 200, "fp8", 1.0),             # smallest hidden size of the FP8 path
+]
+
+
+@pytest.mark.parametrize("shape", FP8, ids=lambda s: s.name)
+def test_fp8_weights_match_oracle(jd, shape):
+    print(f"[case] {shape.name}", flush=True)
+    for seed in (0, 1):
+        x = make_inputs(shape, seed)
+        rep = compare(jd.run_once(x, want_probs=True), oracle_for(x, return_probs=True))
+        print(rep, flush=True)
+
+
+def test_fp8_decode_of_every_code(jd):
+    # logits[v] = scale * decode(code v): one code per vocabulary entry, a one-hot embedding.
+    # Pins the hardware conversion (OCP E4M3: bias 7, subnormals, no infinities) against the table.
+    V, d = 256, 32
+    codes = np.arange(V, dtype=np.uint8); codes[0x7F] = 0x3A; codes[0xFF] = 0xBA   # skip the two NaN codes
+    W = np.zeros((V, d), dtype=np.uint8); W[:, 5] = codes
+    from synth import bf16_bits_from_f32
+    for R_rows, M in ((2, 1), (70, 9)):                                             # small-row and GEMM regime
+        B = R_rows // (M + 1)
+        emb = np.zeros((B, M + 1, d), dtype=np.float32); emb[:, :, 5] = 1.0
+        rng = np.random.default_rng(0)
+        x = {"emb": bf16_bits_from_f32(emb).reshape(emb.shape), "W": W,
+             "w_scale": np.full(V, 1.0 / 64, dtype=np.float32) * (1 + np.arange(V, dtype=np.float32) / 1024),
+             "w_judge": bf16_bits_from_f32(np.ones(d, dtype=np.float32)),
+             "draft_tokens": rng.integers(0, V, size=(B, M)).astype(np.int32),
+             "draft_logits": rng.normal(size=(B, M + 1, V)).astype(np.float32),
+             "uniforms": rng.random((B, M + 1)).astype(np.float32)}
+        ref = oracle_for(x, return_probs=True)
+        got = jd.run_once(x, want_probs=True)
+        compare(got, ref)
+        want = np.log(ref["probs"][0, 0]); have = np.log(got["probs"][0, 0].astype(np.float64))
+        assert np.abs((have - have[0x38]) - (want - want[0x38])).max() < 1e-5   # logit differences, all 254 codes
+    # a NaN code anywhere in a used weight row raises the NaN status
+    Wn = W.copy(); Wn[17, 5] = 0x7F
+    x["W"] = Wn
+    got = jd.run_once(x)
+    assert (got["status"].astype(np.int64) & 2).all()
+
+
 def test_separate_judge_embedding(jd):
     shape = VerifyShape("t", 3, 6, 256, 900, "bf16", 1.0)
     x = make_inputs(shape, 7)
@@ -312,7 +362,7 @@ def test_run_argument_errors(jd):
     assert jb.load_library().jd_verify_destroy(None) == jb.JD_OK
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C4q"])
 def test_full_size_single_sequence(jd, name):
     # full-size configs in the launch configuration the benchmark times; the oracle
     # evaluates the whole call (B = 1)
