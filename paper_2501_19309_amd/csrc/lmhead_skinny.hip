@@ -144,7 +144,10 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   constexpr int ITEMS = ROWS * (kKChunk / 8);  // 16-byte items per staged chunk
   constexpr int IPT = ITEMS / T;               // items per thread
   static_assert(ITEMS % T == 0, "staging must divide evenly");
-  constexpr int GROUPS = kStepsPerChunk / kPF;
+  // K steps per weight prefetch group: 2 for bf16 (8 KiB per wavefront in flight); 4 for FP8, whose
+  // fragments are half the size, so that the same 8 KiB stay in flight
+  constexpr int PFS = W8 ? 2 * kPF : kPF;
+  constexpr int GROUPS = kStepsPerChunk / PFS;
   static_assert(GROUPS % 2 == 0, "prefetch parity must be static");
 
   __shared__ uint4 xs[2][ITEMS];
@@ -164,16 +167,16 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   const int gq = lane >> 4;  // MFMA K quarter / output row quad
   const int vg = blockIdx.x * NWAVES + wave;  // < nVGalloc by construction of the grid
   const int KS = nChunks * kStepsPerChunk;
-  const int nGroupsTotal = KS / kPF;
+  const int nGroupsTotal = KS / PFS;
 
   const uint4* wptr = Wp + (W8 ? wp8_group_offset(vg) : wp_group_offset(vg)) + lane;
-  static_assert(kPF == 2, "an FP8 fragment load carries exactly one prefetch group (two K steps)");
-  // 16-byte units: position of prefetch group g (K steps 2g, 2g+1), sub-fragment `sub`, step s
-  auto w_offset = [&](int g, int s, int sub) -> size_t {
-    if constexpr (W8) return wp8_pair_offset(g, nVGalloc) + sub * 64;  // one load holds both steps
-    return wp_step_offset(g * kPF + s, nVGalloc) + sub * 64;
+  // 16-byte units: position of load i (of WS) of prefetch group g for sub-fragment `sub`.
+  // bf16: one load per K step.  FP8: one load per pair of K steps (it carries both).
+  constexpr int WS = W8 ? PFS / 2 : PFS;  // loads per (group, sub)
+  auto w_offset = [&](int g, int i, int sub) -> size_t {
+    if constexpr (W8) return wp8_pair_offset(g * WS + i, nVGalloc) + sub * 64;
+    return wp_step_offset(g * PFS + i, nVGalloc) + sub * 64;
   };
-  constexpr int WS = W8 ? 1 : kPF;  // loads per (group, sub)
 
   f32x4 acc[4][NXB];
 #pragma unroll
@@ -234,8 +237,8 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
       // scheduler sinks the loads next to their uses and the stream loses its depth
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int s = 0; s < kPF; ++s) {
-        const int c = (gi * kPF + s) * 4 + gq;
+      for (int s = 0; s < PFS; ++s) {
+        const int c = (gi * PFS + s) * 4 + gq;
         bf16x8 bfrag[NXB];
 #pragma unroll
         for (int x = 0; x < NXB; ++x) bfrag[x] = __builtin_bit_cast(bf16x8, xcur[xs_index(x * 16 + n, c)]);
@@ -243,8 +246,8 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
         for (int sub = 0; sub < 4; ++sub) {
           bf16x8 afrag;
           if constexpr (W8) {
-            const uint4 w = wbuf[gi & 1][0][sub];
-            afrag = __builtin_bit_cast(bf16x8, s == 0 ? fp8x8_to_bf16x8(w.x, w.y) : fp8x8_to_bf16x8(w.z, w.w));
+            const uint4 w = wbuf[gi & 1][s / 2][sub];
+            afrag = __builtin_bit_cast(bf16x8, (s & 1) == 0 ? fp8x8_to_bf16x8(w.x, w.y) : fp8x8_to_bf16x8(w.z, w.w));
           } else {
             afrag = __builtin_bit_cast(bf16x8, wbuf[gi & 1][s][sub]);
           }
