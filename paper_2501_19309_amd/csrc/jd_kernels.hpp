@@ -128,11 +128,24 @@ hipError_t launch_lmhead_skinny(const void* Wp, int w_fp8, const float* vscale, 
 constexpr int kGemmRowBlocks = 11;                 // 16-row MFMA blocks per row tile
 constexpr int kGemmRows = kGemmRowBlocks * 16;     // 176: 704 = 4 x 176, no padding at B=64, M=10
 constexpr int kGemmKChunk = 128;                   // hidden indices per LDS-staged chunk
-inline size_t gemm_xp_bytes(int R, const Geometry& g) {
-  return (size_t)((R + kGemmRows - 1) / kGemmRows) * kGemmRows * (size_t)g.dpad * 2;
+constexpr int kDmaRowBlocks = 22;                  // 352-row tiles of the second tiling (two 176-row halves)
+constexpr int kDmaRows = kDmaRowBlocks * 16;
+inline size_t gemm_xp_bytes(int R, const Geometry& g) {  // enough for either tiling
+  return (size_t)((R + kDmaRows - 1) / kDmaRows) * kDmaRows * (size_t)g.dpad * 2;
 }
 hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
                               float invT, float* L, float2* part, void* Xp, int num_cus, hipStream_t st);
+// The same projection on 352-row x 256-entry tiles with both operands shared through LDS; the better
+// choice when gemm_prefers_352(R), i.e. when 352-row tiles add no padding rows over 176-row tiles.
+hipError_t launch_lmhead_gemm_dma(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
+                                  float invT, float* L, float2* part, void* Xp, hipStream_t st);
+inline bool gemm_prefers_352(int R) {
+  return (R + kDmaRows - 1) / kDmaRows * kDmaRows == (R + kGemmRows - 1) / kGemmRows * kGemmRows;
+}
+// Re-tile bf16 embeddings X[R][d] into MFMA fragment order Xp[rt][chunk][xb][s][lane][8] (row tiles of
+// rowBlocks*16 rows, chunks of `steps` K steps), zero padded.
+hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks, int rowBlocks, int steps, void* Xp,
+                         hipStream_t st);
 
 // fp32 LM head (any layout), plain FMA; writes logits only.
 hipError_t launch_lmhead_f32(const float* W, int layout, const float* X, int R, int d, int V, float invT,

@@ -266,6 +266,8 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
     if (R <= 64) {
       JD_HIP(launch_lmhead_skinny(fp8 ? c->Wp8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart,
                                   side, st));
+    } else if (gemm_prefers_352(R)) {
+      JD_HIP(launch_lmhead_gemm_dma(c->Wp, fp8 ? c->wscale : nullptr, d_emb, R, g, invT, c->L, c->tpart, c->Xp, st));
     } else {
       JD_HIP(launch_lmhead_gemm(c->Wp, fp8 ? c->wscale : nullptr, d_emb, R, g, invT, c->L, c->tpart, c->Xp,
                                 c->num_cus, st));

@@ -47,23 +47,33 @@ constexpr int kGemmSteps = kGemmKChunk / kKStep;  // 4 K steps per staged chunk
 constexpr int kGemmPF = 2;                        // K steps per weight prefetch group
 constexpr int kGemmWBufs = 4;                     // register ring of weight groups: 3 groups (6 K steps) ahead
 
-// Xp[rt][chunk][xb][s][lane][8]: row rt*176 + xb*16 + lane%16, hidden index
-// chunk*128 + s*32 + (lane/16)*8 + 0..7; zero for rows >= R and indices >= d.
+// Xp[rt][chunk][xb][s][lane][8]: row rt*(rowBlocks*16) + xb*16 + lane%16, hidden index
+// chunk*(steps*32) + s*32 + (lane/16)*8 + 0..7; zero for rows >= R and indices >= d.
 __global__ __launch_bounds__(256) void pack_x_kernel(const uint16_t* __restrict__ X, int R, int d, int nChunks,
-                                                      size_t total, uint4* __restrict__ Xp) {
+                                                      int rowBlocks, int steps, size_t total,
+                                                      uint4* __restrict__ Xp) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   const int lane = (int)(idx & 63);
   size_t t = idx >> 6;
-  const int s = (int)(t % kGemmSteps); t /= kGemmSteps;
-  const int xb = (int)(t % kGemmRowBlocks); t /= kGemmRowBlocks;
+  const int s = (int)(t % steps); t /= steps;
+  const int xb = (int)(t % rowBlocks); t /= rowBlocks;
   const int ch = (int)(t % (size_t)nChunks);
   const int rt = (int)(t / (size_t)nChunks);
-  const int row = rt * kGemmRows + xb * 16 + (lane & 15);
-  const int k = ch * kGemmKChunk + s * kKStep + (lane >> 4) * 8;
+  const int row = rt * rowBlocks * 16 + xb * 16 + (lane & 15);
+  const int k = (ch * steps + s) * kKStep + (lane >> 4) * 8;
   uint4 v = make_uint4(0u, 0u, 0u, 0u);
   if (row < R && k < d) v = *reinterpret_cast<const uint4*>(X + (size_t)row * d + k);  // d % 8 == 0
   Xp[idx] = v;
+}
+
+hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks, int rowBlocks, int steps, void* Xp,
+                         hipStream_t st) {
+  const size_t total = (size_t)nRowTiles * nChunks * rowBlocks * steps * 64;
+  hipLaunchKernelGGL(pack_x_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const uint16_t*>(X), R, d, nChunks, rowBlocks, steps, total,
+                     static_cast<uint4*>(Xp));
+  return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
@@ -280,10 +290,7 @@ hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X
   if (R <= 0 || !Xp) return hipErrorInvalidValue;
   const int nRowTiles = (R + kGemmRows - 1) / kGemmRows;
   const int nChunks = g.dpad / kGemmKChunk;
-  const size_t total = (size_t)nRowTiles * nChunks * kGemmRowBlocks * kGemmSteps * 64;
-  hipLaunchKernelGGL(pack_x_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(X), R, g.d, nChunks, total, static_cast<uint4*>(Xp));
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, nChunks, kGemmRowBlocks, kGemmSteps, Xp, st);
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;

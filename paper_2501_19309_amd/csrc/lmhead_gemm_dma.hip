@@ -1,0 +1,283 @@
+// LM-head projection for the large-row regime, 352-row tiles (Sec. 3.1, Eq. 2 for all rows
+// of a batch), gfx950.  Same contract as the 176-row kernel next door; used when the row
+// count fills 352-row tiles without extra padding (704 rows = 2 tiles at B=64, M=10).
+//
+// Why a second tiling.  With one 176 x 256 tile per workgroup the compute units request
+// 27 KiB of operands from L2 per 704 matrix-core cycles, which is about what the
+// texture/L1 path of a compute unit sustains for this access pattern (measured: 64 B/clk
+// for pure L2 hits, about half of that when a quarter of the lines come from HBM) - the
+// loads, not the MFMAs, set the pace.  Here a workgroup owns 352 rows x 256 vocabulary
+// entries, both operands are fetched once per workgroup and shared through LDS, and the
+// requests drop to 38 KiB per 1408 cycles (0.70 x per flop).
+//
+//   * 4 wavefronts (one per SIMD) as 2 (row halves) x 2 (vocabulary halves); each owns
+//     176 x 128 = 11 x 8 accumulator tiles of v_mfma_f32_16x16x32_bf16 = 352 registers:
+//     the 64 tiles of row blocks 0..7 live in accumulation registers, the 24 tiles of row
+//     blocks 8..10 in ordinary vector registers (the MFMA takes either).
+//   * operands travel HBM/L2 -> LDS by direct-to-LDS loads (global_load_lds_dwordx4: no
+//     staging registers, no LDS-write instructions).  One K step (32 hidden indices) is
+//     one stage of 38 KiB (22 KiB embeddings in fragment order + 16 KiB weights, which the
+//     re-tiled W_lm already holds in fragment order); four stages = 152 KiB of LDS, so a
+//     stage is requested three K steps (~2 us) before it is read.
+//   * per K step a wavefront issues 88 MFMAs, 19 conflict-free ds_read_b128 (11 embedding
+//     fragments, refilled in place right after their row block, 8 weight fragments into the
+//     other half of a double buffer), 9-10 direct-to-LDS loads and one barrier, dealt out
+//     singly between the row blocks.
+//   * direct-to-LDS loads are written as inline assembly: the compiler then neither knows
+//     nor waits for them, and the kernel counts them itself (they complete in issue order):
+//     before the barrier of step k a wavefront waits until only its loads for steps k+2 and
+//     k+3 are outstanding.  The barrier then says two things at once: every wavefront's
+//     part of stage k+1 has landed, and nobody reads stage k any more (its operands are in
+//     registers), so stage k is re-filled for step k+4.
+#include <type_traits>
+
+#include "jd_kernels.hpp"
+
+namespace jd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kXcds = 8;
+constexpr int kDmaWaveRowBlocks = kDmaRowBlocks / 2;                    // 11 row blocks per wavefront
+constexpr int kDmaStages = 4;
+constexpr int kDmaXItems = kDmaRowBlocks * 64;                          // 16-byte items: 22 KiB of embeddings
+constexpr int kDmaWItems = 16 * 64;                                     // 16 KiB of weights (4 groups x 4 sub-blocks)
+constexpr int kDmaStageItems = kDmaXItems + kDmaWItems;                 // 38 KiB per K step
+constexpr size_t kDmaLdsBytes = (size_t)kDmaStages * kDmaStageItems * sizeof(uint4);  // 152 KiB
+constexpr int kAccRowBlocks = 8;  // row blocks whose tiles live in accumulation registers (8 x 8 x 4 = 256)
+static_assert(kDmaWaveRowBlocks == 11, "piece assignment and wait counts below assume 22 row blocks");
+
+// acc += A * B in place; the accumulator is tied to an accumulation register (ACC) or to an
+// ordinary vector register.  Inline assembly keeps all 88 tiles where they are (left to the
+// register allocator they are copied around every iteration).  Hazards the compiler no longer
+// sees: two MFMAs on one tile are 87 MFMAs apart, and the epilogue waits before reading.
+template <bool ACC>
+__device__ __forceinline__ void mfma_inplace(f32x4& acc, const uint4& a, const uint4& b) {
+  const u32x4 av = __builtin_bit_cast(u32x4, a);
+  const u32x4 bv = __builtin_bit_cast(u32x4, b);
+  if constexpr (ACC)
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(av), "v"(bv));
+  else
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(av), "v"(bv));
+}
+
+// f(integral_constant<int, I>) for I = 0 .. N-1, in order
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// One direct-to-LDS load: lane l of the wavefront copies 16 bytes from gsrc + l*16 to LDS byte
+// address lds_byte + l*16 (M0 carries the wavefront's LDS base).  The compiler uses M0 for
+// nothing else in this kernel.
+__device__ __forceinline__ void dma_1k(const uint4* gsrc, unsigned lds_byte, unsigned lane16) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_byte), "v"(lane16), "s"(gsrc) : "memory");
+}
+
+__global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
+    const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
+    int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld,
+    float2* __restrict__ part) {
+  extern __shared__ uint4 lds[];  // kDmaStages stages of [22 x 64 embedding items][16 x 64 weight items]
+
+  // XCD-aware tile id: the row tiles that stream the same 256 vocabulary rows get ids that the
+  // hardware deals to one XCD, so W_lm crosses from HBM into one L2 only.
+  const int bid = blockIdx.x;
+  const int xcd = bid % kXcds;
+  const int j = bid / kXcds;
+  const int rt = j % nRowTiles;
+  const int vt = (j / nRowTiles) * kXcds + xcd;
+  if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rh = wave >> 1, vh = wave & 1;  // row half, vocabulary half
+  const int n = lane & 15;
+  const int gq = lane >> 4;
+  const unsigned lane16 = (unsigned)lane * 16u;
+  const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)lds;
+
+  // direct-to-LDS sources of this wavefront: the 4 KiB of vocabulary group vt*4 + wave (< nVGalloc,
+  // allocated in multiples of 8 groups), and embedding row blocks wave, wave+4, .. (< 22)
+  const uint4* wsrc0 = Wp + wp_group_offset(vt * 4 + wave);
+  const uint4* xsrc0 = Xp + ((size_t)rt * KS * kDmaRowBlocks + wave) * 64;
+  const bool six = wave < 2;  // wavefronts 0, 1 own six embedding row blocks, 2, 3 own five
+
+  // piece p (0..9) of the K step `ks` into stage `stage`; pieces 0..3 weights, 4..9 embeddings
+  auto dma_piece = [&](int ks, int stage, int p) {
+    const unsigned dst = lds0 + (unsigned)stage * (kDmaStageItems * 16);
+    if (p < 4) {
+      dma_1k(wsrc0 + wp_step_offset(ks, nVGalloc) + p * 64, dst + (kDmaXItems + (wave * 4 + p) * 64) * 16, lane16);
+    } else {
+      const int q = p - 4;  // row block wave + 4q
+      if (q < 5 || six)
+        dma_1k(xsrc0 + ((size_t)ks * kDmaRowBlocks + 4 * q) * 64, dst + (unsigned)((wave + 4 * q) * 64) * 16, lane16);
+    }
+  };
+  // wait until at most `groups` K steps of this wavefront's direct-to-LDS loads are outstanding
+  // (10 loads per step for wavefronts 0, 1; 9 for 2, 3), and all its LDS reads have returned
+  auto wait_groups = [&](auto gc) {
+    constexpr int g = decltype(gc)::value;
+    if (six) {
+      if constexpr (g == 3) asm volatile("s_waitcnt vmcnt(30) lgkmcnt(0)" ::: "memory");
+      if constexpr (g == 2) asm volatile("s_waitcnt vmcnt(20) lgkmcnt(0)" ::: "memory");
+      if constexpr (g == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    } else {
+      if constexpr (g == 3) asm volatile("s_waitcnt vmcnt(27) lgkmcnt(0)" ::: "memory");
+      if constexpr (g == 2) asm volatile("s_waitcnt vmcnt(18) lgkmcnt(0)" ::: "memory");
+      if constexpr (g == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    }
+  };
+
+  f32x4 acc[8][kDmaWaveRowBlocks];
+#pragma unroll
+  for (int s = 0; s < 8; ++s)
+#pragma unroll
+    for (int x = 0; x < kDmaWaveRowBlocks; ++x) acc[s][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  uint4 xf[kDmaWaveRowBlocks];  // embedding fragments of the current K step, refilled in place
+  uint4 wf[2][8];               // weight fragments: current step / next step
+
+  // prologue: request K steps 0..3 (KS >= 8), wait for step 0, read its operands
+#pragma unroll
+  for (int s = 0; s < kDmaStages; ++s)
+#pragma unroll
+    for (int p = 0; p < 10; ++p) dma_piece(s, s, p);
+  wait_groups(std::integral_constant<int, 3>{});
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  {
+    const uint4* xr = lds + rh * kDmaWaveRowBlocks * 64 + lane;
+    const uint4* wr = lds + kDmaXItems + vh * 8 * 64 + lane;
+#pragma unroll
+    for (int x = 0; x < kDmaWaveRowBlocks; ++x) xf[x] = xr[x * 64];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) wf[0][s] = wr[s * 64];
+  }
+
+  // K step k, whose stage index k % 4 = ST is a compile-time constant
+  auto k_step = [&](const int k, auto stc) {
+    constexpr int ST = decltype(stc)::value;
+    constexpr int cur = ST & 1, nxt = cur ^ 1;
+    constexpr int RS = (ST + 1) % kDmaStages;  // stage of step k+1: read after the barrier
+    const uint4* xr = lds + RS * kDmaStageItems + rh * kDmaWaveRowBlocks * 64 + lane;
+    const uint4* wr = lds + RS * kDmaStageItems + kDmaXItems + vh * 8 * 64 + lane;
+    // branch-free past the end: the last step is requested again into a stage nobody reads
+    const int kt = min(k + kDmaStages, KS - 1);
+    static_for<0, kDmaWaveRowBlocks>([&](auto xc) {
+      constexpr int x = decltype(xc)::value;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) mfma_inplace<(x < kAccRowBlocks)>(acc[s][x], wf[cur][s], xf[x]);
+      if constexpr (x == 0) {
+        // stage k+1 complete for this wavefront's part; after the barrier for everybody's,
+        // and stage k (= ST) is free: all its fragments were read during step k-1
+        wait_groups(std::integral_constant<int, 2>{});
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");  // no LDS read moves above the barrier
+      }
+      xf[x] = xr[x * 64];                                                 // row block x of step k+1
+      if constexpr (x >= 1 && x <= 8) wf[nxt][x - 1] = wr[(x - 1) * 64];  // weight sub-block x-1 of step k+1
+      if constexpr (x >= 1) dma_piece(kt, ST, x - 1);  // piece x-1 of step k+4 into the freed stage
+      __builtin_amdgcn_sched_barrier(0);               // keep this dealing-out as written
+    });
+  };
+
+  for (int k = 0; k < KS; k += 4) {  // KS is a multiple of 8: d is padded to 256
+    k_step(k, std::integral_constant<int, 0>{});
+    k_step(k + 1, std::integral_constant<int, 1>{});
+    k_step(k + 2, std::integral_constant<int, 2>{});
+    k_step(k + 3, std::integral_constant<int, 3>{});
+  }
+
+  // every direct-to-LDS load must have landed before the workgroup gives its LDS back, and the
+  // last MFMAs must have left the matrix pipeline before their tiles are read
+  wait_groups(std::integral_constant<int, 0>{});
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+
+  // epilogue: acc[s][x][i] = logit of row rt*352 + rh*176 + x*16 + n,
+  //           vocabulary entry (vt*4 + vh*2 + s/4)*64 + (s%4)*16 + gq*4 + i
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int vg = vt * 4 + vh * 2 + half;
+    if (vg >= nVG) continue;
+    float osc[4][4];  // (per-entry weight scale, FP8 weights only) / T for this lane's 16 entries
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int v = vg * kVocabGroup + sub * 16 + gq * 4 + i;
+        osc[sub][i] = (vscale != nullptr && v < V) ? vscale[v] * invT : invT;
+      }
+#pragma unroll
+    for (int x = 0; x < kDmaWaveRowBlocks; ++x) {
+      const int r = rt * kDmaRows + rh * (kDmaWaveRowBlocks * 16) + x * 16 + n;
+      float vals[4][4];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int v = vg * kVocabGroup + sub * 16 + gq * 4 + i;
+          const float l = acc[half * 4 + sub][x][i] * osc[sub][i];
+          vals[sub][i] = l;
+          if (v < V) mx = fmaxf(mx, l);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      float sum = 0.f;
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int v = vg * kVocabGroup + sub * 16 + gq * 4 + i;
+          if (v < V) sum += __expf(vals[sub][i] - mx);
+        }
+      sum += __shfl_xor(sum, 16);
+      sum += __shfl_xor(sum, 32);
+      if (r < R) {
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) {
+          const int v0 = vg * kVocabGroup + sub * 16 + gq * 4;
+          *reinterpret_cast<float4*>(L + (size_t)r * Lld + v0) =
+              make_float4(vals[sub][0], vals[sub][1], vals[sub][2], vals[sub][3]);
+        }
+        if (gq == 0) part[(size_t)r * nVG + vg] = make_float2(mx, sum);
+      }
+    }
+  }
+}
+
+hipError_t launch_lmhead_gemm_dma(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
+                                  float invT, float* L, float2* part, void* Xp, hipStream_t st) {
+  static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
+  static_assert(kWpKG * 256 == 4 * 256 && kKStep == 32, "a K step of one vocabulary group is 4 KiB, contiguous");
+  if (R <= 0 || !Xp) return hipErrorInvalidValue;
+  const int nRowTiles = (R + kDmaRows - 1) / kDmaRows;
+  const int KS = g.dpad / kKStep;  // multiple of 8
+  if (KS < 2 * kDmaStages) return hipErrorInvalidValue;
+  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, KS, kDmaRowBlocks, 1, Xp, st);
+  if (e != hipSuccess) return e;
+  const int nVocabTiles = (g.nVG + 3) / 4;
+  const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
+  static bool attr_set = false;
+  if (!attr_set) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(lmhead_gemm_dma_kernel, dim3(grid), dim3(256), kDmaLdsBytes, st, static_cast<const uint4*>(Wp),
+                     vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG, g.nVGalloc, nRowTiles, nVocabTiles,
+                     invT, L, g.Vpad, part);
+  return hipGetLastError();
+}
+
+}  // namespace jd

@@ -49,7 +49,10 @@ EDGE = [
     VerifyShape("e_d8", 2, 5, 8, 700, "bf16", 1.0),              # smallest hidden size the bf16 path takes
     VerifyShape("e_B200", 200, 2, 64, 333, "bf16", 1.0),         # many sequences, R = 600
     VerifyShape("e_R65", 5, 12, 96, 1024, "bf16", 1.0),          # first row count of the GEMM regime
-    VerifyShape("e_R177", 3, 58, 64, 640, "bf16", 1.0),          # one row into a second 176-row tile
+    VerifyShape("e_R177", 3, 58, 64, 640, "bf16", 1.0),          # one row into a second 176-row tile (352-row tiling)
+    VerifyShape("e_R352", 32, 10, 520, 4100, "bf16", (0.5, 2.0)),  # exactly one 352-row tile, 24 K steps, ragged V
+    VerifyShape("e_R400", 40, 9, 264, 1000, "bf16", 1.0),        # three 176-row tiles (176-row tiling)
+    VerifyShape("e_R1000", 100, 9, 128, 700, "bf16", 1.0),       # three 352-row tiles, the last one ragged
     VerifyShape("e_V1", 2, 2, 8, 1, "f32", 1.0),                 # single token vocabulary: everything is certain
 ]
 
@@ -228,6 +231,7 @@ FP8 = [
     VerifyShape("q_ragged", 2, 9, 272, 1000, "fp8", 2.0),        # d % 256 != 0, V % 64 != 0
     VerifyShape("q_4blk", 4, 15, 768, 3000, "fp8", 1.5),         # R = 64
     VerifyShape("q_gemm", 9, 10, 512, 5000, "fp8", (0.5, 2.5)),  # R = 99: large-row regime, bf16 copy + scales
+    VerifyShape("q_gemm352", 20, 10, 288, 2100, "fp8", (0.5, 2.5)),  # R = 220: the 352-row tiling with scales
     VerifyShape("q_d16", 2, 3, 16, 200, "fp8", 1.0),             # smallest hidden size of the FP8 path
 ]
 
