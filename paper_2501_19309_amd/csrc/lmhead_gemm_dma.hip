@@ -80,6 +80,13 @@ __device__ __forceinline__ void dma_1k(const uint4* gsrc, unsigned lds_byte, uns
                :: "s"(lds_byte), "v"(lane16), "s"(gsrc) : "memory");
 }
 
+// The same in two instructions that the caller places at least one instruction apart (a write of M0
+// needs a wait state before the load that uses it).
+__device__ __forceinline__ void set_m0(unsigned lds_byte) { asm volatile("s_mov_b32 m0, %0" ::"s"(lds_byte)); }
+__device__ __forceinline__ void dma_issue(const uint4* gbase, unsigned lane_off) {
+  asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase) : "memory");
+}
+
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
     int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld,
@@ -121,19 +128,15 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
         dma_1k(xsrc0 + ((size_t)ks * kDmaRowBlocks + 4 * q) * 64, dst + (unsigned)((wave + 4 * q) * 64) * 16, lane16);
     }
   };
-  // wait until at most `groups` K steps of this wavefront's direct-to-LDS loads are outstanding
-  // (10 loads per step for wavefronts 0, 1; 9 for 2, 3), and all its LDS reads have returned
+  // Wait until at most `groups` K steps of this wavefront's direct-to-LDS loads are outstanding and all
+  // its LDS reads have returned.  Wavefronts 0, 1 issue 10 loads per step and 2, 3 issue 9; loads
+  // complete in issue order, so the count for 9 is right for both (0, 1 then also wait for the first
+  // one or two loads of the following, much older, step).
   auto wait_groups = [&](auto gc) {
     constexpr int g = decltype(gc)::value;
-    if (six) {
-      if constexpr (g == 3) asm volatile("s_waitcnt vmcnt(30) lgkmcnt(0)" ::: "memory");
-      if constexpr (g == 2) asm volatile("s_waitcnt vmcnt(20) lgkmcnt(0)" ::: "memory");
-      if constexpr (g == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    } else {
-      if constexpr (g == 3) asm volatile("s_waitcnt vmcnt(27) lgkmcnt(0)" ::: "memory");
-      if constexpr (g == 2) asm volatile("s_waitcnt vmcnt(18) lgkmcnt(0)" ::: "memory");
-      if constexpr (g == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    }
+    if constexpr (g == 3) asm volatile("s_waitcnt vmcnt(27) lgkmcnt(0)" ::: "memory");
+    if constexpr (g == 2) asm volatile("s_waitcnt vmcnt(18) lgkmcnt(0)" ::: "memory");
+    if constexpr (g == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   };
 
   f32x4 acc[8][kDmaWaveRowBlocks];
@@ -162,38 +165,64 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     for (int s = 0; s < 8; ++s) wf[0][s] = wr[s * 64];
   }
 
-  // K step k, whose stage index k % 4 = ST is a compile-time constant
-  auto k_step = [&](const int k, auto stc) {
+  // K step k = 4*kk + ST; the stage index ST is a compile-time constant.  The wavefront's instruction
+  // stream is written out MFMA by MFMA: with one wavefront per SIMD nothing else can fill the matrix
+  // pipeline while this wavefront issues other instructions, and an MFMA leaves room for about three
+  // of them, so every LDS read, M0 write and direct-to-LDS load sits alone behind its own MFMA.
+  const size_t wGroupStride = (size_t)nVGalloc * (kWpKG * 256);
+  const unsigned ldsW0 = lds0 + (unsigned)(kDmaXItems + wave * 4 * 64) * 16;
+  const unsigned ldsX0 = lds0 + (unsigned)(wave * 64) * 16;
+  auto k_step = [&](const uint4* wIter, const uint4* xIter, auto stc) {
     constexpr int ST = decltype(stc)::value;
     constexpr int cur = ST & 1, nxt = cur ^ 1;
     constexpr int RS = (ST + 1) % kDmaStages;  // stage of step k+1: read after the barrier
+    constexpr unsigned stageByte = (unsigned)ST * (kDmaStageItems * 16);
     const uint4* xr = lds + RS * kDmaStageItems + rh * kDmaWaveRowBlocks * 64 + lane;
     const uint4* wr = lds + RS * kDmaStageItems + kDmaXItems + vh * 8 * 64 + lane;
-    // branch-free past the end: the last step is requested again into a stage nobody reads
-    const int kt = min(k + kDmaStages, KS - 1);
-    static_for<0, kDmaWaveRowBlocks>([&](auto xc) {
-      constexpr int x = decltype(xc)::value;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) mfma_inplace<(x < kAccRowBlocks)>(acc[s][x], wf[cur][s], xf[x]);
-      if constexpr (x == 0) {
+    // requested now: step k+4 into the stage this step frees (wIter, xIter: its group of four steps).
+    // In the last group step k itself is requested again into its own, already consumed stage
+    // (branch-free, unread).
+    const uint4* wg = wIter + ST * 256;
+    const uint4* xg = xIter + ST * (kDmaRowBlocks * 64);
+    static_for<0, 8 * kDmaWaveRowBlocks>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      constexpr int x = i / 8, sb = i % 8;  // row block, weight sub-block
+      mfma_inplace<(x < kAccRowBlocks)>(acc[sb][x], wf[cur][sb], xf[x]);
+      if constexpr (i == 7) {
         // stage k+1 complete for this wavefront's part; after the barrier for everybody's,
         // and stage k (= ST) is free: all its fragments were read during step k-1
         wait_groups(std::integral_constant<int, 2>{});
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");  // no LDS read moves above the barrier
       }
-      xf[x] = xr[x * 64];                                                 // row block x of step k+1
-      if constexpr (x >= 1 && x <= 8) wf[nxt][x - 1] = wr[(x - 1) * 64];  // weight sub-block x-1 of step k+1
-      if constexpr (x >= 1) dma_piece(kt, ST, x - 1);  // piece x-1 of step k+4 into the freed stage
-      __builtin_amdgcn_sched_barrier(0);               // keep this dealing-out as written
+      if constexpr (x >= 1 && sb == 1) xf[x - 1] = xr[(x - 1) * 64];  // row block x-1 of step k+1, in place
+      if constexpr (i == 8 * kDmaWaveRowBlocks - 1) xf[x] = xr[x * 64];
+      if constexpr (x >= 1 && x <= 8 && sb == 3) wf[nxt][x - 1] = wr[(x - 1) * 64];  // weight sub-block x-1
+      if constexpr (x >= 1 && (sb == 5 || sb == 6)) {  // piece x-1: 0..3 weights, 4..9 embedding row block wave+4q
+        constexpr int p = x - 1, q = p - 4;
+        if constexpr (p < 4) {
+          if constexpr (sb == 5) set_m0(ldsW0 + stageByte + p * 1024);
+          if constexpr (sb == 6) dma_issue(wg, lane16 + p * 1024);
+        } else if constexpr (q < 5) {
+          if constexpr (sb == 5) set_m0(ldsX0 + stageByte + q * 4096);
+          if constexpr (sb == 6) dma_issue(xg, lane16 + q * 4096);
+        } else if constexpr (sb == 6) {
+          if (six) dma_1k(xg + q * 256, ldsX0 + stageByte + q * 4096, lane16);  // sixth row block: wavefronts 0, 1
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep this dealing-out as written
     });
   };
 
-  for (int k = 0; k < KS; k += 4) {  // KS is a multiple of 8: d is padded to 256
-    k_step(k, std::integral_constant<int, 0>{});
-    k_step(k + 1, std::integral_constant<int, 1>{});
-    k_step(k + 2, std::integral_constant<int, 2>{});
-    k_step(k + 3, std::integral_constant<int, 3>{});
+  const int nKK = KS / 4;  // KS is a multiple of 8: d is padded to 256
+  for (int kk = 0; kk < nKK; ++kk) {
+    const int kn = min(kk + 1, nKK - 1);  // group of four steps requested during this one
+    const uint4* wIter = wsrc0 + (size_t)kn * wGroupStride;
+    const uint4* xIter = xsrc0 + (size_t)kn * (4 * kDmaRowBlocks * 64);
+    k_step(wIter, xIter, std::integral_constant<int, 0>{});
+    k_step(wIter, xIter, std::integral_constant<int, 1>{});
+    k_step(wIter, xIter, std::integral_constant<int, 2>{});
+    k_step(wIter, xIter, std::integral_constant<int, 3>{});
   }
 
   // every direct-to-LDS load must have landed before the workgroup gives its LDS back, and the
