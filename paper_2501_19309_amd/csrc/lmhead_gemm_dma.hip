@@ -12,8 +12,8 @@
 //
 //   * 4 wavefronts (one per SIMD) as 2 (row halves) x 2 (vocabulary halves); each owns
 //     176 x 128 = 11 x 8 accumulator tiles of v_mfma_f32_16x16x32_bf16 = 352 registers:
-//     the 64 tiles of row blocks 0..7 live in accumulation registers, the 24 tiles of row
-//     blocks 8..10 in ordinary vector registers (the MFMA takes either).
+//     60 tiles live in accumulation registers, the other 28 in ordinary vector registers
+//     (the MFMA takes either).
 //   * operands travel HBM/L2 -> LDS by direct-to-LDS loads (global_load_lds_dwordx4: no
 //     staging registers, no LDS-write instructions).  One K step (32 hidden indices) is
 //     one stage of 38 KiB (22 KiB embeddings in fragment order + 16 KiB weights, which the
@@ -46,7 +46,11 @@ constexpr int kDmaXItems = kDmaRowBlocks * 64;                          // 16-by
 constexpr int kDmaWItems = 16 * 64;                                     // 16 KiB of weights (4 groups x 4 sub-blocks)
 constexpr int kDmaStageItems = kDmaXItems + kDmaWItems;                 // 38 KiB per K step
 constexpr size_t kDmaLdsBytes = (size_t)kDmaStages * kDmaStageItems * sizeof(uint4);  // 152 KiB
-constexpr int kAccRowBlocks = 8;  // row blocks whose tiles live in accumulation registers (8 x 8 x 4 = 256)
+// Tile (row block x, weight sub-block sb) lives in accumulation registers for the first 60 tiles (240 of the
+// 256 registers) and in ordinary vector registers for the other 28.  Filling all 256 leaves the register
+// allocator no room: it then parks values in scratch memory around the epilogue, reading tiles before the wait
+// that protects them.
+__host__ __device__ constexpr bool acc_in_agpr(int x, int sb) { return x < 7 || (x == 7 && sb < 4); }
 static_assert(kDmaWaveRowBlocks == 11, "piece assignment and wait counts below assume 22 row blocks");
 
 // acc += A * B in place; the accumulator is tied to an accumulation register (ACC) or to an
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     static_for<0, 8 * kDmaWaveRowBlocks>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       constexpr int x = i / 8, sb = i % 8;  // row block, weight sub-block
-      mfma_inplace<(x < kAccRowBlocks)>(acc[sb][x], wf[cur][sb], xf[x]);
+      mfma_inplace<acc_in_agpr(x, sb)>(acc[sb][x], wf[cur][sb], xf[x]);
       if constexpr (i == 7) {
         // stage k+1 complete for this wavefront's part; after the barrier for everybody's,
         // and stage k (= ST) is free: all its fragments were read during step k-1
