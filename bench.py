@@ -28,9 +28,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
-# what the same counter reads for a plain 1 GiB copy (profiles/lmhead_skinny_C4_hbm_traffic.md);
+# what the same counter reads for a plain 1 GiB copy (profiles/lmhead_skinny_C4_hbm_traffic.md,
+# profiles/lmhead_gemm_C5_counters.md);
 # None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 4.2396e9}
+MEASURED_TRAFFIC_BYTES = {"C4": 4.2533e9, "C5": 2.888e9}  # fetched + written
 
 
 def log(*a):
