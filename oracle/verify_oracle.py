@@ -50,6 +50,14 @@ Variants of the rule that the paper itself uses (selected by ``rule`` / ``resamp
   * ``resample = RESAMPLE_TARGET``: the literal "sample a correct token from p_i" of
     Sec. 3.1, i.e. the replacement is drawn from p_i itself instead of the residual.
 
+Pre-norm wiring (Sec. 4.1, "Model design and training": the judge reads the last target embedding
+*before* the final RMS normalisation, the LM head reads it after): ``rmsnorm_rows`` turns pre-norm
+hidden states h into the LM-head input x = round_model_dtype(h * gamma / sqrt(mean(h^2) + eps)),
+computed in float64 and rounded ONCE to the storage type of the embeddings (bf16 bit patterns, or
+float32); ``verify(emb=rmsnorm_rows(h, ...), emb_judge=h)`` is then the paper's wiring.  The rounding
+is part of the definition: the LM head multiplies bf16 operands, so the rounded tensor is what both
+sides must use for the integer outputs to be comparable.
+
 Parity pins for every function here live in tests/test_oracle_pins.py: the
 paper's rule on hand cases, brute-force enumeration at V = 8 / M = 3, a
 Monte-Carlo chi-square that standard-only verification emits the target
@@ -113,6 +121,40 @@ def widen(x: np.ndarray) -> np.ndarray:
     if x.dtype in (np.float32, np.float64):
         return x.astype(np.float64)
     raise TypeError(f"unsupported input dtype {x.dtype}")
+
+
+def round_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float64 values to bfloat16 (8 significant bits, round-to-nearest-even, subnormals kept)
+    and return the 16-bit patterns.  Written from the format: x = m * 2^e with 0.5 <= |m| < 1 is
+    rounded to a multiple of 2^(e-8), or of 2^-133 (the smallest subnormal) below the normal range.
+    Scaling by powers of two and rint are exact in float64, so there is no double rounding."""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)
+    quantum_exp = np.maximum(e - 8, -133)                 # exponent of the spacing around x
+    q = np.rint(np.ldexp(x, -quantum_exp))                # ties to even, exact
+    y = np.ldexp(q, quantum_exp)
+    y = np.where(np.abs(y) >= 2.0 ** 128, np.copysign(np.inf, x), y)   # beyond the largest finite bf16
+    y = np.where(np.isnan(x), np.nan, y)
+    f = y.astype(np.float32)                              # exact: every bf16 value is a float32
+    bits = (f.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    return np.where(x == 0, (np.signbit(x).astype(np.uint16) << np.uint16(15)), bits).astype(np.uint16)
+
+
+def rmsnorm_rows(hidden: np.ndarray, gamma: np.ndarray, eps: float):
+    """Final RMS normalisation of pre-norm hidden states, row by row (Sec. 4.1, "Model design and
+    training"): x[k] = h[k] * gamma[k] / sqrt(mean_k(h[k]^2) + eps) in float64, then rounded once to
+    the storage type of ``hidden`` (uint16 = bf16 bit patterns -> bf16 bit patterns; float32 ->
+    float32).  Returns (x in storage type, 1 / sqrt(mean + eps) per row as float64)."""
+    h = widen(hidden)
+    g = widen(gamma)
+    inv = 1.0 / np.sqrt(np.mean(h * h, axis=-1) + float(eps))
+    x = h * g * inv[..., None]
+    hidden = np.asarray(hidden)
+    if hidden.dtype == np.uint16:
+        return round_to_bf16_bits(x), inv
+    if hidden.dtype == np.float32:
+        return x.astype(np.float32), inv
+    raise TypeError(f"unsupported hidden-state dtype {hidden.dtype}")
 
 
 def judge_threshold(delta: float) -> float:

@@ -14,8 +14,10 @@ not depend on the thread count.
 Nothing in this file is part of the verification method: the only arithmetic is
 drawing numbers, rounding to bf16 (or quantising the drawn weights to FP8 E4M3 with
 one scale per row), one single-precision matmul to make the draft logits a perturbed
-copy of the target logits, and a Gumbel arg-max to draw the draft tokens from the
-draft distribution.
+copy of the target logits (for the pre-norm workloads preceded by a single-precision
+normalisation of the drawn hidden states, used for nothing else: the oracle and the
+library each normalise the stored hidden states themselves), and a Gumbel arg-max to
+draw the draft tokens from the draft distribution.
 """
 
 from __future__ import annotations
@@ -28,7 +30,9 @@ from typing import Dict, Tuple, Union
 import numpy as np
 
 # tensor tags: each selects its own family of Philox streams
-_TAG_EMB, _TAG_W, _TAG_JUDGE, _TAG_SCALE, _TAG_NOISE, _TAG_GUMBEL, _TAG_UNIF = range(1, 8)
+_TAG_EMB, _TAG_W, _TAG_JUDGE, _TAG_SCALE, _TAG_NOISE, _TAG_GUMBEL, _TAG_UNIF, _TAG_GAMMA, _TAG_ROWSCALE = range(1, 10)
+
+RMS_EPS = 1e-5  # epsilon of the final RMS normalisation in the pre-norm workloads
 
 _VOCAB_CHUNK = 2048  # rows of W_lm drawn per Philox stream
 
@@ -117,8 +121,15 @@ def _n_threads() -> int:
     return max(1, min(16, avail))
 
 
-def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
+def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False) -> Dict[str, np.ndarray]:
     """Draw every input of one verify call.
+
+    prenorm=True draws the workload in the paper's wiring (Sec. 4.1: the judge sees the last target
+    embedding before the final RMS normalisation): instead of ``emb`` the dict holds
+      hidden        [B, M+1, d]  pre-norm hidden states (rows of very different scale), storage type
+      gamma         [d]          gain of the final RMS normalisation, storage type
+      rms_eps       float
+    and the draft logits are a noisy copy of the logits of a single-precision normalisation of them.
 
     Returns a dict with
       emb           [B, M+1, d]  float32, or uint16 bf16 bit patterns
@@ -139,6 +150,19 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
     # embeddings: N(0,1), each row rescaled to unit rms, then stored
     h = _stream(seed, _TAG_EMB).standard_normal((R, d), dtype=np.float32)
     h /= np.sqrt(np.mean(h.astype(np.float64) ** 2, axis=1, keepdims=True)).astype(np.float32)
+    hidden_store = gamma_store = None
+    if prenorm:
+        # pre-norm hidden states: the unit-rms rows times a log-normal scale per row; gain near 1
+        rowscale = np.exp(_stream(seed, _TAG_ROWSCALE).standard_normal(R).astype(np.float32) * np.float32(0.7))
+        hid = h * rowscale[:, None] * np.float32(3.0)
+        gam = (np.float32(1.0) + np.float32(0.1) * _stream(seed, _TAG_GAMMA).standard_normal(d, dtype=np.float32))
+        if is_bf16:
+            hidden_store = bf16_bits_from_f32(hid); hid = f32_from_bf16_bits(hidden_store)
+            gamma_store = bf16_bits_from_f32(gam); gam = f32_from_bf16_bits(gamma_store)
+        else:
+            hidden_store, gamma_store = hid.copy(), gam.copy()
+        # a single-precision stand-in for the LM-head input, only used to build the draft logits below
+        h = hid * gam / np.sqrt(np.mean(hid.astype(np.float64) ** 2, axis=1, keepdims=True) + RMS_EPS).astype(np.float32)
     if is_bf16:
         emb_store = bf16_bits_from_f32(h)
         h = f32_from_bf16_bits(emb_store)
@@ -216,7 +240,6 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
     uniforms = _stream(seed, _TAG_UNIF).random((B, M + 1), dtype=np.float32)
 
     out = {
-        "emb": emb_store.reshape(B, M + 1, d),
         "W": W_store,
         "w_judge": wj_store,
         "draft_logits": D.reshape(B, M + 1, V),
@@ -224,6 +247,12 @@ def make_inputs(shape: VerifyShape, seed: int = 0) -> Dict[str, np.ndarray]:
         "uniforms": uniforms,
         "sigma_b": sigma_b,
     }
+    if prenorm:
+        out["hidden"] = hidden_store.reshape(B, M + 1, d)
+        out["gamma"] = gamma_store
+        out["rms_eps"] = RMS_EPS
+    else:
+        out["emb"] = emb_store.reshape(B, M + 1, d)
     if is_fp8:
         out["w_scale"] = W_scale
     return out

@@ -23,7 +23,7 @@ import scipy.special
 import scipy.stats
 
 from oracle import verify_oracle as vo
-from synth import VerifyShape, make_inputs
+from synth import VerifyShape, make_inputs, bf16_bits_from_f32, f32_from_bf16_bits
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -606,3 +606,91 @@ def test_fp8_weights_are_scaled_rows():
                     w_scale=x["w_scale"])
     assert (out["status"] == 0).all()
     assert {"C2q", "C3q", "C4q"} <= set(CONFIGS)
+
+
+# ----------------------------------------------------------------------------- pre-norm wiring (final RMS norm)
+
+def test_round_to_bf16_hand_cases():
+    # 8 significant bits, ties to even, written out by hand from the format
+    cases = {
+        1.0: 0x3F80,
+        1.0 + 2.0 ** -8: 0x3F80,                 # exact tie between 1 and 1 + 2^-7: even mantissa wins
+        1.0 + 2.0 ** -8 + 2.0 ** -40: 0x3F81,    # just above the tie
+        1.0 + 2.0 ** -8 + 2.0 ** -30: 0x3F81,    # would round to the tie first if it went through float32
+        1.0 + 3 * 2.0 ** -8: 0x3F82,             # tie between odd 0x3F81 and even 0x3F82
+        -2.5: 0xC020, 0.0: 0x0000, 2.0 ** -133: 0x0001, 2.0 ** -134: 0x0000, 1.5 * 2.0 ** -133: 0x0002,
+        3.3895313892515355e38: 0x7F7F, 3.4e38: 0x7F80,
+    }
+    xs = np.array(list(cases.keys()))
+    assert [int(b) for b in vo.round_to_bf16_bits(xs)] == list(cases.values())
+    assert int(vo.round_to_bf16_bits(np.array([-0.0]))[0]) == 0x8000
+    # library conversion on float32-exact inputs (no double rounding possible there)
+    import torch
+    r = np.random.default_rng(3).standard_normal(200000).astype(np.float32) * np.float32(7.0)
+    want = torch.from_numpy(r).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(vo.round_to_bf16_bits(r.astype(np.float64)), want)
+    # rounding is idempotent and monotone
+    b = vo.round_to_bf16_bits(r.astype(np.float64))
+    assert np.array_equal(vo.round_to_bf16_bits(vo.widen(b)), b)
+    srt = np.sort(r.astype(np.float64))
+    assert (np.diff(vo.widen(vo.round_to_bf16_bits(srt))) >= 0).all()
+
+
+def test_rmsnorm_definition():
+    # hand case: h = (3, 4), gamma = (1, 2): mean square 12.5, x = (3, 8) / sqrt(12.5) = (0.848528.., 2.262741..)
+    h = np.array([[3.0, 4.0]], dtype=np.float32); g = np.array([1.0, 2.0], dtype=np.float32)
+    x, inv = vo.rmsnorm_rows(h, g, 0.0)
+    assert x.dtype == np.float32 and abs(inv[0] - 1 / math.sqrt(12.5)) < 1e-15
+    assert np.allclose(x, [[0.8485281374, 2.2627416998]], rtol=1e-7)
+    xb, _ = vo.rmsnorm_rows(bf16_bits_from_f32(h), bf16_bits_from_f32(g), 0.0)
+    assert xb.dtype == np.uint16 and [int(v) for v in xb[0]] == [0x3F59, 0x4011]   # 0.84765625, 2.265625
+    # epsilon sits inside the square root, added to the MEAN square
+    x, _ = vo.rmsnorm_rows(np.ones((1, 2), dtype=np.float32), np.ones(2, dtype=np.float32), 3.0)
+    assert np.array_equal(x, [[0.5, 0.5]])
+    # independent library routine, float64
+    import torch
+    rng = np.random.default_rng(0)
+    h = (rng.standard_normal((5, 3, 96)) * rng.uniform(0.1, 30, size=(5, 3, 1))).astype(np.float32)
+    g = (1 + 0.1 * rng.standard_normal(96)).astype(np.float32)
+    want = torch.nn.functional.rms_norm(torch.from_numpy(h).double(), (96,), torch.from_numpy(g).double(), eps=1e-5).numpy()
+    x32, inv = vo.rmsnorm_rows(h, g, 1e-5)
+    assert np.array_equal(x32, want.astype(np.float32)) or np.allclose(x32, want, rtol=2e-7, atol=0)
+    xb, _ = vo.rmsnorm_rows(bf16_bits_from_f32(h), bf16_bits_from_f32(g), 1e-5)
+    hb = f32_from_bf16_bits(bf16_bits_from_f32(h)).astype(np.float64); gb = f32_from_bf16_bits(bf16_bits_from_f32(g)).astype(np.float64)
+    wantb = torch.nn.functional.rms_norm(torch.from_numpy(hb), (96,), torch.from_numpy(gb), eps=1e-5).numpy()
+    got = vo.widen(xb)
+    assert (np.abs(got - wantb) <= np.abs(wantb) * 2.0 ** -8 + 1e-300).all()          # within half a bf16 step
+    assert (np.abs(got - wantb) <= np.abs(vo.widen(xb + 1) - wantb) + 1e-300).all()     # and nearer than the next code
+    # invariants: unit gain, eps = 0 -> unit rms; scaling a row by a power of two changes nothing at all
+    x1, _ = vo.rmsnorm_rows(h, np.ones(96, dtype=np.float32), 0.0)
+    assert np.allclose(np.sqrt(np.mean(x1.astype(np.float64) ** 2, axis=-1)), 1.0, atol=1e-6)
+    x2, _ = vo.rmsnorm_rows(bf16_bits_from_f32(h * 4), bf16_bits_from_f32(g), 0.0)
+    x3, _ = vo.rmsnorm_rows(bf16_bits_from_f32(h), bf16_bits_from_f32(g), 0.0)
+    assert np.array_equal(x2, x3)
+
+
+def test_prenorm_wiring_of_the_judge():
+    # Sec. 4.1: LM head after the final RMS norm, judge on the embedding before it
+    from synth import RMS_EPS
+    shape = VerifyShape("t", 6, 5, 64, 200, "bf16", 1.0)
+    x = make_inputs(shape, 4, prenorm=True)
+    assert "emb" not in x and x["hidden"].dtype == np.uint16 and x["gamma"].shape == (64,) and x["rms_eps"] == RMS_EPS
+    emb, inv = vo.rmsnorm_rows(x["hidden"], x["gamma"], x["rms_eps"])
+    out = vo.verify(emb, x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+                    emb_judge=x["hidden"], return_probs=True)
+    H = vo.widen(x["hidden"]); w = vo.widen(x["w_judge"])
+    assert np.allclose(out["judge_logit"], np.einsum("bjk,k->bj", H[:, 1:, :], w), rtol=1e-13, atol=1e-13)
+    # the LM head saw the normalised rows: probabilities are those of softmax(norm(h) W)
+    Xn = vo.widen(emb).reshape(-1, 64)
+    L = (Xn @ vo.widen(x["W"]).T)
+    P = np.exp(L - L.max(1, keepdims=True)); P /= P.sum(1, keepdims=True)
+    assert np.allclose(out["probs"].reshape(-1, 200), P, rtol=1e-12, atol=1e-15)
+    # rows have very different scales before the norm and unit-ish rms after it
+    rms_before = np.sqrt(np.mean(H ** 2, axis=-1)); rms_after = np.sqrt(np.mean(vo.widen(emb) ** 2, axis=-1))
+    assert rms_before.max() / rms_before.min() > 3 and np.allclose(rms_after, 1.0, atol=0.1)
+    # with delta = 0.5 and no bias the judge decision is the sign of w.h, which the positive row
+    # scale 1/rms cannot change: judging the scaled row gives the same mask
+    scaled = (H * inv[..., None])
+    assert np.array_equal(out["z_judge"], (np.einsum("bjk,k->bj", scaled[:, 1:, :], w) > 0).astype(out["z_judge"].dtype))
+    # a sane workload: the draft is a noisy copy of the target, so some but not all slots pass
+    assert 0 < out["z_stand"].mean() < 1 and (out["status"] == 0).all()
