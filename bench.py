@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--rule", default="sampling", choices=["sampling", "topk"],
                     help="acceptance rule: Eq. 4 speculative sampling, or top-K verification (Sec. 5 baseline)")
     ap.add_argument("--top-k", type=int, default=1)
+    ap.add_argument("--prenorm", action="store_true",
+                    help="the paper's wiring (Sec. 4.1): hand over pre-norm hidden states; the library applies the "
+                         "final RMS normalisation for the LM head and the judge reads the hidden states")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the timed region, so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
@@ -72,7 +75,7 @@ def main() -> int:
     R = B * (M + 1)
 
     t0 = time.time()
-    x = make_inputs(shape, args.seed)
+    x = make_inputs(shape, args.seed, prenorm=args.prenorm)
     log(f"[bench] inputs for {shape.name} drawn in {time.time() - t0:.1f}s")
     dev = harness.to_device(x)
     rule_kw = {} if args.rule == "sampling" else {"rule": jb.JD_RULE_TOPK, "top_k": args.top_k}
@@ -81,8 +84,15 @@ def main() -> int:
     torch.cuda.synchronize()
     log(f"[bench] context ready, workspace {ver.workspace_bytes() / 2**30:.2f} GiB")
 
-    def step():
-        ver.run(dev["emb"], dev["draft_tokens"], dev["draft_logits"], dev["uniforms"], out)
+    if args.prenorm:
+        rms_eps = float(x["rms_eps"])
+
+        def step():
+            ver.run_prenorm(dev["hidden"], dev["gamma"], rms_eps, dev["draft_tokens"], dev["draft_logits"],
+                            dev["uniforms"], out)
+    else:
+        def step():
+            ver.run(dev["emb"], dev["draft_tokens"], dev["draft_logits"], dev["uniforms"], out)
 
     for _ in range(args.warmup):
         step()
@@ -153,6 +163,8 @@ def main() -> int:
                                f"{'FP8 E4M3 (+fp32 row scales)' if shape.dtype == 'fp8' else shape.dtype} W_lm, "
                                f"fp32 draft logits; {shape.note}", "seed": args.seed,
                    "rule": args.rule if args.rule == "sampling" else f"topk(K={args.top_k})",
+                   "wiring": "pre-norm hidden states in, RMS norm inside the call" if args.prenorm
+                             else "normalised embeddings in",
                    "rows": R, "W_lm_bytes": w_bytes,
                    "W_lm_retiled_copy": shape.dtype in ("bf16", "fp8")},
         "roofline": roofline,
@@ -175,7 +187,12 @@ def main() -> int:
         seqs = list(range(B)) if R <= 32 else list(range(max(1, 26 // (M + 1))))
         t0 = time.perf_counter()
         okw = {} if args.rule == "sampling" else {"rule": vo.RULE_TOPK, "top_k": args.top_k}
-        ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+        if args.prenorm:
+            emb_ref, _ = vo.rmsnorm_rows(x["hidden"], x["gamma"], x["rms_eps"])
+            okw["emb_judge"] = x["hidden"]
+        else:
+            emb_ref = x["emb"]
+        ref = vo.verify(emb_ref, x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
                         seqs=seqs, w_scale=x.get("w_scale"), **okw)
         t_cpu = time.perf_counter() - t0
         record["cpu_baseline"] = {

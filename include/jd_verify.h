@@ -157,6 +157,25 @@ int jd_verify_run(jd_verify_ctx* ctx, int32_t B, int32_t M,
                   const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
                   const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream);
 
+/*
+ * The same call in the paper's own wiring (Sec. 4.1, "Model design and training": the judge is
+ * trained on the target's last embedding BEFORE the final RMS normalisation, the LM head reads
+ * it after).  The caller hands over the pre-norm hidden states once; the library normalises them
+ * for the LM head and feeds them as they are to the judge:
+ *   x[r, k] = round( h[r, k] * gamma[k] / sqrt(mean_k(h[r, k]^2) + rms_eps) )
+ * computed in float64 and rounded once, to nearest even, to emb_dtype (the rounded tensor is what
+ * the LM head multiplies; it lives in the context's workspace and is overwritten by every call).
+ *   d_hidden       [B, M+1, d]   pre-norm hidden states, emb_dtype; also the judge input
+ *   d_gamma        [d]           gain of the normalisation, emb_dtype
+ *   rms_eps        >= 0, finite  added to the mean square
+ * Everything else, and the error behaviour, as for jd_verify_run; INVALID_ARG also for a NULL
+ * d_gamma or an rms_eps that is negative or not finite.
+ */
+int jd_verify_run_prenorm(jd_verify_ctx* ctx, int32_t B, int32_t M,
+                          const void* d_hidden, const void* d_gamma, double rms_eps,
+                          const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
+                          const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream);
+
 /* Free the workspace and the context.  destroy(NULL) is a no-op returning JD_OK.
  * Caller memory is never freed. */
 int jd_verify_destroy(jd_verify_ctx* ctx);

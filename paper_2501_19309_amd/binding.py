@@ -29,7 +29,7 @@ JD_K_LMHEAD, JD_K_DRAFTSTAT, JD_K_ACCEPT, JD_K_SAMPLER, JD_NUM_KERNELS = 0, 1, 2
 KERNEL_NAMES = ("lmhead", "draftstat", "accept", "sampler")
 
 EXPORTED_SYMBOLS = (
-    "jd_verify_create", "jd_verify_create_scaled", "jd_verify_run", "jd_verify_destroy", "jd_verify_strerror",
+    "jd_verify_create", "jd_verify_create_scaled", "jd_verify_run", "jd_verify_run_prenorm", "jd_verify_destroy", "jd_verify_strerror",
     "jd_verify_profile_begin", "jd_verify_profile_end", "jd_verify_workspace_bytes",
     "jd_verify_validate_config",
 )
@@ -79,6 +79,9 @@ def load_library() -> ctypes.CDLL:
     lib.jd_verify_create_scaled.restype = ctypes.c_int
     lib.jd_verify_run.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, vp, ctypes.POINTER(jd_verify_outputs), vp]
     lib.jd_verify_run.restype = ctypes.c_int
+    lib.jd_verify_run_prenorm.argtypes = [vp, i32, i32, vp, vp, ctypes.c_double, vp, vp, i32, vp,
+                                          ctypes.POINTER(jd_verify_outputs), vp]
+    lib.jd_verify_run_prenorm.restype = ctypes.c_int
     lib.jd_verify_destroy.argtypes = [vp]
     lib.jd_verify_destroy.restype = ctypes.c_int
     lib.jd_verify_strerror.argtypes = [ctypes.c_int]
@@ -185,6 +188,30 @@ class JDVerify:
                                     draft.shape[1], _ptr(uniforms), ctypes.byref(o), ctypes.c_void_p(stream))
         if rc != JD_OK:
             raise JDError(rc, "jd_verify_run")
+
+    def run_prenorm(self, hidden, gamma, rms_eps: float, draft_tokens, draft, uniforms, out: VerifyOutputs, *,
+                    stream=None) -> None:
+        """jd_verify_run_prenorm: pre-norm hidden states in, normalised for the LM head by the library."""
+        B, Mp1 = hidden.shape[0], hidden.shape[1]
+        M = Mp1 - 1
+        o = jd_verify_outputs(*[_ptr(getattr(out, n)) for n in (
+            "accept_len", "next_token", "status", "z_stand", "z_judge", "p_at_draft", "q_at_draft",
+            "judge_logit", "row_max", "row_sumexp", "probs")])
+        if stream is None:
+            stream = self._torch.cuda.current_stream().cuda_stream
+        rc = self.lib.jd_verify_run_prenorm(self.handle, B, M, _ptr(hidden), _ptr(gamma), float(rms_eps),
+                                            _ptr(draft_tokens), _ptr(draft), draft.shape[1], _ptr(uniforms),
+                                            ctypes.byref(o), ctypes.c_void_p(stream))
+        if rc != JD_OK:
+            raise JDError(rc, "jd_verify_run_prenorm")
+
+    def run_prenorm_raw(self, B, M, hidden, gamma, rms_eps, draft_tokens, draft, draft_rows, uniforms,
+                        outputs: jd_verify_outputs, stream=0) -> int:
+        """Direct call returning the error code (used by the error-path tests)."""
+        return self.lib.jd_verify_run_prenorm(self.handle, B, M, hidden, gamma, float(rms_eps), draft_tokens, draft,
+                                              draft_rows, uniforms,
+                                              ctypes.byref(outputs) if outputs is not None else None,
+                                              ctypes.c_void_p(stream))
 
     def run_raw(self, B, M, emb, emb_judge, draft_tokens, draft, draft_rows, uniforms, outputs: jd_verify_outputs,
                 stream=0) -> int:

@@ -211,6 +211,12 @@ hipError_t launch_rank(const float* L, int Lld, const int32_t* tokens, int B, in
 hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const int32_t* accept_len, int B, int M,
                          int V, int* chunk_arg, int nChunk, int32_t* next_token, hipStream_t st);
 
+// Final RMS normalisation of R rows of d values (Sec. 4.1: the LM head reads the embedding after it):
+// Xn[r][k] = round(H[r][k] * gamma[k] / sqrt(mean_k H[r][k]^2 + eps)), float64 arithmetic, one
+// round-to-nearest-even to the storage type (bf16 bit patterns, or fp32 when !is_bf16).
+hipError_t launch_rmsnorm_rows(const void* H, const void* gamma, double eps, int is_bf16, int R, int d, void* Xn,
+                               hipStream_t st);
+
 // probs[r*V + v] = exp(L[r*Lld + v] - t_max[r]) / t_sum[r]
 hipError_t launch_probs(const float* L, int Lld, const float* t_max, const float* t_sum, int R, int V,
                         float* probs, hipStream_t st);

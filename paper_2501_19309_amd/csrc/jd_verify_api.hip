@@ -28,6 +28,7 @@ struct jd_verify_ctx {
   double* chunk_mass;   // [max_B][nChunk] (the top-K rule reuses it as ints)
   int* rankpart;        // [max_B*max_M][kRankSplits], top-K rule only
   void* Xp;             // packed embeddings for the GEMM regime
+  void* Xn;             // [max_R][d] normalised embeddings of the pre-norm entry point
   int nPartT, nPartD, nChunk;
   uint64_t bytes;
   float judge_threshold;
@@ -82,7 +83,7 @@ extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
 
 static void free_ctx(jd_verify_ctx* c) {
   if (!c) return;
-  void* ptrs[] = {c->Wp, c->Wp8, c->L, c->tpart, c->dpart, c->t_max, c->t_sum, c->q_max, c->q_sum, c->g, c->chunk_mass, c->Xp, c->rankpart};
+  void* ptrs[] = {c->Wp, c->Wp8, c->L, c->tpart, c->dpart, c->t_max, c->t_sum, c->q_max, c->q_sum, c->g, c->chunk_mass, c->Xp, c->Xn, c->rankpart};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -173,6 +174,11 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
     rc = dev_alloc(c, &xp, gemm_xp_bytes((int)maxR, c->geo));
     c->Xp = xp;
   }
+  if (rc == JD_OK) {
+    uint8_t* xn = nullptr;
+    rc = dev_alloc(c, &xn, maxR * (size_t)cfg->d * (cfg->emb_dtype == JD_BF16 ? 2 : 4));
+    c->Xn = xn;
+  }
   if (rc != JD_OK) { free_ctx(c); return rc; }
   *out_ctx = c;
   return JD_OK;
@@ -225,10 +231,14 @@ extern "C" int jd_verify_profile_end(jd_verify_ctx* ctx, float* avg_ms, int32_t*
 
 #define JD_HIP(expr) do { if ((expr) != hipSuccess) return JD_ERR_HIP; } while (0)
 
-extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, const void* d_emb_judge,
-                             const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
-                             const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream) {
-  if (!c || !d_emb || !d_draft_tokens || !d_draft || !d_uniforms || !out) return JD_ERR_INVALID_ARG;
+// One verify call.  With d_hidden != NULL the LM-head input is the RMS-normalised d_hidden (written
+// to the context's Xn) and the judge reads d_hidden itself; d_emb / d_emb_judge are then ignored.
+static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, const void* d_emb_judge,
+                    const void* d_hidden, const void* d_gamma, double rms_eps, const int32_t* d_draft_tokens,
+                    const float* d_draft, int32_t draft_rows, const float* d_uniforms, const jd_verify_outputs* out,
+                    void* hip_stream) {
+  if (!c || (!d_emb && !d_hidden) || !d_draft_tokens || !d_draft || !d_uniforms || !out) return JD_ERR_INVALID_ARG;
+  if (d_hidden && (!d_gamma || !(rms_eps >= 0.0) || !std::isfinite(rms_eps))) return JD_ERR_INVALID_ARG;
   if (!out->d_accept_len || !out->d_next_token || !out->d_status) return JD_ERR_INVALID_ARG;
   if (B < 1 || M < 1 || B > c->cfg.max_B || M > c->cfg.max_M) return JD_ERR_SHAPE;
   if (draft_rows != M && draft_rows != M + 1) return JD_ERR_SHAPE;
@@ -244,6 +254,12 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
   hipEvent_t* ev = nullptr;
   if (c->prof_on && c->prof_n < c->prof_max) ev = &c->ev[(size_t)(c->prof_n++) * (JD_NUM_KERNELS + 1)];
   if (ev) JD_HIP(hipEventRecord(ev[0], st));
+
+  if (d_hidden) {  // pre-norm wiring: normalise for the LM head, judge on the hidden states as they are
+    JD_HIP(launch_rmsnorm_rows(d_hidden, d_gamma, rms_eps, cfg.emb_dtype == JD_BF16, R, cfg.d, c->Xn, st));
+    d_emb = c->Xn;
+    d_emb_judge = d_hidden;
+  }
 
   // Draft row statistics (first pass of the draft softmax) and the judge dot products do not
   // depend on the LM head.  In the small-row regime they ride in the LM-head launch as extra
@@ -328,4 +344,21 @@ extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void*
 
   if (out->d_probs) JD_HIP(launch_probs(c->L, g.Vpad, c->t_max, c->t_sum, R, cfg.V, out->d_probs, st));
   return JD_OK;
+}
+
+extern "C" int jd_verify_run(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, const void* d_emb_judge,
+                             const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
+                             const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream) {
+  if (!d_emb) return JD_ERR_INVALID_ARG;
+  return run_impl(c, B, M, d_emb, d_emb_judge, nullptr, nullptr, 0.0, d_draft_tokens, d_draft, draft_rows, d_uniforms,
+                  out, hip_stream);
+}
+
+extern "C" int jd_verify_run_prenorm(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_hidden, const void* d_gamma,
+                                     double rms_eps, const int32_t* d_draft_tokens, const float* d_draft,
+                                     int32_t draft_rows, const float* d_uniforms, const jd_verify_outputs* out,
+                                     void* hip_stream) {
+  if (!d_hidden) return JD_ERR_INVALID_ARG;
+  return run_impl(c, B, M, nullptr, nullptr, d_hidden, d_gamma, rms_eps, d_draft_tokens, d_draft, draft_rows,
+                  d_uniforms, out, hip_stream);
 }

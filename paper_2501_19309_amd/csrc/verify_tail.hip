@@ -444,4 +444,102 @@ hipError_t launch_probs(const float* L, int Lld, const float* t_max, const float
   return hipGetLastError();
 }
 
+// ---- final RMS normalisation (pre-norm wiring) --------------------------------------------
+// One workgroup per row.  float64 throughout: the products h*h and h*gamma are exact, the sum, the
+// reciprocal square root and the last product round once each, so the value that is finally
+// rounded to the storage type agrees with a float64 reference to ~1e-16 and the stored bits agree
+// unless the value sits that close to a rounding tie.
+
+constexpr int kNormThreads = 1024;
+
+__device__ __forceinline__ double block_sum_f64(double v, double* sh) {  // kNormThreads threads
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  double t = 0.0;
+#pragma unroll
+  for (int w = 0; w < kNormThreads / 64; ++w) t += sh[w];
+  __syncthreads();
+  return t;
+}
+
+// float64 -> bfloat16, round to nearest even, through a float32 that is truncated and carries a
+// sticky bit (round to odd), so that the two steps together round exactly once.
+__device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
+  const float f = __double2float_rz(x);
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+  if ((double)f != x) u |= 1u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ double bf16_to_f64(uint32_t bits16) { return (double)__uint_as_float(bits16 << 16); }
+
+// bf16 rows, d % 8 == 0: 128-bit loads and stores, eight values per lane per trip
+__global__ __launch_bounds__(kNormThreads) void rmsnorm_rows_bf16_kernel(const uint4* __restrict__ H,
+                                                                         const uint4* __restrict__ G, double eps,
+                                                                         int d, uint4* __restrict__ X) {
+  __shared__ double sh[kNormThreads / 64];
+  const int nv = d / 8;
+  const uint4* h = H + (size_t)blockIdx.x * nv;
+  uint4* x = X + (size_t)blockIdx.x * nv;
+  double ss = 0.0;
+  for (int k = threadIdx.x; k < nv; k += kNormThreads) {
+    const uint4 v = h[k];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double lo = bf16_to_f64(w[i] & 0xffffu), hi = bf16_to_f64(w[i] >> 16);
+      ss += lo * lo;
+      ss += hi * hi;
+    }
+  }
+  ss = block_sum_f64(ss, sh);
+  const double inv = 1.0 / sqrt(ss / (double)d + eps);
+  for (int k = threadIdx.x; k < nv; k += kNormThreads) {
+    const uint4 v = h[k], gv = G[k];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t lo = f64_to_bf16_rne(bf16_to_f64(w[i] & 0xffffu) * bf16_to_f64(gw[i] & 0xffffu) * inv);
+      const uint32_t hi = f64_to_bf16_rne(bf16_to_f64(w[i] >> 16) * bf16_to_f64(gw[i] >> 16) * inv);
+      o[i] = lo | (hi << 16);
+    }
+    x[k] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+__global__ __launch_bounds__(kNormThreads) void rmsnorm_rows_f32_kernel(const float* __restrict__ H,
+                                                                        const float* __restrict__ G, double eps,
+                                                                        int d, float* __restrict__ X) {
+  __shared__ double sh[kNormThreads / 64];
+  const float* h = H + (size_t)blockIdx.x * d;
+  float* x = X + (size_t)blockIdx.x * d;
+  double ss = 0.0;
+  for (int k = threadIdx.x; k < d; k += kNormThreads) {
+    const double v = (double)h[k];
+    ss += v * v;
+  }
+  ss = block_sum_f64(ss, sh);
+  const double inv = 1.0 / sqrt(ss / (double)d + eps);
+  for (int k = threadIdx.x; k < d; k += kNormThreads) x[k] = (float)((double)h[k] * (double)G[k] * inv);
+}
+
+hipError_t launch_rmsnorm_rows(const void* H, const void* gamma, double eps, int is_bf16, int R, int d, void* Xn,
+                               hipStream_t st) {
+  if (R <= 0 || d <= 0 || !H || !gamma || !Xn) return hipErrorInvalidValue;
+  if (is_bf16) {
+    if (d % 8 != 0) return hipErrorInvalidValue;  // the bf16 path requires it everywhere (128-bit rows)
+    hipLaunchKernelGGL(rmsnorm_rows_bf16_kernel, dim3(R), dim3(kNormThreads), 0, st, static_cast<const uint4*>(H),
+                       static_cast<const uint4*>(gamma), eps, d, static_cast<uint4*>(Xn));
+  } else {
+    hipLaunchKernelGGL(rmsnorm_rows_f32_kernel, dim3(R), dim3(kNormThreads), 0, st, static_cast<const float*>(H),
+                       static_cast<const float*>(gamma), eps, d, static_cast<float*>(Xn));
+  }
+  return hipGetLastError();
+}
+
 }  // namespace jd

@@ -18,8 +18,8 @@ def to_device(inputs: Dict[str, np.ndarray], device: int = 0):
 
     dev = torch.device("cuda", device)
     out = {}
-    for k in ("emb", "W", "w_judge", "w_scale", "draft_logits", "draft_tokens", "uniforms", "emb_judge",
-              "draft_probs"):
+    for k in ("emb", "hidden", "gamma", "W", "w_judge", "w_scale", "draft_logits", "draft_tokens", "uniforms",
+              "emb_judge", "draft_probs"):
         if k not in inputs or inputs[k] is None:
             continue
         a = np.ascontiguousarray(inputs[k])
@@ -35,7 +35,7 @@ def make_verifier(dev_inputs, *, max_B: Optional[int] = None, max_M: Optional[in
                   w_layout: int = jb.JD_W_VD, **cfg_kw) -> jb.JDVerify:
     import torch
 
-    emb, W = dev_inputs["emb"], dev_inputs["W"]
+    emb, W = dev_inputs.get("emb", dev_inputs.get("hidden")), dev_inputs["W"]
     B, Mp1, d = emb.shape
     V = W.shape[0] if w_layout == jb.JD_W_VD else W.shape[1]
     dt = {torch.bfloat16: jb.JD_BF16, torch.uint8: jb.JD_FP8_E4M3}.get(W.dtype, jb.JD_F32)
@@ -52,12 +52,16 @@ def run_once(inputs: Dict[str, np.ndarray], *, want_probs: bool = False, device:
     dev_in = to_device(inputs, device)
     ver = make_verifier(dev_in, device=device, w_layout=w_layout, **cfg_kw)
     try:
-        emb = dev_in["emb"]
+        emb = dev_in.get("emb", dev_in.get("hidden"))
         B, M = emb.shape[0], emb.shape[1] - 1
         out = ver.alloc_outputs(B, M, want_probs)
         draft = dev_in["draft_probs"] if cfg_kw.get("draft_kind", jb.JD_DRAFT_LOGITS) == jb.JD_DRAFT_PROBS \
             else dev_in["draft_logits"]
-        ver.run(emb, dev_in["draft_tokens"], draft, dev_in["uniforms"], out, emb_judge=dev_in.get("emb_judge"))
+        if "hidden" in dev_in:   # pre-norm wiring: the library normalises, the judge reads the hidden states
+            ver.run_prenorm(dev_in["hidden"], dev_in["gamma"], float(inputs["rms_eps"]), dev_in["draft_tokens"], draft,
+                            dev_in["uniforms"], out)
+        else:
+            ver.run(emb, dev_in["draft_tokens"], draft, dev_in["uniforms"], out, emb_judge=dev_in.get("emb_judge"))
         torch.cuda.synchronize(device)
         return out.to_numpy()
     finally:

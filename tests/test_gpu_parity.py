@@ -6,7 +6,7 @@ import pytest
 
 from oracle import verify_oracle as vo
 from oracle.compare import compare
-from synth import CONFIGS, VerifyShape, make_inputs
+from synth import CONFIGS, VerifyShape, bf16_bits_from_f32, make_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -366,6 +366,88 @@ def test_run_argument_errors(jd):
     assert jb.load_library().jd_verify_destroy(None) == jb.JD_OK
 
 
+# ----------------------------------------------------------------------------- pre-norm wiring (Sec. 4.1)
+
+PRENORM = [
+    VerifyShape("n_f32", 3, 5, 100, 1000, "f32", 1.0),
+    VerifyShape("n_bf16_skinny", 2, 9, 264, 1000, "bf16", 1.5),      # R = 20: judge rides beside the LM head
+    VerifyShape("n_bf16_R64", 4, 15, 768, 3000, "bf16", 1.0),
+    VerifyShape("n_bf16_gemm176", 9, 10, 512, 5000, "bf16", (0.5, 2.5)),   # R = 99
+    VerifyShape("n_bf16_gemm352", 32, 10, 520, 4100, "bf16", (0.5, 2.0)),  # R = 352
+    VerifyShape("n_fp8", 1, 25, 512, 2048, "fp8", 1.0),
+]
+
+
+def prenorm_oracle(x, **kw):
+    emb, _ = vo.rmsnorm_rows(x["hidden"], x["gamma"], x["rms_eps"])
+    if "w_scale" in x:
+        kw.setdefault("w_scale", x["w_scale"])
+    return vo.verify(emb, x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+                     emb_judge=x["hidden"], **kw)
+
+
+@pytest.mark.parametrize("shape", PRENORM, ids=lambda s: s.name)
+def test_prenorm_wiring_matches_oracle(jd, shape):
+    print(f"[case] {shape.name}", flush=True)
+    for seed in (0, 1):
+        x = make_inputs(shape, seed, prenorm=True)
+        ref = prenorm_oracle(x, return_probs=True)
+        got = jd.run_once(x, want_probs=True)
+        rep = compare(got, ref)
+        print(rep, flush=True)
+
+
+def test_prenorm_rounding_is_the_oracles(jd):
+    # identity LM head: the logits ARE the normalised, rounded embeddings, so the probabilities give them
+    # back to ~1e-6 while one bf16 step is 4e-3 relative: every rounding decision of the kernel is checked
+    d = V = 1024
+    shape = VerifyShape("t", 4, 15, d, V, "bf16", 1.0)
+    x = make_inputs(shape, 2, prenorm=True)
+    x["W"] = bf16_bits_from_f32(np.eye(V, dtype=np.float32))
+    got = jd.run_once(x, want_probs=True)
+    emb, _ = vo.rmsnorm_rows(x["hidden"], x["gamma"], x["rms_eps"])
+    want = vo.widen(emb)
+    back = np.log(got["probs"].astype(np.float64)) + np.log(got["row_sumexp"].astype(np.float64))[..., None] \
+        + got["row_max"].astype(np.float64)[..., None]
+    err = np.abs(back - want)
+    print("max |recovered - oracle| =", err.max(), "; smallest bf16 step among the values:",
+          (np.abs(want)[want != 0] * 2.0 ** -8).min(), flush=True)
+    assert err.max() < 2e-5
+    # the same through the fp32 path: rounded once to float32
+    shape = VerifyShape("t", 2, 3, 64, 64, "f32", 1.0)
+    x = make_inputs(shape, 3, prenorm=True)
+    x["W"] = np.eye(64, dtype=np.float32)
+    got = jd.run_once(x, want_probs=True)
+    emb, _ = vo.rmsnorm_rows(x["hidden"], x["gamma"], x["rms_eps"])
+    back = np.log(got["probs"].astype(np.float64)) + np.log(got["row_sumexp"].astype(np.float64))[..., None] \
+        + got["row_max"].astype(np.float64)[..., None]
+    assert np.abs(back - emb.astype(np.float64)).max() < 2e-5
+
+
+def test_prenorm_argument_errors(jd):
+    from paper_2501_19309_amd import binding as jb, harness
+    x = make_inputs(VerifyShape("t", 2, 4, 64, 256, "bf16", 1.0), 0, prenorm=True)
+    dev = harness.to_device(x)
+    ver = harness.make_verifier(dev)
+    try:
+        o = ver.alloc_outputs(2, 4)
+        outs = jb.jd_verify_outputs(o.accept_len.data_ptr(), o.next_token.data_ptr(), o.status.data_ptr())
+        a = dict(hidden=dev["hidden"].data_ptr(), gamma=dev["gamma"].data_ptr(), rms_eps=1e-5,
+                 draft_tokens=dev["draft_tokens"].data_ptr(), draft=dev["draft_logits"].data_ptr(), draft_rows=5,
+                 uniforms=dev["uniforms"].data_ptr(), outputs=outs)
+        assert ver.run_prenorm_raw(2, 4, **a) == jb.JD_OK
+        assert ver.run_prenorm_raw(2, 4, **{**a, "gamma": None}) == jb.JD_ERR_INVALID_ARG
+        assert ver.run_prenorm_raw(2, 4, **{**a, "hidden": None}) == jb.JD_ERR_INVALID_ARG
+        assert ver.run_prenorm_raw(2, 4, **{**a, "rms_eps": -1e-5}) == jb.JD_ERR_INVALID_ARG
+        assert ver.run_prenorm_raw(2, 4, **{**a, "rms_eps": float("nan")}) == jb.JD_ERR_INVALID_ARG
+        assert ver.run_prenorm_raw(2, 4, **{**a, "rms_eps": float("inf")}) == jb.JD_ERR_INVALID_ARG
+        assert ver.run_prenorm_raw(3, 4, **a) == jb.JD_ERR_SHAPE
+        import torch
+        torch.cuda.synchronize()
+    finally:
+        ver.destroy()
+
+
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C4q"])
 def test_full_size_single_sequence(jd, name):
     # full-size configs in the launch configuration the benchmark times; the oracle
@@ -378,6 +460,17 @@ def test_full_size_single_sequence(jd, name):
     ref = oracle_for(x)
     rep = compare(got, ref)
     print(name, rep, flush=True)
+
+
+def test_full_size_prenorm_C4(jd):
+    # the headline shape through the pre-norm entry point, as `bench.py --prenorm` times it
+    print("[case] C4 prenorm", flush=True)
+    x = make_inputs(CONFIGS["C4"], 0, prenorm=True)
+    print("[inputs ready]", flush=True)
+    got = jd.run_once(x)
+    print("[gpu done]", got["accept_len"], got["next_token"], flush=True)
+    rep = compare(got, prenorm_oracle(x))
+    print("C4 prenorm", rep, flush=True)
 
 
 def test_full_size_batched_sampled_sequences(jd):
