@@ -176,12 +176,34 @@ int jd_verify_run_prenorm(jd_verify_ctx* ctx, int32_t B, int32_t M,
                           const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
                           const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream);
 
+/*
+ * The step after a verify call (Sec. 3.1, end of the paragraph after Eq. 4: the accepted tokens and
+ * the one new token are added to the context), stream-ordered so that a decode loop needs no host
+ * synchronisation between calls.  For each sequence b, with n = d_accept_len[b] in [0, M]:
+ *   d_token_buf[b, len .. len+n-1] = d_draft_tokens[b, 0 .. n-1];  d_token_buf[b, len+n] = d_next_token[b];
+ *   d_lengths[b] = len + n + 1,                         where len = d_lengths[b] before the call.
+ * Tokens that would land at or beyond `cap` are dropped and the length saturates at cap; an
+ * accept_len outside [0, M] is clamped into it.
+ *   d_draft_tokens [B, M] int32, d_accept_len [B] int32, d_next_token [B] int32  (inputs, device)
+ *   d_token_buf    [B, cap] int32, d_lengths [B] int32                          (updated in place, device)
+ * Stateless: needs no context, allocates nothing, does not synchronise.
+ * Errors: INVALID_ARG (NULL pointer), SHAPE (B < 1, M < 1, cap < 1), HIP.
+ */
+int jd_verify_append_tokens(int32_t B, int32_t M, const int32_t* d_draft_tokens, const int32_t* d_accept_len,
+                            const int32_t* d_next_token, int32_t* d_token_buf, int32_t cap, int32_t* d_lengths,
+                            void* hip_stream);
+
 /* Free the workspace and the context.  destroy(NULL) is a no-op returning JD_OK.
  * Caller memory is never freed. */
 int jd_verify_destroy(jd_verify_ctx* ctx);
 
 /* Static, NUL-terminated description of an error code. */
 const char* jd_verify_strerror(int code);
+
+/* For JD_ERR_HIP / JD_ERR_OOM: which HIP call failed last in the calling thread and what the
+ * runtime said ("" if none yet).  Thread-local storage owned by the library, overwritten by the
+ * next failure in the same thread. */
+const char* jd_verify_last_error_detail(void);
 
 /*
  * Per-kernel timing with HIP events on the stream passed to jd_verify_run.

@@ -396,6 +396,21 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
 
 # --------------------------------------------------------------------------- scalar tier
 
+def append_tokens(token_buf: np.ndarray, lengths: np.ndarray, draft_tokens: np.ndarray, accept_len: np.ndarray,
+                  next_token: np.ndarray) -> None:
+    """The step after verification (Sec. 3.1, end of the paragraph after Eq. 4): the accepted draft
+    tokens c_1..c_m* and the one new token are added to the sequence's context.  In place on
+    token_buf [B, cap] / lengths [B]; tokens that do not fit into cap are dropped and the length
+    saturates at cap."""
+    B, cap = token_buf.shape
+    for b in range(B):
+        new = [int(t) for t in draft_tokens[b, :int(accept_len[b])]] + [int(next_token[b])]
+        for t in new:
+            if lengths[b] < cap:
+                token_buf[b, lengths[b]] = t
+                lengths[b] += 1
+
+
 def verify_scalar(emb, W, w_judge, draft_tokens, draft, uniforms, *, mode=MODE_JUDGE,
                   draft_kind=DRAFT_LOGITS, temperature=1.0, delta=0.5, judge_bias=0.0):
     """The same definition written as plain Python loops over scalars.

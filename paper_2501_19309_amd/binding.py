@@ -29,7 +29,8 @@ JD_K_LMHEAD, JD_K_DRAFTSTAT, JD_K_ACCEPT, JD_K_SAMPLER, JD_NUM_KERNELS = 0, 1, 2
 KERNEL_NAMES = ("lmhead", "draftstat", "accept", "sampler")
 
 EXPORTED_SYMBOLS = (
-    "jd_verify_create", "jd_verify_create_scaled", "jd_verify_run", "jd_verify_run_prenorm", "jd_verify_destroy", "jd_verify_strerror",
+    "jd_verify_create", "jd_verify_create_scaled", "jd_verify_run", "jd_verify_run_prenorm", "jd_verify_append_tokens",
+    "jd_verify_destroy", "jd_verify_strerror", "jd_verify_last_error_detail",
     "jd_verify_profile_begin", "jd_verify_profile_end", "jd_verify_workspace_bytes",
     "jd_verify_validate_config",
 )
@@ -56,7 +57,10 @@ class jd_verify_outputs(ctypes.Structure):
 class JDError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__(f"{where}: {strerror(code)} ({code})")
+        detail = ""
+        if code in (JD_ERR_HIP, JD_ERR_OOM) and _lib is not None:
+            detail = (_lib.jd_verify_last_error_detail() or b"").decode()
+        super().__init__(f"{where}: {strerror(code)} ({code})" + (f" [{detail}]" if detail else ""))
 
 
 _lib = None
@@ -71,6 +75,11 @@ def load_library() -> ctypes.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2501_19309_amd.build` "
             "(there is no fallback path)")
+    # The device tensors this binding hands over come from PyTorch, which ships its own copy of the HIP
+    # runtime.  Loading PyTorch first makes the library's libamdhip64 dependency resolve to that same,
+    # already loaded copy; the other order puts two runtimes into the process and the second one finds
+    # no device ("no ROCm-capable device is detected" from every call of the library).
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32 = ctypes.c_void_p, ctypes.c_int32
     lib.jd_verify_create.argtypes = [ctypes.POINTER(jd_verify_config), vp, vp, ctypes.POINTER(vp)]
@@ -82,10 +91,14 @@ def load_library() -> ctypes.CDLL:
     lib.jd_verify_run_prenorm.argtypes = [vp, i32, i32, vp, vp, ctypes.c_double, vp, vp, i32, vp,
                                           ctypes.POINTER(jd_verify_outputs), vp]
     lib.jd_verify_run_prenorm.restype = ctypes.c_int
+    lib.jd_verify_append_tokens.argtypes = [i32, i32, vp, vp, vp, vp, i32, vp, vp]
+    lib.jd_verify_append_tokens.restype = ctypes.c_int
     lib.jd_verify_destroy.argtypes = [vp]
     lib.jd_verify_destroy.restype = ctypes.c_int
     lib.jd_verify_strerror.argtypes = [ctypes.c_int]
     lib.jd_verify_strerror.restype = ctypes.c_char_p
+    lib.jd_verify_last_error_detail.argtypes = []
+    lib.jd_verify_last_error_detail.restype = ctypes.c_char_p
     lib.jd_verify_profile_begin.argtypes = [vp, i32]
     lib.jd_verify_profile_begin.restype = ctypes.c_int
     lib.jd_verify_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -115,6 +128,19 @@ def make_config(d, V, max_B, max_M, *, w_dtype=JD_BF16, emb_dtype=None, w_layout
 
 def jd_verify_validate_config(cfg: jd_verify_config) -> int:
     return load_library().jd_verify_validate_config(ctypes.byref(cfg))
+
+
+def append_tokens(draft_tokens, accept_len, next_token, token_buf, lengths, stream=None) -> None:
+    """jd_verify_append_tokens on torch device tensors (int32): grows token_buf [B, cap] / lengths [B] in place."""
+    import torch
+    B, M = draft_tokens.shape
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    rc = load_library().jd_verify_append_tokens(B, M, _ptr(draft_tokens), _ptr(accept_len), _ptr(next_token),
+                                                _ptr(token_buf), token_buf.shape[1], _ptr(lengths),
+                                                ctypes.c_void_p(stream))
+    if rc != JD_OK:
+        raise JDError(rc, "jd_verify_append_tokens")
 
 
 def _ptr(t) -> Optional[int]:

@@ -217,6 +217,12 @@ hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const int3
 hipError_t launch_rmsnorm_rows(const void* H, const void* gamma, double eps, int is_bf16, int R, int d, void* Xn,
                                hipStream_t st);
 
+// Append the accepted draft tokens and the new token of every sequence to its token buffer
+// (Sec. 3.1, after Eq. 4); one wavefront per sequence.
+hipError_t launch_append_tokens(int B, int M, const int32_t* draft_tokens, const int32_t* accept_len,
+                                const int32_t* next_token, int32_t* token_buf, int cap, int32_t* lengths,
+                                hipStream_t st);
+
 // probs[r*V + v] = exp(L[r*Lld + v] - t_max[r]) / t_sum[r]
 hipError_t launch_probs(const float* L, int Lld, const float* t_max, const float* t_sum, int R, int V,
                         float* probs, hipStream_t st);

@@ -4,6 +4,7 @@
 #include "../../include/jd_verify.h"
 
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <new>
 #include <vector>
@@ -40,6 +41,18 @@ struct jd_verify_ctx {
 
 static const int kDraftSplits = 16;   // column ranges per draft row in the statistics pass
 static const int kF32Splits = 8;      // same for target logits on the fp32 path
+
+// What the last failing HIP call of this thread was, for jd_verify_last_error_detail().
+static thread_local char g_detail[320] = "";
+static int hip_fail(const char* what, hipError_t e) {
+  std::snprintf(g_detail, sizeof g_detail, "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+  (void)hipGetLastError();
+  return e == hipErrorOutOfMemory ? JD_ERR_OOM : JD_ERR_HIP;
+}
+#define JD_HIP(expr) do { const hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(#expr, e_); } while (0)
+#define JD_HIP_RC(expr) do { const hipError_t e_ = (expr); if (rc == JD_OK && e_ != hipSuccess) rc = hip_fail(#expr, e_); } while (0)
+
+extern "C" const char* jd_verify_last_error_detail(void) { return g_detail; }
 
 extern "C" const char* jd_verify_strerror(int code) {
   switch (code) {
@@ -96,8 +109,7 @@ static int dev_alloc(jd_verify_ctx* c, T** p, size_t n) {
   hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes);
   if (e != hipSuccess) {
     *p = nullptr;
-    (void)hipGetLastError();
-    return e == hipErrorOutOfMemory ? JD_ERR_OOM : JD_ERR_HIP;
+    return hip_fail("hipMalloc of workspace", e);
   }
   c->bytes += bytes;
   return JD_OK;
@@ -118,10 +130,14 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
   if (d_w_scale && cfg->w_dtype != JD_FP8_E4M3) return JD_ERR_INVALID_ARG;
 
   int ndev = 0;
-  if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device >= ndev) { (void)hipGetLastError(); return JD_ERR_HIP; }
-  if (hipSetDevice(cfg->device) != hipSuccess) return JD_ERR_HIP;
+  JD_HIP(hipGetDeviceCount(&ndev));
+  if (cfg->device >= ndev) return hip_fail("config.device is not a visible device", hipErrorInvalidDevice);
+  JD_HIP(hipSetDevice(cfg->device));
   hipDeviceProp_t prop;
-  if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) return JD_ERR_HIP;
+  JD_HIP(hipGetDeviceProperties(&prop, cfg->device));
+  // The launchers report hipGetLastError(); a stale code left in this thread by an earlier, unrelated
+  // runtime call of the caller (an event query that was "not ready", say) must not be taken for theirs.
+  (void)hipGetLastError();
 
   jd_verify_ctx* c = new (std::nothrow) jd_verify_ctx();
   if (!c) return JD_ERR_OOM;
@@ -155,19 +171,15 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
     uint8_t* wp8 = nullptr;
     rc = dev_alloc(c, &wp8, c->geo.packed8_bytes());
     c->Wp8 = wp8;
-    if (rc == JD_OK && (launch_pack_w8(d_W_lm, cfg->w_layout, c->geo, c->Wp8, nullptr) != hipSuccess ||
-                        hipDeviceSynchronize() != hipSuccess))
-      rc = JD_ERR_HIP;
+    JD_HIP_RC(launch_pack_w8(d_W_lm, cfg->w_layout, c->geo, c->Wp8, nullptr));
+    JD_HIP_RC(hipDeviceSynchronize());
   }
   if (rc == JD_OK && bf16 && (!fp8 || maxR > 64)) {  // FP8 contexts need the bf16 copy only for the GEMM regime
     uint8_t* wp = nullptr;
     rc = dev_alloc(c, &wp, c->geo.packed_bytes());
     c->Wp = wp;
-    if (rc == JD_OK) {
-      if (launch_pack_w(d_W_lm, cfg->w_layout, fp8 ? 1 : 0, c->geo, c->Wp, nullptr) != hipSuccess ||
-          hipDeviceSynchronize() != hipSuccess)
-        rc = JD_ERR_HIP;
-    }
+    JD_HIP_RC(launch_pack_w(d_W_lm, cfg->w_layout, fp8 ? 1 : 0, c->geo, c->Wp, nullptr));
+    JD_HIP_RC(hipDeviceSynchronize());
   }
   if (rc == JD_OK && bf16 && maxR > 64) {
     uint8_t* xp = nullptr;
@@ -203,7 +215,7 @@ extern "C" int jd_verify_profile_begin(jd_verify_ctx* ctx, int32_t max_calls) {
   const size_t need = (size_t)max_calls * (JD_NUM_KERNELS + 1);
   while (ctx->ev.size() < need) {
     hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return JD_ERR_HIP;
+    JD_HIP(hipEventCreate(&e));
     ctx->ev.push_back(e);
   }
   ctx->prof_on = true; ctx->prof_max = max_calls; ctx->prof_n = 0;
@@ -216,10 +228,10 @@ extern "C" int jd_verify_profile_end(jd_verify_ctx* ctx, float* avg_ms, int32_t*
   double sum[JD_NUM_KERNELS] = {0, 0, 0, 0};
   for (int i = 0; i < ctx->prof_n; ++i) {
     hipEvent_t* e = &ctx->ev[(size_t)i * (JD_NUM_KERNELS + 1)];
-    if (hipEventSynchronize(e[JD_NUM_KERNELS]) != hipSuccess) return JD_ERR_HIP;
+    JD_HIP(hipEventSynchronize(e[JD_NUM_KERNELS]));
     for (int k = 0; k < JD_NUM_KERNELS; ++k) {
       float ms = 0.f;
-      if (hipEventElapsedTime(&ms, e[k], e[k + 1]) != hipSuccess) return JD_ERR_HIP;
+      JD_HIP(hipEventElapsedTime(&ms, e[k], e[k + 1]));
       sum[k] += ms;
     }
   }
@@ -228,8 +240,6 @@ extern "C" int jd_verify_profile_end(jd_verify_ctx* ctx, float* avg_ms, int32_t*
   ctx->prof_n = 0;
   return JD_OK;
 }
-
-#define JD_HIP(expr) do { if ((expr) != hipSuccess) return JD_ERR_HIP; } while (0)
 
 // One verify call.  With d_hidden != NULL the LM-head input is the RMS-normalised d_hidden (written
 // to the context's Xn) and the judge reads d_hidden itself; d_emb / d_emb_judge are then ignored.
@@ -243,6 +253,7 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
   if (B < 1 || M < 1 || B > c->cfg.max_B || M > c->cfg.max_M) return JD_ERR_SHAPE;
   if (draft_rows != M && draft_rows != M + 1) return JD_ERR_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  (void)hipGetLastError();  // drop a stale code of the caller's own runtime calls (see create)
   const jd_verify_config& cfg = c->cfg;
   const Geometry& g = c->geo;
   const int R = B * (M + 1);
@@ -361,4 +372,15 @@ extern "C" int jd_verify_run_prenorm(jd_verify_ctx* c, int32_t B, int32_t M, con
   if (!d_hidden) return JD_ERR_INVALID_ARG;
   return run_impl(c, B, M, nullptr, nullptr, d_hidden, d_gamma, rms_eps, d_draft_tokens, d_draft, draft_rows,
                   d_uniforms, out, hip_stream);
+}
+
+extern "C" int jd_verify_append_tokens(int32_t B, int32_t M, const int32_t* d_draft_tokens, const int32_t* d_accept_len,
+                                       const int32_t* d_next_token, int32_t* d_token_buf, int32_t cap,
+                                       int32_t* d_lengths, void* hip_stream) {
+  if (!d_draft_tokens || !d_accept_len || !d_next_token || !d_token_buf || !d_lengths) return JD_ERR_INVALID_ARG;
+  if (B < 1 || M < 1 || M > 63 || cap < 1) return JD_ERR_SHAPE;
+  (void)hipGetLastError();  // drop a stale code of the caller's own runtime calls
+  JD_HIP(launch_append_tokens(B, M, d_draft_tokens, d_accept_len, d_next_token, d_token_buf, cap, d_lengths,
+                              static_cast<hipStream_t>(hip_stream)));
+  return JD_OK;
 }

@@ -542,4 +542,32 @@ hipError_t launch_rmsnorm_rows(const void* H, const void* gamma, double eps, int
   return hipGetLastError();
 }
 
+// ---- the step after verification: grow each sequence's context ------------------------------
+// One wavefront per sequence; lane i < n copies accepted draft token i, lane n writes the new token.
+__global__ __launch_bounds__(256) void append_tokens_kernel(int B, int M, const int32_t* __restrict__ draft_tokens,
+                                                            const int32_t* __restrict__ accept_len,
+                                                            const int32_t* __restrict__ next_token,
+                                                            int32_t* __restrict__ token_buf, int cap,
+                                                            int32_t* __restrict__ lengths) {
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (b >= B) return;
+  const int n = min(max(accept_len[b], 0), M);  // M <= 63: one lane per token
+  const int len = min(max(lengths[b], 0), cap);
+  if (lane <= n) {
+    const int32_t t = lane < n ? draft_tokens[(size_t)b * M + lane] : next_token[b];
+    if (len + lane < cap) token_buf[(size_t)b * cap + len + lane] = t;
+  }
+  if (lane == 0) lengths[b] = min(len + n + 1, cap);
+}
+
+hipError_t launch_append_tokens(int B, int M, const int32_t* draft_tokens, const int32_t* accept_len,
+                                const int32_t* next_token, int32_t* token_buf, int cap, int32_t* lengths,
+                                hipStream_t st) {
+  if (B < 1 || M < 1 || M > 63 || cap < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(append_tokens_kernel, dim3((B + 3) / 4), dim3(256), 0, st, B, M, draft_tokens, accept_len,
+                     next_token, token_buf, cap, lengths);
+  return hipGetLastError();
+}
+
 }  // namespace jd

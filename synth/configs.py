@@ -25,7 +25,7 @@ from __future__ import annotations
 import os
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
-from typing import Dict, Tuple, Union
+from typing import Dict, Optional, Tuple, Union
 
 import numpy as np
 
@@ -121,8 +121,13 @@ def _n_threads() -> int:
     return max(1, min(16, avail))
 
 
-def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False) -> Dict[str, np.ndarray]:
+def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False,
+                weights_seed: Optional[int] = None) -> Dict[str, np.ndarray]:
     """Draw every input of one verify call.
+
+    weights_seed (default: seed) selects the streams of the model's own tensors (W_lm, w_judge, the
+    norm gain): several calls with one weights_seed and different seeds are different batches for the
+    same model, as a decode loop sees them.
 
     prenorm=True draws the workload in the paper's wiring (Sec. 4.1: the judge sees the last target
     embedding before the final RMS normalisation): instead of ``emb`` the dict holds
@@ -155,7 +160,7 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False) -> Dic
         # pre-norm hidden states: the unit-rms rows times a log-normal scale per row; gain near 1
         rowscale = np.exp(_stream(seed, _TAG_ROWSCALE).standard_normal(R).astype(np.float32) * np.float32(0.7))
         hid = h * rowscale[:, None] * np.float32(3.0)
-        gam = (np.float32(1.0) + np.float32(0.1) * _stream(seed, _TAG_GAMMA).standard_normal(d, dtype=np.float32))
+        gam = (np.float32(1.0) + np.float32(0.1) * _stream(seed if weights_seed is None else weights_seed, _TAG_GAMMA).standard_normal(d, dtype=np.float32))
         if is_bf16:
             hidden_store = bf16_bits_from_f32(hid); hid = f32_from_bf16_bits(hidden_store)
             gamma_store = bf16_bits_from_f32(gam); gam = f32_from_bf16_bits(gamma_store)
@@ -169,7 +174,8 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False) -> Dic
     else:
         emb_store = h.copy()
 
-    wj = _stream(seed, _TAG_JUDGE).standard_normal(d, dtype=np.float32) * np.float32(1.0 / np.sqrt(d))
+    wseed = seed if weights_seed is None else weights_seed
+    wj = _stream(wseed, _TAG_JUDGE).standard_normal(d, dtype=np.float32) * np.float32(1.0 / np.sqrt(d))
     wj_store = bf16_bits_from_f32(wj) if is_bf16 else wj
 
     if isinstance(shape.noise, tuple):
@@ -189,7 +195,7 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False) -> Dic
     def draw_chunk(ci: int):
         v0 = ci * _VOCAB_CHUNK
         rows = min(_VOCAB_CHUNK, V - v0)
-        w = _stream(seed, _TAG_W, ci).standard_normal((rows, d), dtype=np.float32)
+        w = _stream(wseed, _TAG_W, ci).standard_normal((rows, d), dtype=np.float32)
         w *= inv_sqrt_d
         noise = _stream(seed, _TAG_NOISE, ci).standard_normal((R, rows), dtype=np.float32)
         gumbel = _stream(seed, _TAG_GUMBEL, ci).gumbel(size=(R, rows)).astype(np.float32)

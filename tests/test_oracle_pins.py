@@ -694,3 +694,28 @@ def test_prenorm_wiring_of_the_judge():
     assert np.array_equal(out["z_judge"], (np.einsum("bjk,k->bj", scaled[:, 1:, :], w) > 0).astype(out["z_judge"].dtype))
     # a sane workload: the draft is a noisy copy of the target, so some but not all slots pass
     assert 0 < out["z_stand"].mean() < 1 and (out["status"] == 0).all()
+
+
+# ----------------------------------------------------------------------------- the step after: growing the context
+
+def test_append_tokens_hand_cases():
+    # Sec. 3.1: accepted tokens, then the one new token, are added to the context
+    buf = np.full((3, 6), -1, dtype=np.int32); buf[0, 0] = 7
+    lengths = np.array([1, 0, 5], dtype=np.int64)
+    draft = np.array([[5, 6, 9], [1, 2, 3], [11, 12, 13]], dtype=np.int32)
+    vo.append_tokens(buf, lengths, draft, np.array([2, 0, 3]), np.array([8, 4, 14]))
+    assert buf[0].tolist() == [7, 5, 6, 8, -1, -1] and lengths[0] == 4      # two accepted + replacement
+    assert buf[1].tolist() == [4, -1, -1, -1, -1, -1] and lengths[1] == 1   # nothing accepted: only the new token
+    assert buf[2].tolist() == [-1, -1, -1, -1, -1, 11] and lengths[2] == 6  # full buffer: the rest is dropped
+    vo.append_tokens(buf, lengths, draft, np.array([3, 3, 3]), np.array([8, 4, 14]))
+    assert buf[0].tolist() == [7, 5, 6, 8, 5, 6] and lengths[0] == 6 and lengths[2] == 6
+    assert buf[1].tolist() == [4, 1, 2, 3, 4, -1] and lengths[1] == 5
+    # a call always emits accept_len + 1 tokens: at least one, at most M + 1
+    x = make_inputs(VerifyShape("t", 16, 4, 16, 64, "f32", 1.5), 2)
+    out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"])
+    buf = np.zeros((16, 8), dtype=np.int32); lengths = np.zeros(16, dtype=np.int64)
+    vo.append_tokens(buf, lengths, x["draft_tokens"], out["accept_len"], out["next_token"])
+    assert np.array_equal(lengths, out["accept_len"] + 1) and lengths.min() >= 1 and lengths.max() <= 5
+    for b in range(16):
+        n = int(out["accept_len"][b])
+        assert np.array_equal(buf[b, :n], x["draft_tokens"][b, :n]) and buf[b, n] == out["next_token"][b]
