@@ -72,7 +72,7 @@ from typing import Dict, Iterable, Optional, Sequence
 import numpy as np
 
 STATUS_BAD_TOKEN = 1      # a draft token id was outside [0, V)
-STATUS_NAN = 2            # a NaN appeared in target logits, draft row or judge logit
+STATUS_NAN = 2            # a NaN in target logits, draft row or judge logit, or a row that is no distribution
 STATUS_ZERO_RESIDUAL = 4  # residual mass was exactly zero; fell back to sampling from p
 
 MODE_JUDGE = 0     # z = z_stand OR z_judge
@@ -346,6 +346,8 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
         if np.isnan(Dm).any():
             status |= STATUS_NAN
         Q = softmax_rows(Dm)[0] if draft_kind == DRAFT_LOGITS else Dm
+        if np.isnan(Q).any() or np.isnan(P).any():             # e.g. a row without one finite logit: no distribution
+            status |= STATUS_NAN
         E = widen(ej_src[b])                                   # judge input rows
         z = []
         for j in range(M):

@@ -20,6 +20,16 @@ __device__ __forceinline__ MS ms_combine(MS a, MS b) {
   return o;
 }
 
+// Fold one logit into the state.  A logit of -inf (a masked token) has probability zero and leaves
+// the state alone; a NaN makes the sum NaN.
+__device__ __forceinline__ MS ms_push(MS st, float x) {
+  if (x != x) { st.s = NAN; return st; }
+  if (x == -INFINITY) return st;
+  if (x > st.m) { st.s *= __expf(st.m - x); st.m = x; }
+  st.s += __expf(x - st.m);
+  return st;
+}
+
 __device__ __forceinline__ MS ms_wave_reduce(MS v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -62,23 +72,34 @@ __device__ __forceinline__ void rowstats_block(const RowStatsArgs& a, int row, i
   if (((reinterpret_cast<uintptr_t>(p) & 15) == 0)) {  // splitLen is a multiple of 4
     const int nvec = (c1 > c0) ? (c1 - c0) / 4 : 0;
     const float4* p4 = reinterpret_cast<const float4*>(p + c0);
-    for (int i = tid; i < nvec; i += 256) {
-      const float4 x = p4[i];
-      const float m4 = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
-      if (m4 > st.m) { st.s *= __expf(st.m - m4); st.m = m4; }
-      st.s += __expf(x.x - st.m) + __expf(x.y - st.m) + __expf(x.z - st.m) + __expf(x.w - st.m);
+    // four 128-bit loads per thread are in flight before any of them is used; a batch is folded in
+    // around its own maximum (one rescale of the running sum, sixteen independent exps)
+    constexpr int kBatch = 4;
+    for (int i0 = 0; i0 < nvec; i0 += 256 * kBatch) {
+      float4 x[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int i = i0 + u * 256 + tid;
+        x[u] = (i < nvec) ? p4[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      }
+      float mb = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) mb = fmaxf(mb, fmaxf(fmaxf(x[u].x, x[u].y), fmaxf(x[u].z, x[u].w)));
+      bool nan = false;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) nan = nan || (x[u].x != x[u].x) || (x[u].y != x[u].y) || (x[u].z != x[u].z) || (x[u].w != x[u].w);
+      if (nan) { st.s = NAN; continue; }     // fmaxf drops NaNs: keep them visible in the sum
+      if (mb == -INFINITY) continue;          // padding, or logits of -inf: probability zero
+      if (mb > st.m) { st.s *= __expf(st.m - mb); st.m = mb; }
+      float add = 0.f;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        add += (__expf(x[u].x - st.m) + __expf(x[u].y - st.m)) + (__expf(x[u].z - st.m) + __expf(x[u].w - st.m));
+      st.s += add;
     }
-    for (int c = c0 + nvec * 4 + tid; c < c1; c += 256) {
-      const float x = p[c];
-      if (x > st.m) { st.s *= __expf(st.m - x); st.m = x; }
-      st.s += __expf(x - st.m);
-    }
+    for (int c = c0 + nvec * 4 + tid; c < c1; c += 256) st = ms_push(st, p[c]);
   } else {
-    for (int c = c0 + tid; c < c1; c += 256) {
-      const float x = p[c];
-      if (x > st.m) { st.s *= __expf(st.m - x); st.m = x; }
-      st.s += __expf(x - st.m);
-    }
+    for (int c = c0 + tid; c < c1; c += 256) st = ms_push(st, p[c]);
   }
   const MS o = ms_block_reduce(st, red);
   if (tid == 0) a.part[(size_t)row * a.nSplit + split] = make_float2(o.m, o.s);

@@ -285,6 +285,31 @@ def test_separate_judge_embedding(jd):
     assert not np.array_equal(base["judge_logit"], ref["judge_logit"].astype(np.float32))
 
 
+def test_masked_draft_logits(jd):
+    # a filtered draft distribution: logits of -inf (probability zero), also at the start of every column
+    # range the statistics pass splits a row into, and on a drafted token itself (q[c] = 0: Eq. 4 then
+    # accepts iff p[c] > 0)
+    for shape in (VerifyShape("m_skinny", 3, 6, 256, 3001, "bf16", 1.0), VerifyShape("m_gemm", 9, 10, 256, 5000, "bf16", 1.5),
+                  VerifyShape("m_f32", 2, 4, 64, 515, "f32", 1.0)):
+        x = make_inputs(shape, 6)
+        D = x["draft_logits"].copy()
+        rng = np.random.default_rng(1)
+        mask = rng.random(D.shape) < 0.3
+        mask[..., :min(700, shape.V // 4)] = True   # a long run of masked tokens from column 0 on
+        for b in range(shape.B):          # drafted tokens keep their mass ...
+            for j in range(shape.M):
+                mask[b, j, x["draft_tokens"][b, j]] = False
+        mask[0, 1, x["draft_tokens"][0, 1]] = True   # ... except one
+        D[mask] = -np.inf
+        x["draft_logits"] = D
+        ref = oracle_for(x)
+        got = jd.run_once(x)
+        rep = compare(got, ref)
+        assert (ref["status"] == 0).all() and (got["status"] == 0).all(), (ref["status"], got["status"])
+        assert got["q_at_draft"][0, 1] == 0.0 and got["z_stand"][0, 1] == 1
+        print(shape.name, rep, flush=True)
+
+
 def test_status_bits(jd):
     shape = VerifyShape("t", 4, 5, 128, 640, "bf16", 1.0)
     x = make_inputs(shape, 9)
@@ -299,6 +324,12 @@ def test_status_bits(jd):
     for b in (0, 1, 2):
         assert int(got["accept_len"][b]) == int(ref["accept_len"][b])
         assert int(got["next_token"][b]) == int(ref["next_token"][b])
+    # a draft row with every token masked (-inf) is no distribution (Eq. 3): reported like a NaN
+    x["draft_logits"][3, 1, 17] = 0.5
+    x["draft_logits"][0, 2, :] = -np.inf
+    ref = oracle_for(x)
+    got = jd.run_once(x)
+    assert (got["status"].astype(np.int64) & 0xFFFFFFFF).tolist() == ref["status"].tolist() == [2, 1, 1, 0]
     # draft == target logits: q == p, no residual mass at a forced rejection -> flag + sample from p
     y = make_inputs(VerifyShape("t", 2, 4, 64, 512, "f32", 1.0), 1)
     L = vo.target_logits(y["emb"].reshape(-1, 64), y["W"]).reshape(2, 5, 512)

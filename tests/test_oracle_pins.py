@@ -719,3 +719,22 @@ def test_append_tokens_hand_cases():
     for b in range(16):
         n = int(out["accept_len"][b])
         assert np.array_equal(buf[b, :n], x["draft_tokens"][b, :n]) and buf[b, n] == out["next_token"][b]
+
+
+def test_masked_draft_tokens_and_rows():
+    # a filtered draft: -inf logits have probability zero; a drafted token with q[c] = 0 passes Eq. 4
+    # iff p[c] > 0 (the division-free form eps * 0 < p); a row of nothing but -inf is no distribution
+    x = make_inputs(VerifyShape("t", 2, 3, 16, 40, "f32", 1.0), 3)
+    D = x["draft_logits"].copy()
+    c = int(x["draft_tokens"][0, 1])
+    D[0, 1, c] = -np.inf
+    D[0, 0, :10] = -np.inf
+    with np.errstate(invalid="ignore"):
+        out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], D, x["uniforms"], mode=vo.MODE_STANDARD)
+    assert out["q_at_draft"][0, 1] == 0.0 and out["z_stand"][0, 1] == 1 and (out["status"] == 0).all()
+    q0 = scipy.special.softmax(D[0, 0].astype(np.float64))
+    assert (q0[:10] == 0).all() and abs(out["q_at_draft"][0, 0] - q0[int(x["draft_tokens"][0, 0])]) < 1e-15
+    D[1, 2, :] = -np.inf
+    with np.errstate(invalid="ignore"):
+        out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], D, x["uniforms"], mode=vo.MODE_STANDARD)
+    assert out["status"].tolist() == [0, vo.STATUS_NAN]
