@@ -29,9 +29,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
 # what the same counter reads for a plain 1 GiB copy (profiles/lmhead_skinny_C4_hbm_traffic.md,
-# profiles/lmhead_gemm_C5_counters.md);
+# profiles/lmhead_gemm_C5_counters.md, profiles/verify_call_C4q_fp8_kernel_stats_and_traffic.md);
 # None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 4.2533e9, "C5": 2.888e9}  # fetched + written
+MEASURED_TRAFFIC_BYTES = {"C4": 4.2533e9, "C4q": 2.1496e9, "C5": 2.855e9}  # fetched + written
 
 
 def log(*a):

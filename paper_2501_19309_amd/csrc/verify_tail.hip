@@ -477,29 +477,29 @@ __device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
 
 __device__ __forceinline__ double bf16_to_f64(uint32_t bits16) { return (double)__uint_as_float(bits16 << 16); }
 
-// bf16 rows, d % 8 == 0: 128-bit loads and stores, eight values per lane per trip
+// bf16 rows, d % 8 == 0: 128-bit loads and stores, eight values per lane per trip.  The first
+// kKeep trips of a lane (rows up to kKeep * 8192 values) stay in registers between the two passes,
+// and the gain is fetched beside them, so that a row costs one trip to memory.
 __global__ __launch_bounds__(kNormThreads) void rmsnorm_rows_bf16_kernel(const uint4* __restrict__ H,
                                                                          const uint4* __restrict__ G, double eps,
                                                                          int d, uint4* __restrict__ X) {
+  constexpr int kKeep = 2;
   __shared__ double sh[kNormThreads / 64];
   const int nv = d / 8;
   const uint4* h = H + (size_t)blockIdx.x * nv;
   uint4* x = X + (size_t)blockIdx.x * nv;
-  double ss = 0.0;
-  for (int k = threadIdx.x; k < nv; k += kNormThreads) {
-    const uint4 v = h[k];
+  auto sum_sq = [](const uint4& v) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    double s = 0.0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const double lo = bf16_to_f64(w[i] & 0xffffu), hi = bf16_to_f64(w[i] >> 16);
-      ss += lo * lo;
-      ss += hi * hi;
+      s += lo * lo;
+      s += hi * hi;
     }
-  }
-  ss = block_sum_f64(ss, sh);
-  const double inv = 1.0 / sqrt(ss / (double)d + eps);
-  for (int k = threadIdx.x; k < nv; k += kNormThreads) {
-    const uint4 v = h[k], gv = G[k];
+    return s;
+  };
+  auto scale = [](const uint4& v, const uint4& gv, double inv) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w};
     uint32_t o[4];
 #pragma unroll
@@ -508,8 +508,27 @@ __global__ __launch_bounds__(kNormThreads) void rmsnorm_rows_bf16_kernel(const u
       const uint32_t hi = f64_to_bf16_rne(bf16_to_f64(w[i] >> 16) * bf16_to_f64(gw[i] >> 16) * inv);
       o[i] = lo | (hi << 16);
     }
-    x[k] = make_uint4(o[0], o[1], o[2], o[3]);
+    return make_uint4(o[0], o[1], o[2], o[3]);
+  };
+  uint4 hv[kKeep], gv[kKeep];
+#pragma unroll
+  for (int u = 0; u < kKeep; ++u) {
+    const int k = threadIdx.x + u * kNormThreads;
+    hv[u] = (k < nv) ? h[k] : make_uint4(0u, 0u, 0u, 0u);
+    gv[u] = (k < nv) ? G[k] : make_uint4(0u, 0u, 0u, 0u);
   }
+  double ss = 0.0;
+#pragma unroll
+  for (int u = 0; u < kKeep; ++u) ss += sum_sq(hv[u]);
+  for (int k = threadIdx.x + kKeep * kNormThreads; k < nv; k += kNormThreads) ss += sum_sq(h[k]);
+  ss = block_sum_f64(ss, sh);
+  const double inv = 1.0 / sqrt(ss / (double)d + eps);
+#pragma unroll
+  for (int u = 0; u < kKeep; ++u) {
+    const int k = threadIdx.x + u * kNormThreads;
+    if (k < nv) x[k] = scale(hv[u], gv[u], inv);
+  }
+  for (int k = threadIdx.x + kKeep * kNormThreads; k < nv; k += kNormThreads) x[k] = scale(h[k], G[k], inv);
 }
 
 __global__ __launch_bounds__(kNormThreads) void rmsnorm_rows_f32_kernel(const float* __restrict__ H,
