@@ -371,6 +371,39 @@ def test_determinism_and_context_reuse(jd):
         ver.destroy()
 
 
+def test_side_stream_and_two_contexts(jd):
+    # work is enqueued on the stream the caller passes (here a non-default one, default priority), and two
+    # contexts with different shapes live side by side without disturbing each other
+    import torch
+    from paper_2501_19309_amd import harness
+    xa = make_inputs(VerifyShape("a", 3, 9, 264, 3000, "bf16", 1.0), 31)     # small-row regime
+    xb = make_inputs(VerifyShape("b", 20, 10, 256, 2100, "bf16", 1.5), 32)   # 352-row tiles
+    da, db = harness.to_device(xa), harness.to_device(xb)
+    va, vb = harness.make_verifier(da), harness.make_verifier(db)
+    try:
+        oa, ob = va.alloc_outputs(3, 9), vb.alloc_outputs(20, 10)
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            for _ in range(3):   # interleaved, all on the side stream
+                va.run(da["emb"], da["draft_tokens"], da["draft_logits"], da["uniforms"], oa)
+                vb.run(db["emb"], db["draft_tokens"], db["draft_logits"], db["uniforms"], ob)
+        side.synchronize()
+        compare(oa.to_numpy(), oracle_for(xa))
+        compare(ob.to_numpy(), oracle_for(xb))
+        # the same calls on the default stream give the same bits
+        ga, gb = oa.to_numpy(), ob.to_numpy()
+        va.run(da["emb"], da["draft_tokens"], da["draft_logits"], da["uniforms"], oa)
+        vb.run(db["emb"], db["draft_tokens"], db["draft_logits"], db["uniforms"], ob)
+        torch.cuda.synchronize()
+        for k, v in oa.to_numpy().items():
+            assert np.array_equal(v, ga[k], equal_nan=True), k
+        for k, v in ob.to_numpy().items():
+            assert np.array_equal(v, gb[k], equal_nan=True), k
+    finally:
+        va.destroy(); vb.destroy()
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
