@@ -139,6 +139,9 @@ hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X
 // choice when gemm_prefers_352(R), i.e. when 352-row tiles add no padding rows over 176-row tiles.
 hipError_t launch_lmhead_gemm_dma(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
                                   float invT, float* L, float2* part, void* Xp, hipStream_t st);
+// Once per process before the first launch of either kernel (they use more dynamic LDS than the default limit).
+hipError_t init_lmhead_gemm();
+hipError_t init_lmhead_gemm_dma();
 inline bool gemm_prefers_352(int R) {
   return (R + kDmaRows - 1) / kDmaRows * kDmaRows == (R + kGemmRows - 1) / kGemmRows * kGemmRows;
 }

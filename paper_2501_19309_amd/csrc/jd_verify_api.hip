@@ -182,6 +182,10 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
     JD_HIP_RC(hipDeviceSynchronize());
   }
   if (rc == JD_OK && bf16 && maxR > 64) {
+    JD_HIP_RC(init_lmhead_gemm());
+    JD_HIP_RC(init_lmhead_gemm_dma());
+  }
+  if (rc == JD_OK && bf16 && maxR > 64) {
     uint8_t* xp = nullptr;
     rc = dev_alloc(c, &xp, gemm_xp_bytes((int)maxR, c->geo));
     c->Xp = xp;

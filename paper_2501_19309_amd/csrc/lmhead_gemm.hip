@@ -284,6 +284,15 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   }
 }
 
+constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * sizeof(uint4);
+
+// More LDS than the default limit of a launch: raised once per process, at context creation (not in the
+// launcher, which may run under stream capture).
+hipError_t init_lmhead_gemm() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+}
+
 hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
                               float invT, float* L, float2* part, void* Xp, int /*num_cus*/, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
@@ -294,15 +303,7 @@ hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
-  constexpr size_t kLds = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * sizeof(uint4);
-  static bool attr_set = false;
-  if (!attr_set) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(lmhead_gemm_kernel, dim3(grid), dim3(256), kLds, st, static_cast<const uint4*>(Wp), vscale,
+  hipLaunchKernelGGL(lmhead_gemm_kernel, dim3(grid), dim3(256), kGemmLdsBytes, st, static_cast<const uint4*>(Wp), vscale,
                      static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG, g.nVGalloc, nRowTiles, nVocabTiles, invT,
                      L, g.Vpad, part);
   return hipGetLastError();

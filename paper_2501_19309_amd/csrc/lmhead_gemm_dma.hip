@@ -288,6 +288,13 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   }
 }
 
+// More LDS than the default limit of a launch: raised once per process, at context creation (not in the
+// launcher, which may run under stream capture).
+hipError_t init_lmhead_gemm_dma() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes);
+}
+
 hipError_t launch_lmhead_gemm_dma(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
                                   float invT, float* L, float2* part, void* Xp, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
@@ -300,13 +307,6 @@ hipError_t launch_lmhead_gemm_dma(const void* Wp, const float* vscale, const voi
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
-  static bool attr_set = false;
-  if (!attr_set) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   hipLaunchKernelGGL(lmhead_gemm_dma_kernel, dim3(grid), dim3(256), kDmaLdsBytes, st, static_cast<const uint4*>(Wp),
                      vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG, g.nVGalloc, nRowTiles, nVocabTiles,
                      invT, L, g.Vpad, part);

@@ -73,7 +73,7 @@ def make_batches(shape, n_sets: int, seed: int, prenorm: bool):
     return host, dev
 
 
-def loop_benchmark(config: str, iters: int, n_sets: int, seed: int, prenorm: bool) -> dict:
+def loop_benchmark(config: str, iters: int, n_sets: int, seed: int, prenorm: bool, graph: bool = False) -> dict:
     import torch
     from synth import CONFIGS
 
@@ -119,6 +119,26 @@ def loop_benchmark(config: str, iters: int, n_sets: int, seed: int, prenorm: boo
         "emitted_tokens_per_s": float(L.sum()) / (ms_loop * 1e-3 * iters),
         "verified_positions_per_s": B * M / (ms_loop * 1e-3),
     }
+    if graph:
+        # the same iterations as HIP graphs: one captured (verify + append) per resident batch, replayed in turn
+        graphs = []
+        for k in range(n_sets):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                enqueue_loop(ver, dev[k:k + 1], outs[k:k + 1], token_buf, lengths, 1)
+            graphs.append(g)
+        token_buf.zero_(); lengths.zero_()
+        for i in range(20):
+            graphs[i % n_sets].replay()
+        torch.cuda.synchronize()
+        token_buf.zero_(); lengths.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(iters):
+            graphs[i % n_sets].replay()
+        torch.cuda.synchronize()
+        rec["ms_per_iteration_graph_replay"] = (time.perf_counter() - t0) * 1e3 / iters
+        rec["graph_replay_same_lengths"] = bool((lengths.cpu().numpy() == L).all())
     ver.destroy()
     return rec
 
@@ -174,6 +194,7 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=3, help="resident input batches the loop cycles through")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--prenorm", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="also time the loop as replayed HIP graphs")
     ap.add_argument("--sweep", default="", help="comma-separated batch sizes; runs the sweep instead of the loop")
     ap.add_argument("--steps", type=int, default=50)
     args = ap.parse_args()
@@ -182,7 +203,7 @@ def main() -> int:
         for rec in sweep([int(b) for b in args.sweep.split(",")], args.steps, args.seed):
             print(json.dumps(rec))
     else:
-        print(json.dumps(loop_benchmark(args.config, args.iters, args.sets, args.seed, args.prenorm)))
+        print(json.dumps(loop_benchmark(args.config, args.iters, args.sets, args.seed, args.prenorm, args.graph)))
     return 0
 
 

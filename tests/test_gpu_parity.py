@@ -404,6 +404,58 @@ def test_side_stream_and_two_contexts(jd):
         va.destroy(); vb.destroy()
 
 
+@pytest.mark.parametrize("shape", [VerifyShape("g_skinny", 2, 9, 264, 3000, "bf16", 1.0),
+                                   VerifyShape("g_gemm", 20, 10, 256, 2100, "bf16", 1.5)], ids=lambda s: s.name)
+def test_graph_capture_and_replay(jd, shape):
+    # a serving loop may capture verify + append into a HIP graph: run() allocates nothing, never synchronises and
+    # sets no function attributes, so it can be captured; every replay (with eager work and synchronisations between
+    # them, and fresh inputs copied into the captured buffers) must equal the eager result and the oracle
+    import torch
+    from paper_2501_19309_amd import binding as jb, harness
+    xs = [make_inputs(shape, 40 + k, prenorm=True, weights_seed=40) for k in range(2)]
+    dev = harness.to_device(xs[0])
+    ver = harness.make_verifier(dev)
+    try:
+        B, M = shape.B, shape.M
+        out = ver.alloc_outputs(B, M)
+        cap = 4 * (M + 1)
+        buf = torch.zeros(B, cap, dtype=torch.int32, device="cuda"); lengths = torch.zeros(B, dtype=torch.int32, device="cuda")
+        eps = float(xs[0]["rms_eps"])
+
+        def call():
+            ver.run_prenorm(dev["hidden"], dev["gamma"], eps, dev["draft_tokens"], dev["draft_logits"], dev["uniforms"], out)
+            jb.append_tokens(dev["draft_tokens"], out.accept_len, out.next_token, buf, lengths)
+
+        call()                       # eager once (also warms everything up)
+        torch.cuda.synchronize()
+        eager0 = out.to_numpy()
+        buf.zero_(); lengths.zero_()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            call()
+        rbuf = np.zeros((B, cap), dtype=np.int32); rlen = np.zeros(B, dtype=np.int64)
+        buf.zero_(); lengths.zero_()
+        for it, k in enumerate((0, 1, 0)):
+            x = xs[k]
+            fresh = harness.to_device({n: x[n] for n in ("hidden", "draft_tokens", "draft_logits", "uniforms")})
+            for n, t in fresh.items():
+                dev[n].copy_(t)      # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = out.to_numpy()
+            ref = prenorm_oracle(x)
+            compare(got, ref)
+            if k == 0:
+                for name, v in got.items():
+                    assert np.array_equal(v, eager0[name], equal_nan=True), (it, name)
+            vo.append_tokens(rbuf, rlen, x["draft_tokens"], got["accept_len"], got["next_token"])
+            assert np.array_equal(lengths.cpu().numpy(), rlen) and np.array_equal(buf.cpu().numpy(), rbuf), it
+    finally:
+        ver.destroy()
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
