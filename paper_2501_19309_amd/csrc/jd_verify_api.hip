@@ -30,6 +30,7 @@ struct jd_verify_ctx {
   int* rankpart;        // [max_B*max_M][kRankSplits], top-K rule only
   void* Xp;             // packed embeddings for the GEMM regime
   void* Xn;             // [max_R][d] normalised embeddings of the pre-norm entry point
+  void* pool;           // one allocation behind tpart .. rankpart (see create)
   int nPartT, nPartD, nChunk;
   uint64_t bytes;
   float judge_threshold;
@@ -96,7 +97,7 @@ extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
 
 static void free_ctx(jd_verify_ctx* c) {
   if (!c) return;
-  void* ptrs[] = {c->Wp, c->Wp8, c->L, c->tpart, c->dpart, c->t_max, c->t_sum, c->q_max, c->q_sum, c->g, c->chunk_mass, c->Xp, c->Xn, c->rankpart};
+  void* ptrs[] = {c->Wp, c->Wp8, c->L, c->pool, c->Xp, c->Xn};  // tpart .. rankpart live inside pool
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -158,15 +159,33 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
   c->nChunk = (cfg->V + kSamplerChunk - 1) / kSamplerChunk;
 
   rc = dev_alloc(c, &c->L, maxR * (size_t)c->geo.Vpad);
-  if (rc == JD_OK) rc = dev_alloc(c, &c->tpart, maxR * (size_t)c->nPartT);
-  if (rc == JD_OK) rc = dev_alloc(c, &c->dpart, maxS * (size_t)c->nPartD);
-  if (rc == JD_OK) rc = dev_alloc(c, &c->t_max, maxR);
-  if (rc == JD_OK) rc = dev_alloc(c, &c->t_sum, maxR);
-  if (rc == JD_OK) rc = dev_alloc(c, &c->q_max, maxS);
-  if (rc == JD_OK) rc = dev_alloc(c, &c->q_sum, maxS);
-  if (rc == JD_OK) rc = dev_alloc(c, &c->g, maxS);
-  if (rc == JD_OK) rc = dev_alloc(c, &c->chunk_mass, (size_t)cfg->max_B * c->nChunk);
-  if (rc == JD_OK && cfg->rule == JD_RULE_TOPK) rc = dev_alloc(c, &c->rankpart, maxS * (size_t)kRankSplits);
+  if (rc == JD_OK) {
+    // The small per-row arrays live side by side in ONE allocation: the kernels after the LM head are a
+    // few microseconds each and walk chains of dependent loads, so every separate allocation they touch
+    // is one more cold address translation on that chain.
+    const bool topk = cfg->rule == JD_RULE_TOPK;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+    const size_t o_tpart = take(maxR * (size_t)c->nPartT * sizeof(float2));
+    const size_t o_dpart = take(maxS * (size_t)c->nPartD * sizeof(float2));
+    const size_t o_tmax = take(maxR * sizeof(float)), o_tsum = take(maxR * sizeof(float));
+    const size_t o_qmax = take(maxS * sizeof(float)), o_qsum = take(maxS * sizeof(float));
+    const size_t o_g = take(maxS * sizeof(float));
+    const size_t o_cm = take((size_t)cfg->max_B * c->nChunk * sizeof(double));
+    const size_t o_rank = take(topk ? maxS * (size_t)kRankSplits * sizeof(int) : 0);
+    uint8_t* pool = nullptr;
+    rc = dev_alloc(c, &pool, off);
+    c->pool = pool;
+    if (rc == JD_OK) {
+      c->tpart = reinterpret_cast<float2*>(pool + o_tpart);
+      c->dpart = reinterpret_cast<float2*>(pool + o_dpart);
+      c->t_max = reinterpret_cast<float*>(pool + o_tmax); c->t_sum = reinterpret_cast<float*>(pool + o_tsum);
+      c->q_max = reinterpret_cast<float*>(pool + o_qmax); c->q_sum = reinterpret_cast<float*>(pool + o_qsum);
+      c->g = reinterpret_cast<float*>(pool + o_g);
+      c->chunk_mass = reinterpret_cast<double*>(pool + o_cm);
+      c->rankpart = topk ? reinterpret_cast<int*>(pool + o_rank) : nullptr;
+    }
+  }
   if (rc == JD_OK && fp8) {
     uint8_t* wp8 = nullptr;
     rc = dev_alloc(c, &wp8, c->geo.packed8_bytes());

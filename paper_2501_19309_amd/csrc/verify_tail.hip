@@ -236,13 +236,34 @@ __device__ __forceinline__ double total_chunk_mass(const double* cm, int nChunk,
   return block_sum256(v, red);
 }
 
+// Block-wide (256 threads) minimum of `lo` and maximum of `hi`: wavefront reductions, then the four
+// wavefront results through LDS.  (LDS atomics on one address from every thread serialise: with them
+// this step alone took 5 us of the kernel's 12.)
+__device__ __forceinline__ void block_min_max256(int lo, int hi, int* s_lo /*[4]*/, int* s_hi /*[4]*/, int* out_lo,
+                                                 int* out_hi) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    lo = min(lo, __shfl_xor(lo, o));
+    hi = max(hi, __shfl_xor(hi, o));
+  }
+  if ((threadIdx.x & 63) == 0) { s_lo[threadIdx.x >> 6] = lo; s_hi[threadIdx.x >> 6] = hi; }
+  __syncthreads();
+  *out_lo = min(min(s_lo[0], s_lo[1]), min(s_lo[2], s_lo[3]));
+  *out_hi = max(max(s_hi[0], s_hi[1]), max(s_hi[2], s_hi[3]));
+  __syncthreads();
+}
+
 // Inverse CDF in ascending token id: next = min{ v : cdf[v] > u_s * S }.
 __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
   __shared__ double red[256];
   __shared__ double s_base, s_carry;
-  __shared__ int s_chunk, s_lastchunk;
   const int b = blockIdx.x, tid = threadIdx.x;
   double* cm = a.chunk_mass + (size_t)b * a.nChunk;
+
+  // Requested before the first barrier, so that these two levels of dependent loads (accepted prefix,
+  // then the statistics of its row) travel while the chunk masses are summed.
+  MassRow row = make_mass_row(a, b, false);
+  const float u_s = a.uniforms[b * (a.M + 1) + a.M];
 
   double S = total_chunk_mass(cm, a.nChunk, red);
   const bool plain = !(S > 0.0);
@@ -258,42 +279,43 @@ __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
     S = total_chunk_mass(cm, a.nChunk, red);
     if (tid == 0 && !(S == S)) atomicOr(&a.status[b], 2u);
   }
-  const MassRow row = make_mass_row(a, b, plain);
-  const double thresh = (double)a.uniforms[b * (a.M + 1) + a.M] * S;
+  if (plain) row.use_q = 0;
+  const double thresh = (double)u_s * S;
 
   // first chunk whose inclusive prefix exceeds the threshold
-  if (tid == 0) { s_chunk = 0x7fffffff; s_lastchunk = -1; s_carry = 0.0; s_base = 0.0; }
-  __syncthreads();
+  __shared__ int s_lo[4], s_hi[4];
+  int found = 0x7fffffff, lastchunk = -1;
+  double carry = 0.0;
   for (int base = 0; base < a.nChunk; base += 256) {
     const int i = base + tid;
     const double val = (i < a.nChunk) ? cm[i] : 0.0;
-    const double incl = s_carry + block_inclusive_scan256(val, red);
-    if (i < a.nChunk && val > 0.0) {
-      if (incl > thresh) atomicMin(&s_chunk, i);
-      atomicMax(&s_lastchunk, i);
-    }
-    __syncthreads();
-    if (s_chunk != 0x7fffffff) {
-      if (i == s_chunk) s_base = incl - val;
-      __syncthreads();
+    const double incl = carry + block_inclusive_scan256(val, red);
+    const bool has = i < a.nChunk && val > 0.0;
+    int lo, hi;
+    block_min_max256((has && incl > thresh) ? i : 0x7fffffff, has ? i : -1, s_lo, s_hi, &lo, &hi);
+    lastchunk = max(lastchunk, hi);
+    if (lo != 0x7fffffff) {
+      found = lo;
+      if (i == lo) s_base = incl - val;
       break;
     }
     if (tid == 255) s_carry = incl;
     __syncthreads();
+    carry = s_carry;
   }
-  if (s_chunk == 0x7fffffff) {  // rounding left the threshold beyond the last edge (or S is NaN)
+  if (found == 0x7fffffff) {  // rounding left the threshold beyond the last edge (or S is NaN)
+    found = lastchunk < 0 ? 0 : lastchunk;
     if (tid == 0) {
-      const int last = s_lastchunk < 0 ? 0 : s_lastchunk;
       double run = 0.0;
-      for (int i = 0; i < last; ++i) run += cm[i];
-      s_chunk = last; s_base = run;
+      for (int i = 0; i < found; ++i) run += cm[i];
+      s_base = run;
     }
-    __syncthreads();
   }
+  __syncthreads();
   const double s_thresh = thresh;
 
   // Scan inside the chosen chunk: thread t owns tokens 4t..4t+3 of the chunk.
-  const int chunk = s_chunk;
+  const int chunk = found;
   const int v0 = chunk * kSamplerChunk + tid * 4;
   double mv[4];
   double local = 0.0;
@@ -324,12 +346,8 @@ __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     if (mv[i] > 0.0) lastpos = v0 + i;
-  __shared__ int s_min, s_last;
-  if (tid == 0) { s_min = 0x7fffffff; s_last = -1; }
-  __syncthreads();
-  if (cand != 0x7fffffff) atomicMin(&s_min, cand);
-  if (lastpos >= 0) atomicMax(&s_last, lastpos);
-  __syncthreads();
+  int s_min, s_last;
+  block_min_max256(cand, lastpos, s_lo, s_hi, &s_min, &s_last);
   if (tid == 0) {
     int tok = (s_min != 0x7fffffff) ? s_min : s_last;
     if (tok < 0) tok = 0;
