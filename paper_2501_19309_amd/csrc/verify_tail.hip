@@ -40,6 +40,36 @@ hipError_t launch_rowstats(const float* base, int nRows, int rowsUsed, size_t se
 //   blocks [R+S, R+2S)   judge logit g = w_judge . e[b, j+1] + bias    (Sec. 4.1; App. B.1),
 //                        unless they were already computed beside the LM head
 // with R = B*(M+1), S = B*M.
+// One thread's share (every 256th) of n (max, sum exp) partials.  The partials were written by another
+// kernel and come from HBM, so eight loads are put in flight before anything is combined, and a batch
+// is combined around its common maximum (independent exps, no serial chain).
+__device__ __forceinline__ MS combine_partials(const float2* __restrict__ p, int n, int tid) {
+  constexpr int kBatch = 8;
+  MS st{-INFINITY, 0.f};
+  for (int base = 0; base < n; base += 256 * kBatch) {
+    float2 v[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = base + u * 256 + tid;
+      v[u] = (i < n) ? p[i] : make_float2(-INFINITY, 0.f);
+    }
+    float mx = st.m;
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) mx = fmaxf(mx, v[u].x);
+    if (mx == -INFINITY) {  // nothing but empty partials so far (keeps NaN sums visible)
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) st.s += v[u].y;
+    } else {
+      float sum = st.s * __expf(st.m - mx);
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) sum += v[u].y * __expf(v[u].x - mx);
+      st.s = sum;
+    }
+    st.m = mx;
+  }
+  return st;
+}
+
 __global__ __launch_bounds__(256) void reduce_rows_kernel(AcceptArgs a) {
   __shared__ MS red[4];
   __shared__ float redf[4];
@@ -47,9 +77,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(AcceptArgs a) {
   const int R = a.B * (a.M + 1), S = a.B * a.M;
   int blk = blockIdx.x;
   if (blk < R) {
-    const float2* p = a.tpart + (size_t)blk * a.nPartT;
-    MS st{-INFINITY, 0.f};
-    for (int i = tid; i < a.nPartT; i += 256) st = ms_combine(st, MS{p[i].x, p[i].y});
+    MS st = combine_partials(a.tpart + (size_t)blk * a.nPartT, a.nPartT, tid);
     st = ms_block_reduce(st, red);
     if (tid == 0) {
       a.t_max[blk] = st.m; a.t_sum[blk] = st.s;
@@ -61,9 +89,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(AcceptArgs a) {
   blk -= R;
   if (blk < S) {
     if (!a.draft_is_logits) return;
-    const float2* p = a.dpart + (size_t)blk * a.nPartD;
-    MS st{-INFINITY, 0.f};
-    for (int i = tid; i < a.nPartD; i += 256) st = ms_combine(st, MS{p[i].x, p[i].y});
+    MS st = combine_partials(a.dpart + (size_t)blk * a.nPartD, a.nPartD, tid);
     st = ms_block_reduce(st, red);
     if (tid == 0) { a.q_max[blk] = st.m; a.q_sum[blk] = st.s; }
     return;
