@@ -21,8 +21,8 @@
 //     stage is requested three K steps (~2 us) before it is read.
 //   * per K step a wavefront issues 88 MFMAs, 19 conflict-free ds_read_b128 (11 embedding
 //     fragments, refilled in place right after their row block, 8 weight fragments into the
-//     other half of a double buffer), 9-10 direct-to-LDS loads and one barrier, dealt out
-//     singly between the row blocks.
+//     other half of a double buffer), 9-10 direct-to-LDS loads and one barrier, each placed
+//     alone behind an MFMA of its own.
 //   * direct-to-LDS loads are written as inline assembly: the compiler then neither knows
 //     nor waits for them, and the kernel counts them itself (they complete in issue order):
 //     before the barrier of step k a wavefront waits until only its loads for steps k+2 and
@@ -35,7 +35,6 @@
 
 namespace jd {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
