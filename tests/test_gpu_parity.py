@@ -53,6 +53,9 @@ EDGE = [
     VerifyShape("e_R352", 32, 10, 520, 4100, "bf16", (0.5, 2.0)),  # exactly one 352-row tile, 24 K steps, ragged V
     VerifyShape("e_R400", 40, 9, 264, 1000, "bf16", 1.0),        # three 176-row tiles (176-row tiling)
     VerifyShape("e_R1000", 100, 9, 128, 700, "bf16", 1.0),       # three 352-row tiles, the last one ragged
+    VerifyShape("e_R704_M63", 11, 63, 72, 130, "bf16", 1.0),     # two full 352-row tiles, widest ballot, 3 vocabulary groups
+    VerifyShape("e_R352_d8", 44, 7, 8, 300, "bf16", 1.0),        # 352-row tiling at the smallest hidden size (one real K step)
+    VerifyShape("e_R300_V9", 30, 9, 40, 9, "bf16", 1.0),         # 352-row tiling with one partial vocabulary group
     VerifyShape("e_V1", 2, 2, 8, 1, "f32", 1.0),                 # single token vocabulary: everything is certain
 ]
 
