@@ -738,3 +738,65 @@ def test_masked_draft_tokens_and_rows():
     with np.errstate(invalid="ignore"):
         out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], D, x["uniforms"], mode=vo.MODE_STANDARD)
     assert out["status"].tolist() == [0, vo.STATUS_NAN]
+
+
+# ----------------------------------------------------------------------------- metamorphic relations
+
+def _verify(x, **kw):
+    return vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"], **kw)
+
+
+def test_sequences_are_independent_and_order_free():
+    # no step of the method crosses sequences (Sec. 3.1: each context is verified on its own)
+    x = make_inputs(VerifyShape("t", 7, 5, 32, 96, "f32", 1.2), 8)
+    out = _verify(x)
+    perm = np.array([3, 0, 6, 1, 5, 2, 4])
+    y = dict(x)
+    for k in ("emb", "draft_tokens", "draft_logits", "uniforms"):
+        y[k] = x[k][perm]
+    outp = _verify(y)
+    for k, v in out.items():
+        assert np.array_equal(outp[k], v[perm], equal_nan=True), k
+
+
+def test_vocabulary_relabelling():
+    # renaming the tokens (rows of W_lm, columns of the draft, drafted ids) changes no decision;
+    # the new token is the renamed old one whenever the CDF order plays no role (everything accepted
+    # is not such a case, so only the masks and the prefix are compared)
+    x = make_inputs(VerifyShape("t", 9, 6, 32, 80, "f32", 1.0), 12)
+    out = _verify(x)
+    pi = np.random.default_rng(0).permutation(80)          # new id of old token v is inv[v]
+    inv = np.empty(80, dtype=np.int64); inv[pi] = np.arange(80)
+    y = dict(x)
+    y["W"] = x["W"][pi]                                    # row new_id holds old token pi[new_id]
+    y["draft_logits"] = x["draft_logits"][:, :, pi]
+    y["draft_tokens"] = inv[x["draft_tokens"]].astype(np.int32)
+    outp = _verify(y)
+    away = (out["accept_margin"] > 1e-9) & (out["judge_margin"] > 1e-9)
+    assert away.all()
+    for k in ("z_stand", "z_judge", "accept_len"):
+        assert np.array_equal(out[k], outp[k]), k
+    assert np.allclose(out["p_at_draft"], outp["p_at_draft"], rtol=1e-12) and np.allclose(out["q_at_draft"], outp["q_at_draft"], rtol=1e-12)
+
+
+def test_draft_logit_shift_and_truncated_drafts():
+    x = make_inputs(VerifyShape("t", 8, 6, 32, 96, "f32", 1.5), 14)
+    out = _verify(x)
+    # softmax is shift invariant: a constant added to a draft row changes nothing away from ties
+    y = dict(x); y["draft_logits"] = (x["draft_logits"].astype(np.float64) + 3.25).astype(np.float32)
+    outs = _verify(y)
+    assert (out["accept_margin"] > 1e-6).all() and (out["sampler_margin"] > 1e-6).all()
+    for k in ("z_stand", "z_judge", "accept_len", "next_token"):
+        assert np.array_equal(out[k], outs[k]), k
+    # verifying only the first M' drafted tokens: same masks on those slots, prefix cut at M', and the same
+    # new token whenever the cut fell before M' (same row, same residual, same sampler draw)
+    Mp = 3
+    z = dict(x)
+    z["emb"] = x["emb"][:, :Mp + 1]; z["draft_tokens"] = x["draft_tokens"][:, :Mp]
+    z["draft_logits"] = x["draft_logits"][:, :Mp + 1]
+    z["uniforms"] = np.concatenate([x["uniforms"][:, :Mp], x["uniforms"][:, 6:7]], axis=1)
+    outt = _verify(z)
+    assert np.array_equal(outt["z_stand"], out["z_stand"][:, :Mp]) and np.array_equal(outt["z_judge"], out["z_judge"][:, :Mp])
+    assert np.array_equal(outt["accept_len"], np.minimum(out["accept_len"], Mp))
+    early = out["accept_len"] < Mp
+    assert early.any() and np.array_equal(outt["next_token"][early], out["next_token"][early])
