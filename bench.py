@@ -43,7 +43,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "C2q", "C3q", "C4q"],
+    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "C2q", "C3q", "C4q", "C5q"],
                     help="C2..C5: bf16 W_lm (C4 is the headline); C2q..C4q: the same shapes with FP8 E4M3 W_lm")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -136,7 +136,7 @@ def main() -> int:
     x_bytes = R * d * elem
     lm_ms = kernel_ms["lmhead"]
     flops = 2.0 * R * d * V
-    if args.config == "C5":  # MFMA-bound regime
+    if args.config in ("C5", "C5q"):  # MFMA-bound regime
         achieved = flops / (lm_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)}

@@ -137,8 +137,11 @@ hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X
                               float invT, float* L, float2* part, void* Xp, int num_cus, hipStream_t st);
 // The same projection on 352-row x 256-entry tiles with both operands shared through LDS; the better
 // choice when gemm_prefers_352(R), i.e. when 352-row tiles add no padding rows over 176-row tiles.
-hipError_t launch_lmhead_gemm_dma(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
-                                  float invT, float* L, float2* part, void* Xp, hipStream_t st);
+// w_fp8: W is Wg8, the FP8 copy that launch_pack_w8g builds (Geometry::packed8_bytes() bytes), and vscale
+// holds the per-entry scales; otherwise W is the bf16 Wp.
+hipError_t launch_lmhead_gemm_dma(const void* W, int w_fp8, const float* vscale, const void* X, int R,
+                                  const Geometry& g, float invT, float* L, float2* part, void* Xp, hipStream_t st);
+hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* Wg8, hipStream_t st);
 // Once per process before the first launch of either kernel (they use more dynamic LDS than the default limit).
 hipError_t init_lmhead_gemm();
 hipError_t init_lmhead_gemm_dma();

@@ -20,7 +20,8 @@ struct jd_verify_ctx {
   const void* W;
   const void* wj;
   void* Wp;             // re-tiled bf16 weights (bf16 path; FP8 path only for the large-row regime)
-  void* Wp8;            // re-tiled FP8 weights (FP8 path)
+  void* Wp8;            // re-tiled FP8 weights (FP8 path, small-row kernel)
+  void* Wg8;            // re-tiled FP8 weights for the 352-row kernel (FP8 path, max_R > 64)
   const float* wscale;  // per-vocabulary-entry weight scale (FP8 path, may be NULL)
   float* L;             // [maxR][Vpad] fp32 logits
   float2* tpart;        // [maxR][nPartT]
@@ -97,7 +98,7 @@ extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
 
 static void free_ctx(jd_verify_ctx* c) {
   if (!c) return;
-  void* ptrs[] = {c->Wp, c->Wp8, c->L, c->pool, c->Xp, c->Xn};  // tpart .. rankpart live inside pool
+  void* ptrs[] = {c->Wp, c->Wp8, c->Wg8, c->L, c->pool, c->Xp, c->Xn};  // tpart .. rankpart live inside pool
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -198,6 +199,13 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
     rc = dev_alloc(c, &wp, c->geo.packed_bytes());
     c->Wp = wp;
     JD_HIP_RC(launch_pack_w(d_W_lm, cfg->w_layout, fp8 ? 1 : 0, c->geo, c->Wp, nullptr));
+    JD_HIP_RC(hipDeviceSynchronize());
+  }
+  if (rc == JD_OK && fp8 && maxR > 64) {  // FP8 fragments for the 352-row kernel
+    uint8_t* wg8 = nullptr;
+    rc = dev_alloc(c, &wg8, c->geo.packed8_bytes());
+    c->Wg8 = wg8;
+    JD_HIP_RC(launch_pack_w8g(d_W_lm, cfg->w_layout, c->geo, c->Wg8, nullptr));
     JD_HIP_RC(hipDeviceSynchronize());
   }
   if (rc == JD_OK && bf16 && maxR > 64) {
@@ -317,7 +325,8 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
       JD_HIP(launch_lmhead_skinny(fp8 ? c->Wp8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart,
                                   side, st));
     } else if (gemm_prefers_352(R)) {
-      JD_HIP(launch_lmhead_gemm_dma(c->Wp, fp8 ? c->wscale : nullptr, d_emb, R, g, invT, c->L, c->tpart, c->Xp, st));
+      JD_HIP(launch_lmhead_gemm_dma(fp8 ? c->Wg8 : c->Wp, fp8 ? 1 : 0, fp8 ? c->wscale : nullptr, d_emb, R, g, invT,
+                                    c->L, c->tpart, c->Xp, st));
     } else {
       JD_HIP(launch_lmhead_gemm(c->Wp, fp8 ? c->wscale : nullptr, d_emb, R, g, invT, c->L, c->tpart, c->Xp,
                                 c->num_cus, st));

@@ -42,9 +42,10 @@ constexpr int kXcds = 8;
 constexpr int kDmaWaveRowBlocks = kDmaRowBlocks / 2;                    // 11 row blocks per wavefront
 constexpr int kDmaStages = 4;
 constexpr int kDmaXItems = kDmaRowBlocks * 64;                          // 16-byte items: 22 KiB of embeddings
-constexpr int kDmaWItems = 16 * 64;                                     // 16 KiB of weights (4 groups x 4 sub-blocks)
-constexpr int kDmaStageItems = kDmaXItems + kDmaWItems;                 // 38 KiB per K step
-constexpr size_t kDmaLdsBytes = (size_t)kDmaStages * kDmaStageItems * sizeof(uint4);  // 152 KiB
+// weights of one K step: 4 groups x 4 sub-blocks, 16 KiB as bf16 fragments, 8 KiB as FP8 fragments
+template <bool W8> constexpr int kDmaWItems = W8 ? 8 * 64 : 16 * 64;
+template <bool W8> constexpr int kDmaStageItems = kDmaXItems + kDmaWItems<W8>;      // 38 KiB (30 KiB) per K step
+template <bool W8> constexpr size_t kDmaLdsBytes = (size_t)kDmaStages * kDmaStageItems<W8> * sizeof(uint4);  // 152 (120) KiB
 // Tile (row block x, weight sub-block sb) lives in accumulation registers for the first 60 tiles (240 of the
 // 256 registers) and in ordinary vector registers for the other 28.  Filling all 256 leaves the register
 // allocator no room: it then parks values in scratch memory around the epilogue, reading tiles before the wait
@@ -90,11 +91,38 @@ __device__ __forceinline__ void dma_issue(const uint4* gbase, unsigned lane_off)
   asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase) : "memory");
 }
 
+// Dword j (0..3) of the bf16 fragment of eight FP8 E4M3 codes c (two dwords, ascending hidden index):
+// gfx950 converts two codes to two packed bf16 values in one instruction (the scale operand is 1; every
+// E4M3 value is a bf16 value, so the result is exact - checked on the device for all code pairs against
+// the float conversion).  Inline assembly because the instruction has to stay behind the MFMA it is
+// written behind: between two MFMAs of a lone wavefront exactly one vector, LDS or memory instruction
+// issues for free, every further one delays the next MFMA by about 7 cycles (measured); scalar
+// instructions ride along.  Left to the compiler, all conversions of a K step end up in one block.
+__device__ __forceinline__ uint32_t fp8_pair_to_bf16x2(const uint2& c, int j) {
+  const uint32_t src = j < 2 ? c.x : c.y;
+  uint32_t o;
+  if (j & 1)
+    asm volatile("v_cvt_scalef32_pk_bf16_fp8 %0, %1, 1.0 op_sel:[1,0,0]" : "=v"(o) : "v"(src));
+  else
+    asm volatile("v_cvt_scalef32_pk_bf16_fp8 %0, %1, 1.0" : "=v"(o) : "v"(src));
+  return o;
+}
+__device__ __forceinline__ void set_dword(uint4& v, int j, uint32_t x) {
+  if (j == 0) v.x = x; else if (j == 1) v.y = x; else if (j == 2) v.z = x; else v.w = x;
+}
+
+// W8 = false: Wsrc is the re-tiled bf16 copy Wp.  W8 = true: Wsrc is the FP8 copy Wg8 (see pack_w8g_kernel):
+// half the weight bytes through L2, L1 and LDS; fragments are converted to bf16 in registers, one
+// instruction behind each MFMA, one K step ahead; the per-entry scale is applied in the epilogue.
+template <bool W8>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
-    const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
+    const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
     int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld,
     float2* __restrict__ part) {
-  extern __shared__ uint4 lds[];  // kDmaStages stages of [22 x 64 embedding items][16 x 64 weight items]
+  constexpr int kStageItems = kDmaStageItems<W8>;
+  constexpr int kNW = W8 ? 2 : 4;       // direct-to-LDS loads of weights per wavefront and K step
+  constexpr int kPieces = kNW + 6;      // + up to six embedding row blocks
+  extern __shared__ uint4 lds[];  // kDmaStages stages of [22 x 64 embedding items][weight items]
 
   // XCD-aware tile id: the row tiles that stream the same 256 vocabulary rows get ids that the
   // hardware deals to one XCD, so W_lm crosses from HBM into one L2 only.
@@ -114,33 +142,29 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   const unsigned lane16 = (unsigned)lane * 16u;
   const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)lds;
 
-  // direct-to-LDS sources of this wavefront: the 4 KiB of vocabulary group vt*4 + wave (< nVGalloc,
-  // allocated in multiples of 8 groups), and embedding row blocks wave, wave+4, .. (< 22)
-  const uint4* wsrc0 = Wp + wp_group_offset(vt * 4 + wave);
+  // direct-to-LDS sources of this wavefront: the weights of vocabulary group vt*4 + wave (< nVGalloc,
+  // allocated in multiples of 8 groups; 4 KiB per K step as bf16, 2 KiB as FP8), and embedding row
+  // blocks wave, wave+4, .. (< 22)
+  const uint4* wsrc0 = W8 ? Wsrc + (size_t)(vt * 4 + wave) * 128 : Wsrc + wp_group_offset(vt * 4 + wave);
+  const size_t wStep8 = (size_t)nVGalloc * 128;  // FP8: 16-byte items between consecutive K steps
   const uint4* xsrc0 = Xp + ((size_t)rt * KS * kDmaRowBlocks + wave) * 64;
   const bool six = wave < 2;  // wavefronts 0, 1 own six embedding row blocks, 2, 3 own five
+  const unsigned ldsW0 = lds0 + (unsigned)(kDmaXItems + wave * kNW * 64) * 16;
+  const unsigned ldsX0 = lds0 + (unsigned)(wave * 64) * 16;
 
-  // piece p (0..9) of the K step `ks` into stage `stage`; pieces 0..3 weights, 4..9 embeddings
-  auto dma_piece = [&](int ks, int stage, int p) {
-    const unsigned dst = lds0 + (unsigned)stage * (kDmaStageItems * 16);
-    if (p < 4) {
-      dma_1k(wsrc0 + wp_step_offset(ks, nVGalloc) + p * 64, dst + (kDmaXItems + (wave * 4 + p) * 64) * 16, lane16);
-    } else {
-      const int q = p - 4;  // row block wave + 4q
-      if (q < 5 || six)
-        dma_1k(xsrc0 + ((size_t)ks * kDmaRowBlocks + 4 * q) * 64, dst + (unsigned)((wave + 4 * q) * 64) * 16, lane16);
-    }
-  };
   // Wait until at most `groups` K steps of this wavefront's direct-to-LDS loads are outstanding and all
-  // its LDS reads have returned.  Wavefronts 0, 1 issue 10 loads per step and 2, 3 issue 9; loads
-  // complete in issue order, so the count for 9 is right for both (0, 1 then also wait for the first
-  // one or two loads of the following, much older, step).
+  // its LDS reads have returned.  Wavefronts 0, 1 issue kPieces loads per step and 2, 3 one fewer; loads
+  // complete in issue order, so the count for the smaller number is right for both (0, 1 then also wait
+  // for the first one or two loads of the following, much older, step).
   auto wait_groups = [&](auto gc) {
     constexpr int g = decltype(gc)::value;
-    if constexpr (g == 3) asm volatile("s_waitcnt vmcnt(27) lgkmcnt(0)" ::: "memory");
-    if constexpr (g == 2) asm volatile("s_waitcnt vmcnt(18) lgkmcnt(0)" ::: "memory");
+    if constexpr (g == 3 && !W8) asm volatile("s_waitcnt vmcnt(27) lgkmcnt(0)" ::: "memory");
+    if constexpr (g == 2 && !W8) asm volatile("s_waitcnt vmcnt(18) lgkmcnt(0)" ::: "memory");
+    if constexpr (g == 3 && W8) asm volatile("s_waitcnt vmcnt(21) lgkmcnt(0)" ::: "memory");
+    if constexpr (g == 2 && W8) asm volatile("s_waitcnt vmcnt(14) lgkmcnt(0)" ::: "memory");
     if constexpr (g == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   };
+  static_assert(3 * (kPieces - 1) == (W8 ? 21 : 27) && 2 * (kPieces - 1) == (W8 ? 14 : 18), "wait counts above");
 
   f32x4 acc[8][kDmaWaveRowBlocks];
 #pragma unroll
@@ -149,43 +173,60 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     for (int x = 0; x < kDmaWaveRowBlocks; ++x) acc[s][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   uint4 xf[kDmaWaveRowBlocks];  // embedding fragments of the current K step, refilled in place
-  uint4 wf[2][8];               // weight fragments: current step / next step
+  uint4 wf[2][8];               // weight fragments (bf16): current step / next step
+  uint2 raw[8];                 // FP8 only: codes of the next step's fragments on their way into wf
 
   // prologue: request K steps 0..3 (KS >= 8), wait for step 0, read its operands
 #pragma unroll
-  for (int s = 0; s < kDmaStages; ++s)
+  for (int s = 0; s < kDmaStages; ++s) {
+    const unsigned dst = (unsigned)s * (kStageItems * 16);
+    const uint4* wg = W8 ? wsrc0 + (size_t)s * wStep8 : wsrc0 + wp_step_offset(s, nVGalloc);
+    const uint4* xg = xsrc0 + (size_t)s * (kDmaRowBlocks * 64);
 #pragma unroll
-    for (int p = 0; p < 10; ++p) dma_piece(s, s, p);
+    for (int p = 0; p < kNW; ++p) dma_1k(wg + p * 64, ldsW0 + dst + p * 1024, lane16);
+#pragma unroll
+    for (int q = 0; q < 6; ++q)
+      if (q < 5 || six) dma_1k(xg + q * 256, ldsX0 + dst + q * 4096, lane16);
+  }
   wait_groups(std::integral_constant<int, 3>{});
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   {
     const uint4* xr = lds + rh * kDmaWaveRowBlocks * 64 + lane;
-    const uint4* wr = lds + kDmaXItems + vh * 8 * 64 + lane;
 #pragma unroll
     for (int x = 0; x < kDmaWaveRowBlocks; ++x) xf[x] = xr[x * 64];
+    if constexpr (W8) {
+      const uint2* wr = reinterpret_cast<const uint2*>(lds + kDmaXItems) + vh * 8 * 64 + lane;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) wf[0][s] = wr[s * 64];
+      for (int s = 0; s < 8; ++s) {
+        const uint2 c = wr[s * 64];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) set_dword(wf[0][s], jj, fp8_pair_to_bf16x2(c, jj));
+      }
+    } else {
+      const uint4* wr = lds + kDmaXItems + vh * 8 * 64 + lane;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) wf[0][s] = wr[s * 64];
+    }
   }
 
   // K step k = 4*kk + ST; the stage index ST is a compile-time constant.  The wavefront's instruction
   // stream is written out MFMA by MFMA: with one wavefront per SIMD nothing else can fill the matrix
   // pipeline while this wavefront issues other instructions, and an MFMA leaves room for about three
-  // of them, so every LDS read, M0 write and direct-to-LDS load sits alone behind its own MFMA.
-  const size_t wGroupStride = (size_t)nVGalloc * (kWpKG * 256);
-  const unsigned ldsW0 = lds0 + (unsigned)(kDmaXItems + wave * 4 * 64) * 16;
-  const unsigned ldsX0 = lds0 + (unsigned)(wave * 64) * 16;
+  // of them, so every LDS read, M0 write, direct-to-LDS load and pair of conversion instructions sits
+  // alone behind its own MFMA.
   auto k_step = [&](const uint4* wIter, const uint4* xIter, auto stc) {
     constexpr int ST = decltype(stc)::value;
     constexpr int cur = ST & 1, nxt = cur ^ 1;
     constexpr int RS = (ST + 1) % kDmaStages;  // stage of step k+1: read after the barrier
-    constexpr unsigned stageByte = (unsigned)ST * (kDmaStageItems * 16);
-    const uint4* xr = lds + RS * kDmaStageItems + rh * kDmaWaveRowBlocks * 64 + lane;
-    const uint4* wr = lds + RS * kDmaStageItems + kDmaXItems + vh * 8 * 64 + lane;
+    constexpr unsigned stageByte = (unsigned)ST * (kStageItems * 16);
+    const uint4* xr = lds + RS * kStageItems + rh * kDmaWaveRowBlocks * 64 + lane;
+    const uint4* wr = lds + RS * kStageItems + kDmaXItems + vh * 8 * 64 + lane;                              // bf16
+    const uint2* wr8 = reinterpret_cast<const uint2*>(lds + RS * kStageItems + kDmaXItems) + vh * 8 * 64 + lane;  // FP8
     // requested now: step k+4 into the stage this step frees (wIter, xIter: its group of four steps).
     // In the last group step k itself is requested again into its own, already consumed stage
     // (branch-free, unread).
-    const uint4* wg = wIter + ST * 256;
+    const uint4* wg = W8 ? wIter + (size_t)ST * wStep8 : wIter + ST * 256;
     const uint4* xg = xIter + ST * (kDmaRowBlocks * 64);
     static_for<0, 8 * kDmaWaveRowBlocks>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
@@ -200,10 +241,17 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
       }
       if constexpr (x >= 1 && sb == 1) xf[x - 1] = xr[(x - 1) * 64];  // row block x-1 of step k+1, in place
       if constexpr (i == 8 * kDmaWaveRowBlocks - 1) xf[x] = xr[x * 64];
-      if constexpr (x >= 1 && x <= 8 && sb == 3) wf[nxt][x - 1] = wr[(x - 1) * 64];  // weight sub-block x-1
-      if constexpr (x >= 1 && (sb == 5 || sb == 6)) {  // piece x-1: 0..3 weights, 4..9 embedding row block wave+4q
-        constexpr int p = x - 1, q = p - 4;
-        if constexpr (p < 4) {
+      if constexpr (W8) {
+        // weight sub-block x-1 of step k+1: codes read behind MFMA (x, 0), converted behind MFMAs (x+1, 2..5),
+        // so that every MFMA of the step has at most one vector, LDS or memory instruction behind it
+        if constexpr (x >= 2 && x <= 9 && sb >= 2 && sb <= 5) set_dword(wf[nxt][x - 2], sb - 2, fp8_pair_to_bf16x2(raw[x - 2], sb - 2));
+        if constexpr (x >= 1 && x <= 8 && sb == 0) raw[x - 1] = wr8[(x - 1) * 64];
+      } else {
+        if constexpr (x >= 1 && x <= 8 && sb == 3) wf[nxt][x - 1] = wr[(x - 1) * 64];  // weight sub-block x-1
+      }
+      if constexpr (x >= 1 && x <= kPieces && (sb == 5 || sb == 6)) {  // piece x-1: weights first, then row blocks wave+4q
+        constexpr int p = x - 1, q = p - kNW;
+        if constexpr (p < kNW) {
           if constexpr (sb == 5) set_m0(ldsW0 + stageByte + p * 1024);
           if constexpr (sb == 6) dma_issue(wg, lane16 + p * 1024);
         } else if constexpr (q < 5) {
@@ -220,7 +268,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   const int nKK = KS / 4;  // KS is a multiple of 8: d is padded to 256
   for (int kk = 0; kk < nKK; ++kk) {
     const int kn = min(kk + 1, nKK - 1);  // group of four steps requested during this one
-    const uint4* wIter = wsrc0 + (size_t)kn * wGroupStride;
+    const uint4* wIter = W8 ? wsrc0 + (size_t)kn * 4 * wStep8 : wsrc0 + (size_t)kn * ((size_t)nVGalloc * (kWpKG * 256));
     const uint4* xIter = xsrc0 + (size_t)kn * (4 * kDmaRowBlocks * 64);
     k_step(wIter, xIter, std::integral_constant<int, 0>{});
     k_step(wIter, xIter, std::integral_constant<int, 1>{});
@@ -287,18 +335,53 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   }
 }
 
+// Wg8[ks][vg][sub][lane][8 B]: the FP8 E4M3 codes of W_lm in MFMA fragment order for this kernel, one
+// 512-byte fragment per (K step, vocabulary group, 16-row sub-block): lane holds row vg*64 + sub*16 + lane%16,
+// hidden indices ks*32 + (lane/16)*8 + 0..7.  The four fragments of a group and the four groups of a
+// workgroup's tile are adjacent, so a K step of a tile is 8 KiB of consecutive memory.  Zero padded.
+__global__ __launch_bounds__(256) void pack_w8g_kernel(const uint8_t* __restrict__ W8, int layout, int V, int d,
+                                                        int nVGalloc, size_t total, uint2* __restrict__ Wg8) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const int sub = (int)((idx >> 6) & 3);
+  const size_t t = idx >> 8;
+  const int vg = (int)(t % (size_t)nVGalloc);
+  const int ks = (int)(t / (size_t)nVGalloc);
+  const int v = vg * kVocabGroup + sub * 16 + (lane & 15);
+  const int k0 = ks * kKStep + (lane >> 4) * 8;
+  union { uint2 q; uint8_t b[8]; } o;
+  o.q = make_uint2(0u, 0u);
+  if (v < V)
+    for (int e = 0; e < 8; ++e)
+      if (k0 + e < d) o.b[e] = (layout == 0) ? W8[(size_t)v * d + k0 + e] : W8[(size_t)(k0 + e) * V + v];
+  Wg8[idx] = o.q;
+}
+
+hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* Wg8, hipStream_t st) {
+  const size_t total = (size_t)(g.dpad / kKStep) * g.nVGalloc * 256;
+  const size_t blocks = (total + 255) / 256;
+  if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(pack_w8g_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const uint8_t*>(W8),
+                     layout, g.V, g.d, g.nVGalloc, total, static_cast<uint2*>(Wg8));
+  return hipGetLastError();
+}
+
 // More LDS than the default limit of a launch: raised once per process, at context creation (not in the
 // launcher, which may run under stream capture).
 hipError_t init_lmhead_gemm_dma() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<false>);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<true>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<true>);
 }
 
-hipError_t launch_lmhead_gemm_dma(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
-                                  float invT, float* L, float2* part, void* Xp, hipStream_t st) {
+hipError_t launch_lmhead_gemm_dma(const void* W, int w_fp8, const float* vscale, const void* X, int R,
+                                  const Geometry& g, float invT, float* L, float2* part, void* Xp, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
   static_assert(kWpKG * 256 == 4 * 256 && kKStep == 32, "a K step of one vocabulary group is 4 KiB, contiguous");
-  if (R <= 0 || !Xp) return hipErrorInvalidValue;
+  if (R <= 0 || !Xp || !W) return hipErrorInvalidValue;
   const int nRowTiles = (R + kDmaRows - 1) / kDmaRows;
   const int KS = g.dpad / kKStep;  // multiple of 8
   if (KS < 2 * kDmaStages) return hipErrorInvalidValue;
@@ -306,9 +389,14 @@ hipError_t launch_lmhead_gemm_dma(const void* Wp, const float* vscale, const voi
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
-  hipLaunchKernelGGL(lmhead_gemm_dma_kernel, dim3(grid), dim3(256), kDmaLdsBytes, st, static_cast<const uint4*>(Wp),
-                     vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG, g.nVGalloc, nRowTiles, nVocabTiles,
-                     invT, L, g.Vpad, part);
+  if (w_fp8)
+    hipLaunchKernelGGL(lmhead_gemm_dma_kernel<true>, dim3(grid), dim3(256), kDmaLdsBytes<true>, st,
+                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG,
+                       g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
+  else
+    hipLaunchKernelGGL(lmhead_gemm_dma_kernel<false>, dim3(grid), dim3(256), kDmaLdsBytes<false>, st,
+                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG,
+                       g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
   return hipGetLastError();
 }
 

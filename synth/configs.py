@@ -66,6 +66,7 @@ CONFIGS: Dict[str, VerifyShape] = {
     "C2q": VerifyShape("C2q", 1, 5, 4096, 128256, "fp8", 1.5, "Llama-3.1-8B-shaped head, FP8 W_lm"),
     "C3q": VerifyShape("C3q", 1, 25, 8192, 128256, "fp8", 1.0, "Llama-3.1-70B-shaped head, FP8 W_lm"),
     "C4q": VerifyShape("C4q", 1, 25, 16384, 128256, "fp8", 2.0, "Llama-3.1-405B-shaped head, FP8 W_lm"),
+    "C5q": VerifyShape("C5q", 64, 10, 8192, 128256, "fp8", (0.5, 2.5), "batched verification, FP8 W_lm"),
 }
 
 
