@@ -175,23 +175,36 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     const uint4* xnext = xbase + (size_t)min(ch + 2, nChunks - 1) * ITEMS;
     uint4* xdst = xs[parity ^ 1];
     const uint4* xcur = xs[parity] + lane;
-    // Memory instructions are dealt out one per row block between the MFMAs, never in a
-    // burst: with one wavefront per SIMD nothing else can issue while a wavefront waits for
-    // the texture-address or LDS queue to take its instruction, and the four wavefronts of
-    // the workgroup together keep those queues busy for ~60 % of the MFMA time.
-    auto stage_item = [&](const int i) {  // write item i of chunk c+1 to LDS, reload it for chunk c+2
+    // write item i of chunk c+1 to LDS / reload the same registers with item i of chunk c+2
+    auto stage_store = [&](const int i) {
       switch (i) {
-        case 0: xdst[tid] = xa0; xa0 = xnext[tid]; break;
-        case 1: xdst[tid + 256] = xa1; xa1 = xnext[tid + 256]; break;
-        case 2: xdst[tid + 512] = xa2; xa2 = xnext[tid + 512]; break;
-        case 3: xdst[tid + 768] = xa3; xa3 = xnext[tid + 768]; break;
-        case 4: xdst[tid + 1024] = xb0; xb0 = xnext[tid + 1024]; break;
-        case 5: xdst[tid + 1280] = xb1; xb1 = xnext[tid + 1280]; break;
-        case 6: xdst[tid + 1536] = xb2; xb2 = xnext[tid + 1536]; break;
-        case 7: xdst[tid + 1792] = xb3; xb3 = xnext[tid + 1792]; break;
-        case 8: xdst[tid + 2048] = xc0; xc0 = xnext[tid + 2048]; break;
-        case 9: xdst[tid + 2304] = xc1; xc1 = xnext[tid + 2304]; break;
-        case 10: xdst[tid + 2560] = xc2; xc2 = xnext[tid + 2560]; break;
+        case 0: xdst[tid] = xa0; break;
+        case 1: xdst[tid + 256] = xa1; break;
+        case 2: xdst[tid + 512] = xa2; break;
+        case 3: xdst[tid + 768] = xa3; break;
+        case 4: xdst[tid + 1024] = xb0; break;
+        case 5: xdst[tid + 1280] = xb1; break;
+        case 6: xdst[tid + 1536] = xb2; break;
+        case 7: xdst[tid + 1792] = xb3; break;
+        case 8: xdst[tid + 2048] = xc0; break;
+        case 9: xdst[tid + 2304] = xc1; break;
+        case 10: xdst[tid + 2560] = xc2; break;
+        default: break;
+      }
+    };
+    auto stage_load = [&](const int i) {
+      switch (i) {
+        case 0: xa0 = xnext[tid]; break;
+        case 1: xa1 = xnext[tid + 256]; break;
+        case 2: xa2 = xnext[tid + 512]; break;
+        case 3: xa3 = xnext[tid + 768]; break;
+        case 4: xb0 = xnext[tid + 1024]; break;
+        case 5: xb1 = xnext[tid + 1280]; break;
+        case 6: xb2 = xnext[tid + 1536]; break;
+        case 7: xb3 = xnext[tid + 1792]; break;
+        case 8: xc0 = xnext[tid + 2048]; break;
+        case 9: xc1 = xnext[tid + 2304]; break;
+        case 10: xc2 = xnext[tid + 2560]; break;
         default: break;
       }
     };
@@ -208,15 +221,21 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
       bf16x8 bfrag[3];
       bfrag[0] = __builtin_bit_cast(bf16x8, xcur[(0 * kGemmSteps + ks) * 64]);
       bfrag[1] = __builtin_bit_cast(bf16x8, xcur[(1 * kGemmSteps + ks) * 64]);
+      // Behind each MFMA of a lone wavefront exactly one vector, LDS or memory instruction issues for free
+      // (every further one delays the next MFMA by about 7 cycles), so the step's loads, LDS writes and LDS
+      // reads are dealt out one per MFMA: row block x carries behind its four MFMAs
+      //   a weight load (even x) or a staging write (odd x) | the matching staging load | an operand read | -
 #pragma unroll
       for (int x = 0; x < NXB; ++x) {
-        if (x % 2 == 0 && x / 2 < 4) wbuf[nslot][s][x / 2] = wsrc[s * 256 + (x / 2) * 64];
-        if (x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < IPT) stage_item(ks * 4 + x / 2);
-        if (x + 2 < NXB) bfrag[(x + 2) % 3] = __builtin_bit_cast(bf16x8, xcur[((x + 2) * kGemmSteps + ks) * 64]);
 #pragma unroll
-        for (int sub = 0; sub < 4; ++sub)
+        for (int sub = 0; sub < 4; ++sub) {
           mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
-        __builtin_amdgcn_sched_barrier(0);  // keep this dealing-out as written
+          if (sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][s][x / 2] = wsrc[s * 256 + (x / 2) * 64];
+          if (sub == 0 && x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < IPT) stage_store(ks * 4 + x / 2);
+          if (sub == 1 && x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < IPT) stage_load(ks * 4 + x / 2);
+          if (sub == 2 && x + 2 < NXB) bfrag[(x + 2) % 3] = __builtin_bit_cast(bf16x8, xcur[((x + 2) * kGemmSteps + ks) * 64]);
+          __builtin_amdgcn_sched_barrier(0);  // keep this dealing-out as written
+        }
       }
     };
     k_step(std::integral_constant<int, 0>{});
