@@ -131,8 +131,8 @@ int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void
  * 8-bit weights, Table 1 / App. B.3): the effective LM head is W[v,:] = d_w_scale[v] * decode(code[v,:]).
  *   d_w_scale   [V] fp32 device pointer, borrowed for the lifetime of the context; NULL means all ones.
  *               Must be NULL for JD_F32 / JD_BF16 weights (INVALID_ARG otherwise).
- * The library builds a re-tiled FP8 copy (V*d bytes) for the small-row regime and, if
- * max_B*(max_M+1) > 64, a re-tiled bf16 copy (exact conversion) for the large-row regime.
+ * The library builds a re-tiled FP8 copy (V*d bytes) and, if max_B*(max_M+1) > 64, a second FP8 copy in
+ * the fragment order of the large-row kernels (another V*d bytes); codes become bf16 in registers (exact).
  * d must be a multiple of 16.  Other errors as jd_verify_create.
  */
 int jd_verify_create_scaled(const jd_verify_config* cfg, const void* d_W_lm, const float* d_w_scale,

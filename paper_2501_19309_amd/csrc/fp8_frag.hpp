@@ -1,0 +1,34 @@
+// FP8 E4M3 codes -> bf16 MFMA fragments in registers (device code shared by the large-row LM-head kernels).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace jd {
+
+// Two FP8 E4M3 codes (the low or the high 16 bits of `src`) to two packed bf16 values: gfx950 does it in
+// one instruction (the scale operand is 1; every E4M3 value is a bf16 value, so the result is exact -
+// checked on the device for all code pairs against the float conversion).  Inline assembly because the
+// instruction has to stay behind the MFMA it is written behind: between two MFMAs of a lone wavefront
+// exactly one vector, LDS or memory instruction issues for free, every further one delays the next MFMA by
+// about 7 cycles (measured); scalar instructions ride along.  Left to the compiler, all conversions of a
+// K step end up in one block.
+__device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t src, bool high_half) {
+  uint32_t o;
+  if (high_half)
+    asm volatile("v_cvt_scalef32_pk_bf16_fp8 %0, %1, 1.0 op_sel:[1,0,0]" : "=v"(o) : "v"(src));
+  else
+    asm volatile("v_cvt_scalef32_pk_bf16_fp8 %0, %1, 1.0" : "=v"(o) : "v"(src));
+  return o;
+}
+
+// Dword j (0..3) of the bf16 fragment of the eight codes (lo, hi), ascending hidden index.
+__device__ __forceinline__ uint32_t fp8_frag_dword(uint32_t lo, uint32_t hi, int j) {
+  return fp8x2_to_bf16x2(j < 2 ? lo : hi, (j & 1) != 0);
+}
+
+__device__ __forceinline__ void set_dword(uint4& v, int j, uint32_t x) {
+  if (j == 0) v.x = x; else if (j == 1) v.y = x; else if (j == 2) v.z = x; else v.w = x;
+}
+
+}  // namespace jd

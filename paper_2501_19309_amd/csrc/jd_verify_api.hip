@@ -194,7 +194,7 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
     JD_HIP_RC(launch_pack_w8(d_W_lm, cfg->w_layout, c->geo, c->Wp8, nullptr));
     JD_HIP_RC(hipDeviceSynchronize());
   }
-  if (rc == JD_OK && bf16 && (!fp8 || maxR > 64)) {  // FP8 contexts need the bf16 copy only for the GEMM regime
+  if (rc == JD_OK && bf16 && !fp8) {  // FP8 contexts work from their FP8 copies in every regime
     uint8_t* wp = nullptr;
     rc = dev_alloc(c, &wp, c->geo.packed_bytes());
     c->Wp = wp;
@@ -328,8 +328,8 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
       JD_HIP(launch_lmhead_gemm_dma(fp8 ? c->Wg8 : c->Wp, fp8 ? 1 : 0, fp8 ? c->wscale : nullptr, d_emb, R, g, invT,
                                     c->L, c->tpart, c->Xp, st));
     } else {
-      JD_HIP(launch_lmhead_gemm(c->Wp, fp8 ? c->wscale : nullptr, d_emb, R, g, invT, c->L, c->tpart, c->Xp,
-                                c->num_cus, st));
+      JD_HIP(launch_lmhead_gemm(fp8 ? c->Wp8 : c->Wp, fp8 ? 1 : 0, fp8 ? c->wscale : nullptr, d_emb, R, g, invT, c->L,
+                                c->tpart, c->Xp, st));
     }
   } else {
     JD_HIP(launch_lmhead_f32(static_cast<const float*>(c->W), cfg.w_layout, static_cast<const float*>(d_emb), R,

@@ -21,6 +21,7 @@
 // partial per (row, 64-entry vocabulary group).
 #include <type_traits>
 
+#include "fp8_frag.hpp"
 #include "jd_kernels.hpp"
 
 namespace jd {
@@ -76,6 +77,11 @@ hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks
   return hipGetLastError();
 }
 
+// W8 = false: Wp is the re-tiled bf16 copy.  W8 = true: Wp is Wp8, the FP8 copy of the small-row kernel (a
+// lane's 16 bytes are its codes for the two K steps of a prefetch group): half the weight bytes from HBM
+// and through L2; fragments are converted to bf16 in registers one K step ahead, one instruction behind
+// an MFMA each; the per-entry scale is applied in the epilogue.
+template <bool W8>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
     int nChunks, int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L,
@@ -109,7 +115,8 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   const int nGroupsTotal = KS / kGemmPF;
   static_assert(kWpKG % kGemmPF == 0, "a prefetch group (8 KiB) never straddles two K-step blocks of Wp");
 
-  const uint4* wbase = Wp + wp_group_offset(vg);
+  static_assert(kGemmPF == 2 && kW8KG % 2 == 0, "a prefetch group is one FP8 K-step pair");
+  const uint4* wbase = Wp + (W8 ? wp8_group_offset(vg) : wp_group_offset(vg));
   const uint4* xbase = Xp + (size_t)rt * nChunks * ITEMS;
 
   f32x4 acc[4][NXB];
@@ -118,7 +125,8 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
 #pragma unroll
     for (int x = 0; x < NXB; ++x) acc[s][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  uint4 wbuf[kGemmWBufs][kGemmPF][4];
+  uint4 wbuf[kGemmWBufs][W8 ? 1 : kGemmPF][4];  // ring of weight groups (FP8: codes of both K steps in one item)
+  uint4 cv[2][4];                               // FP8 only: converted fragments of the current / next K step
 
   // Staging of the embedding tile runs a whole chunk ahead: during chunk c, step p first
   // writes portion p of chunk c+1 (loaded one chunk earlier) into the idle LDS buffer and
@@ -143,11 +151,17 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     if constexpr (p == 2) { dst[tid + 2048] = xc0; dst[tid + 2304] = xc1; dst[tid + 2560] = xc2; }
   };
   auto load_wgroup = [&](const int buf, int g) {
-    const uint4* src = wbase + wp_step_offset(g * kGemmPF, nVGalloc);
+    if constexpr (W8) {
+      const uint4* src = wbase + wp8_pair_offset(g, nVGalloc);
 #pragma unroll
-    for (int s2 = 0; s2 < kGemmPF; ++s2)
+      for (int sub = 0; sub < 4; ++sub) wbuf[buf][0][sub] = src[sub * 64 + lane];
+    } else {
+      const uint4* src = wbase + wp_step_offset(g * kGemmPF, nVGalloc);
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub) wbuf[buf][s2][sub] = src[s2 * 256 + sub * 64 + lane];
+      for (int s2 = 0; s2 < kGemmPF; ++s2)
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) wbuf[buf][s2][sub] = src[s2 * 256 + sub * 64 + lane];
+    }
   };
 
   // prologue: chunk 0 into LDS buffer 0, chunk 1 into the staging registers
@@ -165,6 +179,12 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   load_wgroup(0, 0);
   load_wgroup(1, min(1, nGroupsTotal - 1));
   load_wgroup(2, min(2, nGroupsTotal - 1));
+  if constexpr (W8) {  // fragments of K step 0
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) set_dword(cv[0][sub], jj, fp8_frag_dword(wbuf[0][0][sub].x, wbuf[0][0][sub].y, jj));
+  }
   __syncthreads();
 
   // One staged chunk.  `parity` (chunk index mod 2) is a compile-time constant: it selects the
@@ -215,8 +235,8 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
       constexpr int nslot = (slot + kGemmWBufs - 1) % kGemmWBufs;
       // the weight group three ahead goes into the slot freed by the previous group, four
       // fragments per K step (past the end it re-reads the last group, unread)
-      const uint4* wsrc =
-          wbase + wp_step_offset(min(ch * GROUPS + gi + kGemmWBufs - 1, nGroupsTotal - 1) * kGemmPF, nVGalloc) + lane;
+      const int gnext = min(ch * GROUPS + gi + kGemmWBufs - 1, nGroupsTotal - 1);
+      const uint4* wsrc = wbase + (W8 ? wp8_pair_offset(gnext, nVGalloc) : wp_step_offset(gnext * kGemmPF, nVGalloc)) + lane;
       // operand reads run two row blocks ahead of the MFMAs that consume them
       bf16x8 bfrag[3];
       bfrag[0] = __builtin_bit_cast(bf16x8, xcur[(0 * kGemmSteps + ks) * 64]);
@@ -229,8 +249,24 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
       for (int x = 0; x < NXB; ++x) {
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub) {
-          mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
-          if (sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][s][x / 2] = wsrc[s * 256 + (x / 2) * 64];
+          if constexpr (W8) {
+            mfma_16x16x32_bf16_inplace(acc[sub][x], cv[ks & 1][sub], bfrag[x % 3]);
+            // codes of the group three ahead: four loads, in the first K step of a group only
+            if (s == 0 && sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][0][x / 2] = wsrc[(x / 2) * 64];
+            // fragments of the next K step (second half of this group's codes, or first half of the next
+            // group's): 16 conversions, behind MFMA (x, 3) of every row block and five otherwise empty slots
+            constexpr int cslot = (s == 0) ? slot : (slot + 1) % kGemmWBufs;
+            const int c = (sub == 3) ? x : (x == 8 && sub < 2) ? 11 + sub : (x == 9 && sub < 2) ? 13 + sub
+                                                                         : (x == 10 && sub == 0) ? 15 : -1;
+            if (c >= 0) {
+              const uint4& codes = wbuf[cslot][0][c / 4];
+              set_dword(cv[(ks + 1) & 1][c / 4], c % 4,
+                        s == 0 ? fp8_frag_dword(codes.z, codes.w, c % 4) : fp8_frag_dword(codes.x, codes.y, c % 4));
+            }
+          } else {
+            mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
+            if (sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][s][x / 2] = wsrc[s * 256 + (x / 2) * 64];
+          }
           if (sub == 0 && x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < IPT) stage_store(ks * 4 + x / 2);
           if (sub == 1 && x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < IPT) stage_load(ks * 4 + x / 2);
           if (sub == 2 && x + 2 < NXB) bfrag[(x + 2) % 3] = __builtin_bit_cast(bf16x8, xcur[((x + 2) * kGemmSteps + ks) * 64]);
@@ -308,23 +344,31 @@ constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * 
 // More LDS than the default limit of a launch: raised once per process, at context creation (not in the
 // launcher, which may run under stream capture).
 hipError_t init_lmhead_gemm() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<true>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
 }
 
-hipError_t launch_lmhead_gemm(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
-                              float invT, float* L, float2* part, void* Xp, int /*num_cus*/, hipStream_t st) {
+hipError_t launch_lmhead_gemm(const void* W, int w_fp8, const float* vscale, const void* X, int R, const Geometry& g,
+                              float invT, float* L, float2* part, void* Xp, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
-  if (R <= 0 || !Xp) return hipErrorInvalidValue;
+  if (R <= 0 || !Xp || !W) return hipErrorInvalidValue;
   const int nRowTiles = (R + kGemmRows - 1) / kGemmRows;
   const int nChunks = g.dpad / kGemmKChunk;
   hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, nChunks, kGemmRowBlocks, kGemmSteps, Xp, st);
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
-  hipLaunchKernelGGL(lmhead_gemm_kernel, dim3(grid), dim3(256), kGemmLdsBytes, st, static_cast<const uint4*>(Wp), vscale,
-                     static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG, g.nVGalloc, nRowTiles, nVocabTiles, invT,
-                     L, g.Vpad, part);
+  if (w_fp8)
+    hipLaunchKernelGGL(lmhead_gemm_kernel<true>, dim3(grid), dim3(256), kGemmLdsBytes, st,
+                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,
+                       g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
+  else
+    hipLaunchKernelGGL(lmhead_gemm_kernel<false>, dim3(grid), dim3(256), kGemmLdsBytes, st,
+                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,
+                       g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
   return hipGetLastError();
 }
 

@@ -31,6 +31,7 @@
 //     registers), so stage k is re-filled for step k+4.
 #include <type_traits>
 
+#include "fp8_frag.hpp"
 #include "jd_kernels.hpp"
 
 namespace jd {
@@ -89,26 +90,6 @@ __device__ __forceinline__ void dma_1k(const uint4* gsrc, unsigned lds_byte, uns
 __device__ __forceinline__ void set_m0(unsigned lds_byte) { asm volatile("s_mov_b32 m0, %0" ::"s"(lds_byte)); }
 __device__ __forceinline__ void dma_issue(const uint4* gbase, unsigned lane_off) {
   asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase) : "memory");
-}
-
-// Dword j (0..3) of the bf16 fragment of eight FP8 E4M3 codes c (two dwords, ascending hidden index):
-// gfx950 converts two codes to two packed bf16 values in one instruction (the scale operand is 1; every
-// E4M3 value is a bf16 value, so the result is exact - checked on the device for all code pairs against
-// the float conversion).  Inline assembly because the instruction has to stay behind the MFMA it is
-// written behind: between two MFMAs of a lone wavefront exactly one vector, LDS or memory instruction
-// issues for free, every further one delays the next MFMA by about 7 cycles (measured); scalar
-// instructions ride along.  Left to the compiler, all conversions of a K step end up in one block.
-__device__ __forceinline__ uint32_t fp8_pair_to_bf16x2(const uint2& c, int j) {
-  const uint32_t src = j < 2 ? c.x : c.y;
-  uint32_t o;
-  if (j & 1)
-    asm volatile("v_cvt_scalef32_pk_bf16_fp8 %0, %1, 1.0 op_sel:[1,0,0]" : "=v"(o) : "v"(src));
-  else
-    asm volatile("v_cvt_scalef32_pk_bf16_fp8 %0, %1, 1.0" : "=v"(o) : "v"(src));
-  return o;
-}
-__device__ __forceinline__ void set_dword(uint4& v, int j, uint32_t x) {
-  if (j == 0) v.x = x; else if (j == 1) v.y = x; else if (j == 2) v.z = x; else v.w = x;
 }
 
 // W8 = false: Wsrc is the re-tiled bf16 copy Wp.  W8 = true: Wsrc is the FP8 copy Wg8 (see pack_w8g_kernel):
@@ -201,7 +182,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
       for (int s = 0; s < 8; ++s) {
         const uint2 c = wr[s * 64];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) set_dword(wf[0][s], jj, fp8_pair_to_bf16x2(c, jj));
+        for (int jj = 0; jj < 4; ++jj) set_dword(wf[0][s], jj, fp8_frag_dword(c.x, c.y, jj));
       }
     } else {
       const uint4* wr = lds + kDmaXItems + vh * 8 * 64 + lane;
@@ -244,7 +225,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
       if constexpr (W8) {
         // weight sub-block x-1 of step k+1: codes read behind MFMA (x, 0), converted behind MFMAs (x+1, 2..5),
         // so that every MFMA of the step has at most one vector, LDS or memory instruction behind it
-        if constexpr (x >= 2 && x <= 9 && sb >= 2 && sb <= 5) set_dword(wf[nxt][x - 2], sb - 2, fp8_pair_to_bf16x2(raw[x - 2], sb - 2));
+        if constexpr (x >= 2 && x <= 9 && sb >= 2 && sb <= 5) set_dword(wf[nxt][x - 2], sb - 2, fp8_frag_dword(raw[x - 2].x, raw[x - 2].y, sb - 2));
         if constexpr (x >= 1 && x <= 8 && sb == 0) raw[x - 1] = wr8[(x - 1) * 64];
       } else {
         if constexpr (x >= 1 && x <= 8 && sb == 3) wf[nxt][x - 1] = wr[(x - 1) * 64];  // weight sub-block x-1

@@ -143,19 +143,19 @@ def loop_benchmark(config: str, iters: int, n_sets: int, seed: int, prenorm: boo
     return rec
 
 
-def sweep(batch_sizes: List[int], steps: int, seed: int) -> List[dict]:
+def sweep(batch_sizes: List[int], steps: int, seed: int, dtype: str = "bf16") -> List[dict]:
     import torch
     from synth import VerifyShape, make_inputs
 
     Bmax, M, d, V = max(batch_sizes), 10, 8192, 128256
-    shape = VerifyShape("sweep", Bmax, M, d, V, "bf16", (0.5, 2.5), "70B-shaped head, batch sweep")
+    shape = VerifyShape("sweep", Bmax, M, d, V, dtype, (0.5, 2.5), "70B-shaped head, batch sweep")
     t0 = time.time()
     x = make_inputs(shape, seed)
     log(f"[sweep] inputs for B={Bmax} drawn in {time.time() - t0:.1f}s")
     dev = harness.to_device(x)
     ver = harness.make_verifier(dev)   # max_B = Bmax: one context, one re-tiled W_lm for every batch size
     recs = []
-    w_bytes = V * d * 2
+    w_bytes = V * d * (1 if dtype == "fp8" else 2)
     for B in batch_sizes:
         R = B * (M + 1)
         e, t, D, u = (dev[k][:B].contiguous() for k in ("emb", "draft_tokens", "draft_logits", "uniforms"))
@@ -176,7 +176,7 @@ def sweep(batch_sizes: List[int], steps: int, seed: int) -> List[dict]:
         lm = kms["lmhead"]
         kernel = "skinny (W_lm streamed once)" if R <= 64 else ("352 x 256 tiles" if -(-R // 352) * 352 == -(-R // 176) * 176
                                                               else "176 x 256 tiles")
-        recs.append({"B": B, "M": M, "rows": R, "ms_per_call": ms, "verified_positions_per_s": B * M / (ms * 1e-3),
+        recs.append({"B": B, "M": M, "W_lm": dtype, "rows": R, "ms_per_call": ms, "verified_positions_per_s": B * M / (ms * 1e-3),
                      "lmhead_ms": lm, "lmhead_kernel": kernel,
                      "lmhead_W_GBs": w_bytes / (lm * 1e-3) / 1e9, "lmhead_frac_hbm_peak": w_bytes / (lm * 1e-3) / 8e12,
                      "lmhead_TFLOPs": 2.0 * R * d * V / (lm * 1e-3) / 1e12,
@@ -197,10 +197,11 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true", help="also time the loop as replayed HIP graphs")
     ap.add_argument("--sweep", default="", help="comma-separated batch sizes; runs the sweep instead of the loop")
     ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--dtype", default="bf16", choices=("bf16", "fp8"), help="W_lm storage type of the sweep")
     args = ap.parse_args()
     jb.load_library()
     if args.sweep:
-        for rec in sweep([int(b) for b in args.sweep.split(",")], args.steps, args.seed):
+        for rec in sweep([int(b) for b in args.sweep.split(",")], args.steps, args.seed, args.dtype):
             print(json.dumps(rec))
     else:
         print(json.dumps(loop_benchmark(args.config, args.iters, args.sets, args.seed, args.prenorm, args.graph)))

@@ -233,7 +233,8 @@ FP8 = [
     VerifyShape("q_2blk", 1, 25, 512, 2048, "fp8", 1.0),
     VerifyShape("q_ragged", 2, 9, 272, 1000, "fp8", 2.0),        # d % 256 != 0, V % 64 != 0
     VerifyShape("q_4blk", 4, 15, 768, 3000, "fp8", 1.5),         # R = 64
-    VerifyShape("q_gemm", 9, 10, 512, 5000, "fp8", (0.5, 2.5)),  # R = 99: large-row regime, bf16 copy + scales
+    VerifyShape("q_gemm", 9, 10, 512, 5000, "fp8", (0.5, 2.5)),  # R = 99: 176-row tiling, FP8 codes converted in registers
+    VerifyShape("q_gemm176x3", 40, 10, 784, 3333, "fp8", (0.5, 2.5)),  # R = 440: three 176-row tiles, ragged d and V
     VerifyShape("q_gemm352", 20, 10, 288, 2100, "fp8", (0.5, 2.5)),  # R = 220: 352-row tiling, FP8 fragments
     VerifyShape("q_gemm704", 64, 10, 528, 4100, "fp8", (0.5, 2.5)),  # R = 704: two 352-row tiles, ragged d and V
     VerifyShape("q_gemm_d16", 33, 10, 16, 130, "fp8", 1.0),          # R = 363: two tiles, one real K step
