@@ -43,8 +43,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "C2q", "C3q", "C4q", "C5q"],
-                    help="C2..C5: bf16 W_lm (C4 is the headline); C2q..C4q: the same shapes with FP8 E4M3 W_lm")
+    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "C2q", "C3q", "C4q", "C5q", "C2i", "C3i", "C4i"],
+                    help="C2..C5: bf16 W_lm (C4 is the headline); C2q..C5q: the same shapes with FP8 E4M3 W_lm; "
+                         "C2i..C4i: with INT8 W_lm")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rule", default="sampling", choices=["sampling", "topk"],
@@ -130,9 +131,9 @@ def main() -> int:
     log(f"[bench] ms/step {ms_per_step:.4f} (with per-kernel events {ms_events:.4f}); kernels {kernel_ms}")
 
     got = out.to_numpy()
-    elem = {"bf16": 2, "fp8": 2, "f32": 4}[shape.dtype]      # embeddings / judge weight
-    w_elem = {"bf16": 2, "fp8": 1, "f32": 4}[shape.dtype]    # LM-head weight
-    w_bytes = V * d * w_elem + (V * 4 if shape.dtype == "fp8" else 0)   # FP8: + one fp32 scale per entry
+    elem = {"bf16": 2, "fp8": 2, "int8": 2, "f32": 4}[shape.dtype]      # embeddings / judge weight
+    w_elem = {"bf16": 2, "fp8": 1, "int8": 1, "f32": 4}[shape.dtype]    # LM-head weight
+    w_bytes = V * d * w_elem + (V * 4 if shape.dtype in ("fp8", "int8") else 0)   # 8-bit: + one fp32 scale per entry
     x_bytes = R * d * elem
     lm_ms = kernel_ms["lmhead"]
     flops = 2.0 * R * d * V
@@ -158,15 +159,15 @@ def main() -> int:
         "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if shape.dtype == "fp8" else shape.dtype, "data": "synthetic",
+        "dtype": "bf16" if shape.dtype in ("fp8", "int8") else shape.dtype, "data": "synthetic",
         "config": {"workload": f"{shape.name}: B={B} M={M} (+1 bonus row) d={d} V={V} "
-                               f"{'FP8 E4M3 (+fp32 row scales)' if shape.dtype == 'fp8' else shape.dtype} W_lm, "
+                               f"{ {'fp8': 'FP8 E4M3 (+fp32 row scales)', 'int8': 'INT8 (+fp32 row scales)'}.get(shape.dtype, shape.dtype)} W_lm, "
                                f"fp32 draft logits; {shape.note}", "seed": args.seed,
                    "rule": args.rule if args.rule == "sampling" else f"topk(K={args.top_k})",
                    "wiring": "pre-norm hidden states in, RMS norm inside the call" if args.prenorm
                              else "normalised embeddings in",
                    "rows": R, "W_lm_bytes": w_bytes,
-                   "W_lm_retiled_copy": shape.dtype in ("bf16", "fp8")},
+                   "W_lm_retiled_copy": shape.dtype in ("bf16", "fp8", "int8")},
         "roofline": roofline,
         "whole_call": {"ms_per_step_with_kernel_events": ms_events, "algorithmic_bytes": call_bytes,
                        "gbs": call_bytes / (ms_per_step * 1e-3) / 1e9,

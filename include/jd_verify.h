@@ -51,6 +51,9 @@ extern "C" {
 #define JD_FP8_E4M3 2                 /* W_lm only: OCP FP8 E4M3 ("e4m3fn") codes, 1 byte, with one   */
                                       /* fp32 scale per vocabulary entry (jd_verify_create_scaled);   */
                                       /* the paper runs its targets with 8-bit weights (Table 1)      */
+#define JD_INT8  3                    /* W_lm only: two's-complement 8-bit integers, 1 byte, with one */
+                                      /* fp32 scale per vocabulary entry (weight-only quantisation    */
+                                      /* with per-output-channel scales; jd_verify_create_scaled)     */
 
 #define JD_W_VD  0                    /* W_lm stored [V][d]: row v = vocabulary entry v (checkpoint)  */
 #define JD_W_DV  1                    /* W_lm stored [d][V]                                           */
@@ -86,7 +89,7 @@ typedef struct jd_verify_ctx jd_verify_ctx;   /* opaque, owned by the library */
 typedef struct {
   int32_t d, V;                 /* hidden size, vocabulary size                                       */
   int32_t max_B, max_M;         /* workspace is sized for these; 1 <= max_M <= 63                     */
-  int32_t w_dtype, emb_dtype;   /* JD_F32 | JD_BF16, equal; or w_dtype JD_FP8_E4M3 with emb_dtype JD_BF16 */
+  int32_t w_dtype, emb_dtype;   /* JD_F32 | JD_BF16, equal; or w_dtype JD_FP8_E4M3 | JD_INT8 with emb_dtype JD_BF16 */
                                 /* (w_judge always has emb_dtype)                                      */
   int32_t w_layout;             /* JD_W_VD | JD_W_DV                                                  */
   int32_t draft_kind;           /* JD_DRAFT_LOGITS | JD_DRAFT_PROBS                                   */
@@ -127,12 +130,13 @@ int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void
                      jd_verify_ctx** out_ctx);
 
 /*
- * Same as jd_verify_create for quantised weights (w_dtype JD_FP8_E4M3; the paper's targets run with
- * 8-bit weights, Table 1 / App. B.3): the effective LM head is W[v,:] = d_w_scale[v] * decode(code[v,:]).
+ * Same as jd_verify_create for quantised weights (w_dtype JD_FP8_E4M3 or JD_INT8; the paper's targets run
+ * with 8-bit weights, Table 1 / App. B.3): the effective LM head is W[v,:] = d_w_scale[v] * decode(code[v,:]).
  *   d_w_scale   [V] fp32 device pointer, borrowed for the lifetime of the context; NULL means all ones.
  *               Must be NULL for JD_F32 / JD_BF16 weights (INVALID_ARG otherwise).
- * The library builds a re-tiled FP8 copy (V*d bytes) and, if max_B*(max_M+1) > 64, a second FP8 copy in
- * the fragment order of the large-row kernels (another V*d bytes); codes become bf16 in registers (exact).
+ * The library builds a re-tiled copy of the codes (V*d bytes) and, if max_B*(max_M+1) > 64, for the
+ * large-row kernels a second FP8 copy in their fragment order (another V*d bytes) resp. a bf16 copy of the
+ * INT8 weights (2*V*d bytes); codes become bf16 exactly, in registers or in that copy.
  * d must be a multiple of 16.  Other errors as jd_verify_create.
  */
 int jd_verify_create_scaled(const jd_verify_config* cfg, const void* d_W_lm, const float* d_w_scale,

@@ -40,7 +40,8 @@ Readings taken where the paper is silent (each is listed in the design notes):
 8-bit weights (the paper runs its targets with 8-bit weights: Table 1, App. B.3): ``W`` may hold FP8
 E4M3 codes (uint8, the OCP "e4m3fn" format: 4 exponent bits with bias 7, 3 mantissa bits, no
 infinities, 0x7f / 0xff = NaN) with one float32 scale per vocabulary entry; the effective weight is
-scale[v] * decode(code), exactly, and everything downstream is unchanged.
+scale[v] * decode(code), exactly, and everything downstream is unchanged.  ``W`` of dtype int8 is
+8-bit integer weight-only quantisation with the same per-entry scales: decode(code) = the integer.
 
 Variants of the rule that the paper itself uses (selected by ``rule`` / ``resample``):
   * top-K verification, the training-free baseline of Sec. 5: c is accepted iff it is among
@@ -112,10 +113,12 @@ E4M3FN = _e4m3fn_table()
 
 def widen(x: np.ndarray) -> np.ndarray:
     """Exact float64 view of an input tensor: uint16 arrays are bf16 bit patterns, uint8 arrays
-    are FP8 E4M3 codes."""
+    are FP8 E4M3 codes, int8 arrays are 8-bit integer weights."""
     x = np.asarray(x)
     if x.dtype == np.uint8:
         return E4M3FN[x]
+    if x.dtype == np.int8:
+        return x.astype(np.float64)
     if x.dtype == np.uint16:
         return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     if x.dtype in (np.float32, np.float64):
@@ -291,8 +294,8 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
     """Verify one batch of drafts.  See the module docstring for the steps.
 
     emb          [B, M+1, d]  LM-head input (bf16 bits as uint16, or float32)
-    W            [V, d] / [d, V]  (float32, bf16 bits as uint16, or FP8 E4M3 codes as uint8)
-    w_scale      [V] float32 per-vocabulary-entry scale of W (None = 1), meant for FP8 weights
+    W            [V, d] / [d, V]  (float32, bf16 bits as uint16, FP8 E4M3 codes as uint8, or int8 weights)
+    w_scale      [V] float32 per-vocabulary-entry scale of W (None = 1), meant for 8-bit weights
     w_judge      [d]
     draft_tokens [B, M] int
     draft        [B, rows >= M, V] float32 logits or probabilities (rows beyond M unused)

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libjdverify.so")
 
 JD_OK = 0
 JD_ERR_INVALID_ARG, JD_ERR_SHAPE, JD_ERR_UNSUPPORTED_DTYPE, JD_ERR_OOM, JD_ERR_HIP = -1, -2, -3, -4, -5
-JD_F32, JD_BF16, JD_FP8_E4M3 = 0, 1, 2
+JD_F32, JD_BF16, JD_FP8_E4M3, JD_INT8 = 0, 1, 2, 3
 JD_W_VD, JD_W_DV = 0, 1
 JD_DRAFT_LOGITS, JD_DRAFT_PROBS = 0, 1
 JD_MODE_JUDGE, JD_MODE_STANDARD = 0, 1
@@ -120,7 +120,7 @@ def make_config(d, V, max_B, max_M, *, w_dtype=JD_BF16, emb_dtype=None, w_layout
                 judge_bias=0.0, device=0, rule=JD_RULE_SAMPLING, top_k=1,
                 resample=JD_RESAMPLE_RESIDUAL) -> jd_verify_config:
     if emb_dtype is None:
-        emb_dtype = JD_BF16 if w_dtype == JD_FP8_E4M3 else w_dtype
+        emb_dtype = JD_BF16 if w_dtype in (JD_FP8_E4M3, JD_INT8) else w_dtype
     return jd_verify_config(d, V, max_B, max_M, w_dtype, emb_dtype,
                             w_layout, draft_kind, mode, temperature, delta, judge_bias, device,
                             rule, top_k, resample)

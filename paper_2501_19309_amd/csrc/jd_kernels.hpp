@@ -67,6 +67,9 @@ inline Geometry make_geometry(int d, int V) {
   return g;
 }
 
+// Storage of W_lm as the LM-head kernels see it.
+enum WCode : int { kWBf16 = 0, kWFp8 = 1, kWInt8 = 2 };
+
 // ---- packed FP8 W_lm --------------------------------------------------------------
 // FP8 E4M3 weights (one byte per weight, one fp32 scale per vocabulary entry) are re-tiled into
 //
@@ -107,18 +110,18 @@ RowStatsArgs make_rowstats_args(const float* base, int rowsUsed, size_t seqStrid
 // ---- launchers (all asynchronous on `st`) -----------------------------------------
 
 // Re-tile W_lm ([V][d] if layout==0, [d][V] if layout==1) into bf16 Wp, zero padded.  The source
-// holds bf16 values, or (src_fp8) FP8 E4M3 codes that are converted exactly.
-hipError_t launch_pack_w(const void* W, int layout, int src_fp8, const Geometry& g, void* Wp, hipStream_t st);
+// holds bf16 values (src_code kWBf16), or one-byte codes (kWFp8, kWInt8) that are converted exactly.
+hipError_t launch_pack_w(const void* W, int layout, int src_code, const Geometry& g, void* Wp, hipStream_t st);
 
-// Re-tile FP8 E4M3 W_lm into Wp8 (see above), zero padded.
+// Re-tile one-byte codes of W_lm (FP8 E4M3 or INT8) into Wp8 (see above), zero padded.
 hipError_t launch_pack_w8(const void* W8, int layout, const Geometry& g, void* Wp8, hipStream_t st);
 
 // Small-row regime LM head (R <= 64): streams Wp once, MFMA, writes fp32 logits
 // L[r*Lld + v] = (x_r . w_v) * invT for r < R, v < Vpad, and one softmax partial
 // (max, sum exp) per (row, vocabulary group): part[r*nVG + vg].
 // `side` (may be empty) is executed by extra workgroups of the same launch.
-// w_fp8: Wp is Wp8; vscale (fp32 per vocabulary entry, or NULL = 1) multiplies the logits.
-hipError_t launch_lmhead_skinny(const void* Wp, int w_fp8, const float* vscale, const void* X, int R,
+// w_code kWFp8 / kWInt8: Wp is Wp8 and vscale (fp32 per vocabulary entry, or NULL = 1) multiplies the logits.
+hipError_t launch_lmhead_skinny(const void* Wp, int w_code, const float* vscale, const void* X, int R,
                                 const Geometry& g, float invT, float* L, float2* part, const SideWork& side,
                                 hipStream_t st);
 

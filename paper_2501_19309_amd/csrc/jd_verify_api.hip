@@ -19,10 +19,10 @@ struct jd_verify_ctx {
   int num_cus;
   const void* W;
   const void* wj;
-  void* Wp;             // re-tiled bf16 weights (bf16 path; FP8 path only for the large-row regime)
-  void* Wp8;            // re-tiled FP8 weights (FP8 path, small-row kernel)
-  void* Wg8;            // re-tiled FP8 weights for the 352-row kernel (FP8 path, max_R > 64)
-  const float* wscale;  // per-vocabulary-entry weight scale (FP8 path, may be NULL)
+  void* Wp;             // re-tiled bf16 weights (bf16 weights; INT8 weights only for the large-row regime)
+  void* Wp8;            // re-tiled one-byte codes (FP8 and INT8 weights)
+  void* Wg8;            // re-tiled FP8 weights for the 352-row kernel (FP8 weights, max_R > 64)
+  const float* wscale;  // per-vocabulary-entry weight scale (FP8 and INT8 weights, may be NULL)
   float* L;             // [maxR][Vpad] fp32 logits
   float2* tpart;        // [maxR][nPartT]
   float2* dpart;        // [max_B*max_M][nPartD]
@@ -70,7 +70,8 @@ extern "C" const char* jd_verify_strerror(int code) {
 
 extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
   if (!c) return JD_ERR_INVALID_ARG;
-  if (c->w_dtype != JD_F32 && c->w_dtype != JD_BF16 && c->w_dtype != JD_FP8_E4M3) return JD_ERR_INVALID_ARG;
+  if (c->w_dtype != JD_F32 && c->w_dtype != JD_BF16 && c->w_dtype != JD_FP8_E4M3 && c->w_dtype != JD_INT8)
+    return JD_ERR_INVALID_ARG;
   if (c->emb_dtype != JD_F32 && c->emb_dtype != JD_BF16) return JD_ERR_INVALID_ARG;
   if (c->w_layout != JD_W_VD && c->w_layout != JD_W_DV) return JD_ERR_INVALID_ARG;
   if (c->draft_kind != JD_DRAFT_LOGITS && c->draft_kind != JD_DRAFT_PROBS) return JD_ERR_INVALID_ARG;
@@ -86,7 +87,7 @@ extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
   if (c->V > (1 << 30) || c->d > (1 << 20)) return JD_ERR_SHAPE;
   if ((int64_t)c->max_B * (c->max_M + 1) > (1 << 20)) return JD_ERR_SHAPE;
   if (c->rule == JD_RULE_TOPK && (c->top_k < 1 || c->top_k > c->V)) return JD_ERR_SHAPE;
-  if (c->w_dtype == JD_FP8_E4M3) {
+  if (c->w_dtype == JD_FP8_E4M3 || c->w_dtype == JD_INT8) {
     if (c->emb_dtype != JD_BF16) return JD_ERR_UNSUPPORTED_DTYPE;
     if ((c->d % 16) != 0) return JD_ERR_SHAPE;
   } else if (c->w_dtype != c->emb_dtype) {
@@ -129,7 +130,7 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
   int rc = jd_verify_validate_config(cfg);
   if (rc != JD_OK) return rc;
   if (!d_W_lm || !d_w_judge) return JD_ERR_INVALID_ARG;
-  if (d_w_scale && cfg->w_dtype != JD_FP8_E4M3) return JD_ERR_INVALID_ARG;
+  if (d_w_scale && cfg->w_dtype != JD_FP8_E4M3 && cfg->w_dtype != JD_INT8) return JD_ERR_INVALID_ARG;
 
   int ndev = 0;
   JD_HIP(hipGetDeviceCount(&ndev));
@@ -153,8 +154,8 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
 
   const size_t maxR = (size_t)cfg->max_B * (cfg->max_M + 1);
   const size_t maxS = (size_t)cfg->max_B * cfg->max_M;
-  const bool fp8 = cfg->w_dtype == JD_FP8_E4M3;
-  const bool bf16 = cfg->w_dtype == JD_BF16 || fp8;   // MFMA path (bf16 embeddings)
+  const bool fp8 = cfg->w_dtype == JD_FP8_E4M3, int8 = cfg->w_dtype == JD_INT8;
+  const bool bf16 = cfg->w_dtype == JD_BF16 || fp8 || int8;   // MFMA path (bf16 embeddings)
   c->nPartT = bf16 ? c->geo.nVG : kF32Splits;
   c->nPartD = kDraftSplits;
   c->nChunk = (cfg->V + kSamplerChunk - 1) / kSamplerChunk;
@@ -187,18 +188,20 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
       c->rankpart = topk ? reinterpret_cast<int*>(pool + o_rank) : nullptr;
     }
   }
-  if (rc == JD_OK && fp8) {
+  if (rc == JD_OK && (fp8 || int8)) {
     uint8_t* wp8 = nullptr;
     rc = dev_alloc(c, &wp8, c->geo.packed8_bytes());
     c->Wp8 = wp8;
     JD_HIP_RC(launch_pack_w8(d_W_lm, cfg->w_layout, c->geo, c->Wp8, nullptr));
     JD_HIP_RC(hipDeviceSynchronize());
   }
-  if (rc == JD_OK && bf16 && !fp8) {  // FP8 contexts work from their FP8 copies in every regime
+  // FP8 contexts work from their FP8 copies in every regime; INT8 codes cost three instructions per two
+  // weights to convert, which the MFMA-bound large-row kernels cannot hide, so those run on an exact bf16 copy
+  if (rc == JD_OK && bf16 && !fp8 && !(int8 && maxR <= 64)) {
     uint8_t* wp = nullptr;
     rc = dev_alloc(c, &wp, c->geo.packed_bytes());
     c->Wp = wp;
-    JD_HIP_RC(launch_pack_w(d_W_lm, cfg->w_layout, fp8 ? 1 : 0, c->geo, c->Wp, nullptr));
+    JD_HIP_RC(launch_pack_w(d_W_lm, cfg->w_layout, int8 ? kWInt8 : kWBf16, c->geo, c->Wp, nullptr));
     JD_HIP_RC(hipDeviceSynchronize());
   }
   if (rc == JD_OK && fp8 && maxR > 64) {  // FP8 fragments for the 352-row kernel
@@ -289,8 +292,8 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
   const Geometry& g = c->geo;
   const int R = B * (M + 1);
   const float invT = 1.0f / cfg.temperature;
-  const bool fp8 = cfg.w_dtype == JD_FP8_E4M3;
-  const bool bf16 = cfg.w_dtype == JD_BF16 || fp8;
+  const bool fp8 = cfg.w_dtype == JD_FP8_E4M3, int8 = cfg.w_dtype == JD_INT8;
+  const bool bf16 = cfg.w_dtype == JD_BF16 || fp8 || int8;
   const bool logits = cfg.draft_kind == JD_DRAFT_LOGITS;
 
   hipEvent_t* ev = nullptr;
@@ -322,14 +325,14 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
   // step 1: LM head (+ first softmax pass)
   if (bf16) {
     if (R <= 64) {
-      JD_HIP(launch_lmhead_skinny(fp8 ? c->Wp8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart,
-                                  side, st));
+      JD_HIP(launch_lmhead_skinny(fp8 || int8 ? c->Wp8 : c->Wp, fp8 ? kWFp8 : int8 ? kWInt8 : kWBf16, c->wscale, d_emb, R,
+                                  g, invT, c->L, c->tpart, side, st));
     } else if (gemm_prefers_352(R)) {
-      JD_HIP(launch_lmhead_gemm_dma(fp8 ? c->Wg8 : c->Wp, fp8 ? 1 : 0, fp8 ? c->wscale : nullptr, d_emb, R, g, invT,
-                                    c->L, c->tpart, c->Xp, st));
+      JD_HIP(launch_lmhead_gemm_dma(fp8 ? c->Wg8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart,
+                                    c->Xp, st));
     } else {
-      JD_HIP(launch_lmhead_gemm(fp8 ? c->Wp8 : c->Wp, fp8 ? 1 : 0, fp8 ? c->wscale : nullptr, d_emb, R, g, invT, c->L,
-                                c->tpart, c->Xp, st));
+      JD_HIP(launch_lmhead_gemm(fp8 ? c->Wp8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart, c->Xp,
+                                st));
     }
   } else {
     JD_HIP(launch_lmhead_f32(static_cast<const float*>(c->W), cfg.w_layout, static_cast<const float*>(d_emb), R,

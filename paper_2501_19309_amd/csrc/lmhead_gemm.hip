@@ -21,7 +21,7 @@
 // partial per (row, 64-entry vocabulary group).
 #include <type_traits>
 
-#include "fp8_frag.hpp"
+#include "w8_frag.hpp"
 #include "jd_kernels.hpp"
 
 namespace jd {

@@ -31,7 +31,7 @@
 //     registers), so stage k is re-filled for step k+4.
 #include <type_traits>
 
-#include "fp8_frag.hpp"
+#include "w8_frag.hpp"
 #include "jd_kernels.hpp"
 
 namespace jd {

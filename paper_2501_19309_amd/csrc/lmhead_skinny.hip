@@ -18,6 +18,7 @@
 //    row per sequence later) and reduced on the fly to one (max, sum exp) partial per
 //    (row, vocabulary group) - the first pass of the vocabulary softmax.
 #include "jd_kernels.hpp"
+#include "w8_frag.hpp"
 #include "side_work.hpp"
 
 namespace jd {
@@ -33,18 +34,8 @@ constexpr int kPF = JD_PF;  // K steps per weight prefetch group
 // ------------------------------------------------------------------------------- pack
 
 // One thread writes one 16-byte element of Wp (8 consecutive hidden indices of one row).
-// Eight FP8 E4M3 codes (two dwords, ascending hidden index) to eight bf16 values.  The hardware
-// converts two codes to two floats at a time; an E4M3 value has 3 mantissa bits, so the upper
-// half of its float is exactly its bf16.
-__device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
-  typedef float f32x2 __attribute__((ext_vector_type(2)));
-  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)lo, true);
-  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)hi, false), e = __builtin_amdgcn_cvt_pk_f32_fp8((int)hi, true);
-  auto pack = [](float x, float y) { return (__float_as_uint(x) >> 16) | (__float_as_uint(y) & 0xffff0000u); };
-  return make_uint4(pack(a[0], a[1]), pack(b[0], b[1]), pack(c[0], c[1]), pack(e[0], e[1]));
-}
-
-__global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int layout, int src_fp8, int V,
+// src_code: kWBf16 = W holds bf16 values; kWFp8 / kWInt8 = W holds one-byte codes, converted exactly.
+__global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int layout, int src_code, int V,
                                                       int d, int KS, int nVGalloc, size_t total,
                                                       uint4* __restrict__ Wp) {
   size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -58,13 +49,13 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
   int k0 = ks * kKStep + (lane >> 4) * 8;
   union { uint4 q; uint16_t h[8]; } o;
   o.q = make_uint4(0u, 0u, 0u, 0u);
-  if (v < V && src_fp8) {
+  if (v < V && src_code != kWBf16) {
     const uint8_t* W8 = reinterpret_cast<const uint8_t*>(W);
     union { uint32_t w[2]; uint8_t b[8]; } c8;
     c8.w[0] = c8.w[1] = 0u;
     for (int e = 0; e < 8; ++e)
       if (k0 + e < d) c8.b[e] = (layout == 0) ? W8[(size_t)v * d + k0 + e] : W8[(size_t)(k0 + e) * V + v];
-    o.q = fp8x8_to_bf16x8(c8.w[0], c8.w[1]);
+    o.q = src_code == kWFp8 ? w8x8_to_bf16x8<kWFp8>(c8.w[0], c8.w[1]) : w8x8_to_bf16x8<kWInt8>(c8.w[0], c8.w[1]);
   } else if (v < V) {
     if (layout == 0) {
       if (k0 + 8 <= d && (d & 7) == 0) {
@@ -81,13 +72,13 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
   Wp[idx] = o.q;
 }
 
-hipError_t launch_pack_w(const void* W, int layout, int src_fp8, const Geometry& g, void* Wp, hipStream_t st) {
+hipError_t launch_pack_w(const void* W, int layout, int src_code, const Geometry& g, void* Wp, hipStream_t st) {
   const int KS = g.dpad / kKStep;
   const size_t total = (size_t)g.nVGalloc * KS * 256;
   const size_t blocks = (total + 255) / 256;
   if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(W), layout, src_fp8, g.V, g.d, KS, g.nVGalloc, total,
+                     static_cast<const uint16_t*>(W), layout, src_code, g.V, g.d, KS, g.nVGalloc, total,
                      static_cast<uint4*>(Wp));
   return hipGetLastError();
 }
@@ -131,10 +122,10 @@ hipError_t launch_pack_w8(const void* W8, int layout, const Geometry& g, void* W
 // and for the operand reads (consecutive lanes, consecutive rows, same column).
 __device__ __forceinline__ int xs_index(int row, int c) { return row * (kKChunk / 8) + (c ^ (row & 15)); }
 
-// W8 = false: Wp holds bf16 fragments.  W8 = true: Wp holds FP8 E4M3 fragments (Wp8 layout), which
+// WK = kWBf16: Wp holds bf16 fragments.  WK = kWFp8 / kWInt8: Wp holds one-byte codes (Wp8 layout), which
 // are converted to bf16 in registers right before the MFMAs, and the logits are multiplied by the
 // per-vocabulary-entry scale in the epilogue.  Everything else is shared.
-template <int NXB, int NWAVES, bool W8>
+template <int NXB, int NWAVES, int WK>
 __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint16_t* __restrict__ X, int R, int d,
     int nChunks, int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld,
@@ -146,6 +137,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   static_assert(ITEMS % T == 0, "staging must divide evenly");
   // K steps per weight prefetch group: 2 for bf16 (8 KiB per wavefront in flight); 4 for FP8, whose
   // fragments are half the size, so that the same 8 KiB stay in flight
+  constexpr bool W8 = WK != kWBf16;
   constexpr int PFS = W8 ? 2 * kPF : kPF;
   constexpr int GROUPS = kStepsPerChunk / PFS;
   static_assert(GROUPS % 2 == 0, "prefetch parity must be static");
@@ -247,7 +239,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
           bf16x8 afrag;
           if constexpr (W8) {
             const uint4 w = wbuf[gi & 1][s / 2][sub];
-            afrag = __builtin_bit_cast(bf16x8, (s & 1) == 0 ? fp8x8_to_bf16x8(w.x, w.y) : fp8x8_to_bf16x8(w.z, w.w));
+            afrag = __builtin_bit_cast(bf16x8, (s & 1) == 0 ? w8x8_to_bf16x8<WK>(w.x, w.y) : w8x8_to_bf16x8<WK>(w.z, w.w));
           } else {
             afrag = __builtin_bit_cast(bf16x8, wbuf[gi & 1][s][sub]);
           }
@@ -310,32 +302,37 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   }
 }
 
-template <int NXB, int NWAVES, bool W8>
+template <int NXB, int NWAVES, int WK>
 static hipError_t launch_skinny_t(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
                                   float invT, float* L, float2* part, const SideWork& side, hipStream_t st) {
   const int nLm = (g.nVG + NWAVES - 1) / NWAVES;  // nLm*NWAVES <= nVGalloc since NWAVES divides kGroupAlloc
   const int grid = nLm + side.nStatBlocks + side.nJudgeBlocks;
-  hipLaunchKernelGGL((lmhead_skinny_kernel<NXB, NWAVES, W8>), dim3(grid), dim3(NWAVES * 64), 0, st,
+  hipLaunchKernelGGL((lmhead_skinny_kernel<NXB, NWAVES, WK>), dim3(grid), dim3(NWAVES * 64), 0, st,
                      static_cast<const uint4*>(Wp), vscale, static_cast<const uint16_t*>(X), R, g.d,
                      g.dpad / kKChunk, g.V, g.nVG, g.nVGalloc, invT, L, g.Vpad, part, nLm, side);
   return hipGetLastError();
 }
 
-hipError_t launch_lmhead_skinny(const void* Wp, int w_fp8, const float* vscale, const void* X, int R,
+template <int WK>
+static hipError_t launch_skinny_rows(const void* Wp, const float* vscale, const void* X, int R, const Geometry& g,
+                                     float invT, float* L, float2* part, const SideWork& side, hipStream_t st) {
+  if (R <= 16) return launch_skinny_t<1, 4, WK>(Wp, vscale, X, R, g, invT, L, part, side, st);
+  if (R <= 32) return launch_skinny_t<2, 4, WK>(Wp, vscale, X, R, g, invT, L, part, side, st);
+  if (R <= 48) return launch_skinny_t<3, 4, WK>(Wp, vscale, X, R, g, invT, L, part, side, st);
+  return launch_skinny_t<4, 4, WK>(Wp, vscale, X, R, g, invT, L, part, side, st);
+}
+
+hipError_t launch_lmhead_skinny(const void* Wp, int w_code, const float* vscale, const void* X, int R,
                                 const Geometry& g, float invT, float* L, float2* part, const SideWork& side,
                                 hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "grid covers only allocated groups");
   if (R <= 0 || R > 64) return hipErrorInvalidValue;
-  if (w_fp8) {
-    if (R <= 16) return launch_skinny_t<1, 4, true>(Wp, vscale, X, R, g, invT, L, part, side, st);
-    if (R <= 32) return launch_skinny_t<2, 4, true>(Wp, vscale, X, R, g, invT, L, part, side, st);
-    if (R <= 48) return launch_skinny_t<3, 4, true>(Wp, vscale, X, R, g, invT, L, part, side, st);
-    return launch_skinny_t<4, 4, true>(Wp, vscale, X, R, g, invT, L, part, side, st);
+  switch (w_code) {
+    case kWBf16: return launch_skinny_rows<kWBf16>(Wp, nullptr, X, R, g, invT, L, part, side, st);
+    case kWFp8: return launch_skinny_rows<kWFp8>(Wp, vscale, X, R, g, invT, L, part, side, st);
+    case kWInt8: return launch_skinny_rows<kWInt8>(Wp, vscale, X, R, g, invT, L, part, side, st);
+    default: return hipErrorInvalidValue;
   }
-  if (R <= 16) return launch_skinny_t<1, 4, false>(Wp, nullptr, X, R, g, invT, L, part, side, st);
-  if (R <= 32) return launch_skinny_t<2, 4, false>(Wp, nullptr, X, R, g, invT, L, part, side, st);
-  if (R <= 48) return launch_skinny_t<3, 4, false>(Wp, nullptr, X, R, g, invT, L, part, side, st);
-  return launch_skinny_t<4, 4, false>(Wp, nullptr, X, R, g, invT, L, part, side, st);
 }
 
 // ------------------------------------------------------------------------------- fp32

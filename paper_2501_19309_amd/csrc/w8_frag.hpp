@@ -1,8 +1,10 @@
-// FP8 E4M3 codes -> bf16 MFMA fragments in registers (device code shared by the large-row LM-head kernels).
+// 8-bit weight codes (FP8 E4M3, INT8) -> bf16 MFMA fragments in registers (device code shared by the LM-head kernels).
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "jd_kernels.hpp"
 
 namespace jd {
 
@@ -29,6 +31,28 @@ __device__ __forceinline__ uint32_t fp8_frag_dword(uint32_t lo, uint32_t hi, int
 
 __device__ __forceinline__ void set_dword(uint4& v, int j, uint32_t x) {
   if (j == 0) v.x = x; else if (j == 1) v.y = x; else if (j == 2) v.z = x; else v.w = x;
+}
+
+// Eight codes (two dwords, ascending hidden index) to eight bf16 values, left to the compiler's scheduler
+// (the small-row kernel is bound by HBM, not by issue slots).  FP8: one instruction per two codes.
+// INT8 (two's complement): sign-extending byte -> float conversions; an integer of magnitude <= 128 has at
+// most 8 significant bits, so the upper half of its float is exactly its bf16 and a byte permute packs two.
+template <int WK>
+__device__ __forceinline__ uint4 w8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+  if constexpr (WK == kWFp8) {
+    auto cv = [](uint32_t w, bool high) {
+      return __builtin_bit_cast(uint32_t, high ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true)
+                                               : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false));
+    };
+    return make_uint4(cv(lo, false), cv(lo, true), cv(hi, false), cv(hi, true));
+  } else {
+    static_assert(WK == kWInt8, "8-bit code");
+    auto pair = [](uint32_t w, int i) {
+      const float a = (float)(int)(int8_t)(w >> (8 * i)), b = (float)(int)(int8_t)(w >> (8 * i + 8));
+      return __builtin_amdgcn_perm(__float_as_uint(b), __float_as_uint(a), 0x07060302u);  // b.hi16 : a.hi16
+    };
+    return make_uint4(pair(lo, 0), pair(lo, 2), pair(hi, 0), pair(hi, 2));
+  }
 }
 
 }  // namespace jd

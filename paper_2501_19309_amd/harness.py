@@ -13,7 +13,7 @@ from . import binding as jb
 
 
 def to_device(inputs: Dict[str, np.ndarray], device: int = 0):
-    """numpy -> torch device tensors; uint16 arrays are bf16 bit patterns, uint8 arrays FP8 codes."""
+    """numpy -> torch device tensors; uint16 arrays are bf16 bit patterns, uint8 arrays FP8 codes, int8 arrays INT8 weights."""
     import torch
 
     dev = torch.device("cuda", device)
@@ -38,7 +38,7 @@ def make_verifier(dev_inputs, *, max_B: Optional[int] = None, max_M: Optional[in
     emb, W = dev_inputs.get("emb", dev_inputs.get("hidden")), dev_inputs["W"]
     B, Mp1, d = emb.shape
     V = W.shape[0] if w_layout == jb.JD_W_VD else W.shape[1]
-    dt = {torch.bfloat16: jb.JD_BF16, torch.uint8: jb.JD_FP8_E4M3}.get(W.dtype, jb.JD_F32)
+    dt = {torch.bfloat16: jb.JD_BF16, torch.uint8: jb.JD_FP8_E4M3, torch.int8: jb.JD_INT8}.get(W.dtype, jb.JD_F32)
     cfg = jb.make_config(d, V, max_B or B, max_M or (Mp1 - 1), w_dtype=dt, w_layout=w_layout, device=device,
                          **cfg_kw)
     return jb.JDVerify(cfg, W, dev_inputs["w_judge"], dev_inputs.get("w_scale"))

@@ -48,6 +48,7 @@ class VerifyShape:
     V: int
     dtype: str  # "f32" | "bf16": storage type of embeddings, W_lm and w_judge;
                 # "fp8": bf16 embeddings and w_judge, W_lm as FP8 E4M3 codes + one fp32 scale per row
+                # "int8": the same with W_lm as two's-complement 8-bit integers
     noise: Union[float, Tuple[float, float]]  # std of draft-logit noise, or U(lo, hi) per sequence
     note: str = ""
 
@@ -67,6 +68,10 @@ CONFIGS: Dict[str, VerifyShape] = {
     "C3q": VerifyShape("C3q", 1, 25, 8192, 128256, "fp8", 1.0, "Llama-3.1-70B-shaped head, FP8 W_lm"),
     "C4q": VerifyShape("C4q", 1, 25, 16384, 128256, "fp8", 2.0, "Llama-3.1-405B-shaped head, FP8 W_lm"),
     "C5q": VerifyShape("C5q", 64, 10, 8192, 128256, "fp8", (0.5, 2.5), "batched verification, FP8 W_lm"),
+    # the same with 8-bit integer weights and one scale per output channel (weight-only quantisation)
+    "C2i": VerifyShape("C2i", 1, 5, 4096, 128256, "int8", 1.5, "Llama-3.1-8B-shaped head, INT8 W_lm"),
+    "C3i": VerifyShape("C3i", 1, 25, 8192, 128256, "int8", 1.0, "Llama-3.1-70B-shaped head, INT8 W_lm"),
+    "C4i": VerifyShape("C4i", 1, 25, 16384, 128256, "int8", 2.0, "Llama-3.1-405B-shaped head, INT8 W_lm"),
 }
 
 
@@ -110,6 +115,20 @@ def fp8_e4m3_quantize_rows(w: np.ndarray):
     return codes, scale, deq.astype(np.float32)
 
 
+def int8_quantize_rows(w: np.ndarray):
+    """Per-row symmetric weight-only quantisation of float32 rows to 8-bit integers (one scale per
+    output channel, the usual recipe of 8-bit weight-only inference).
+
+    scale[v] = max|w[v,:]| / 127 (float32); code = round-half-even(w / scale) in [-127, 127].
+    Returns (codes int8 [rows, d], scale float32 [rows], dequantised float32 [rows, d]).
+    """
+    amax = np.max(np.abs(w), axis=1).astype(np.float32)
+    scale = np.where(amax > 0, amax / np.float32(127.0), np.float32(1.0)).astype(np.float32)
+    q = np.clip(np.rint(w / scale[:, None]), -127, 127)
+    codes = q.astype(np.int8)
+    return codes, scale, (q.astype(np.float32) * scale[:, None]).astype(np.float32)
+
+
 def _stream(seed: int, tag: int, chunk: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64((tag << 40) | chunk)]))
 
@@ -140,7 +159,8 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False,
     Returns a dict with
       emb           [B, M+1, d]  float32, or uint16 bf16 bit patterns
       W             [V, d]       same storage type; row v is vocabulary entry v (K contiguous);
-                                 for dtype "fp8": uint8 FP8 E4M3 codes, plus  w_scale [V] float32
+                                 for dtype "fp8": uint8 FP8 E4M3 codes, plus  w_scale [V] float32;
+                                 for dtype "int8": int8 weights, plus  w_scale [V] float32
       w_judge       [d]          same storage type
       draft_logits  [B, M+1, V]  float32 (row M is present but unused by verification)
       draft_tokens  [B, M]       int32, token j drawn from softmax(draft_logits[:, j])
@@ -148,9 +168,10 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False,
     """
     B, M, d, V = shape.B, shape.M, shape.d, shape.V
     R = B * (M + 1)
-    is_fp8 = shape.dtype == "fp8"
-    is_bf16 = shape.dtype == "bf16" or is_fp8   # storage of embeddings and w_judge
-    if shape.dtype not in ("f32", "bf16", "fp8"):
+    is_fp8, is_int8 = shape.dtype == "fp8", shape.dtype == "int8"
+    is_w8 = is_fp8 or is_int8
+    is_bf16 = shape.dtype == "bf16" or is_w8   # storage of embeddings and w_judge
+    if shape.dtype not in ("f32", "bf16", "fp8", "int8"):
         raise ValueError(f"unknown dtype {shape.dtype!r}")
 
     # embeddings: N(0,1), each row rescaled to unit rms, then stored
@@ -186,7 +207,7 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False,
         sigma_b = np.full(B, shape.noise, dtype=np.float32)
     sigma_r = np.repeat(sigma_b, M + 1)[:, None]  # [R, 1]
 
-    W_store = np.empty((V, d), dtype=np.uint8 if is_fp8 else (np.uint16 if is_bf16 else np.float32))
+    W_store = np.empty((V, d), dtype=np.uint8 if is_fp8 else np.int8 if is_int8 else (np.uint16 if is_bf16 else np.float32))
     W_scale = np.ones(V, dtype=np.float32)
     D = np.empty((R, V), dtype=np.float32)
     best_val = np.full(R, -np.inf, dtype=np.float32)
@@ -200,8 +221,8 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False,
         w *= inv_sqrt_d
         noise = _stream(seed, _TAG_NOISE, ci).standard_normal((R, rows), dtype=np.float32)
         gumbel = _stream(seed, _TAG_GUMBEL, ci).gumbel(size=(R, rows)).astype(np.float32)
-        if is_fp8:
-            codes, scale, deq = fp8_e4m3_quantize_rows(w)
+        if is_w8:
+            codes, scale, deq = fp8_e4m3_quantize_rows(w) if is_fp8 else int8_quantize_rows(w)
             return ci, codes, noise, gumbel, scale, deq
         w_bits = bf16_bits_from_f32(w) if is_bf16 else None
         return ci, (w_bits if is_bf16 else w), noise, gumbel, None, None
@@ -226,7 +247,7 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False,
             v0 = ci * _VOCAB_CHUNK
             rows = w_chunk.shape[0]
             W_store[v0:v0 + rows] = w_chunk
-            if is_fp8:
+            if is_w8:
                 W_scale[v0:v0 + rows] = scale
                 w32 = deq
             else:
@@ -260,6 +281,6 @@ def make_inputs(shape: VerifyShape, seed: int = 0, prenorm: bool = False,
         out["rms_eps"] = RMS_EPS
     else:
         out["emb"] = emb_store.reshape(B, M + 1, d)
-    if is_fp8:
+    if is_w8:
         out["w_scale"] = W_scale
     return out

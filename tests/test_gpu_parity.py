@@ -280,6 +280,57 @@ def test_fp8_decode_of_every_code(jd):
     assert (got["status"].astype(np.int64) & 2).all()
 
 
+INT8 = [
+    VerifyShape("i_1blk", 1, 5, 256, 1024, "int8", 1.0),
+    VerifyShape("i_2blk", 1, 25, 512, 2048, "int8", 1.0),
+    VerifyShape("i_ragged", 2, 9, 272, 1000, "int8", 2.0),           # d % 256 != 0, V % 64 != 0
+    VerifyShape("i_3blk", 4, 10, 768, 3000, "int8", 1.5),            # R = 44
+    VerifyShape("i_4blk", 4, 15, 768, 3000, "int8", 1.5),            # R = 64
+    VerifyShape("i_gemm", 9, 10, 512, 5000, "int8", (0.5, 2.5)),     # R = 99: large-row regime on the bf16 copy
+    VerifyShape("i_gemm352", 20, 10, 288, 2100, "int8", (0.5, 2.5)), # R = 220: 352-row tiling on the bf16 copy
+    VerifyShape("i_d16", 2, 3, 16, 200, "int8", 1.0),                # smallest hidden size of the 8-bit path
+]
+
+
+@pytest.mark.parametrize("shape", INT8, ids=lambda s: s.name)
+def test_int8_weights_match_oracle(jd, shape):
+    print(f"[case] {shape.name}", flush=True)
+    for seed in (0, 1):
+        x = make_inputs(shape, seed)
+        rep = compare(jd.run_once(x, want_probs=True), oracle_for(x, return_probs=True))
+        print(rep, flush=True)
+    if shape.name in ("i_ragged", "i_gemm"):   # the [d, V] storage order of the same weights gives the same call
+        from paper_2501_19309_amd import binding as jb
+        xt = dict(x); xt["W"] = np.ascontiguousarray(x["W"].T)
+        a = jd.run_once(x); b = jd.run_once(xt, w_layout=jb.JD_W_DV)
+        for k in ("accept_len", "next_token", "z_stand", "z_judge", "p_at_draft", "judge_logit"):
+            assert np.array_equal(a[k], b[k]), k
+
+
+def test_int8_decode_of_every_code(jd):
+    # logits[v] = scale[v] * code v: one bit pattern per vocabulary entry, a one-hot embedding, compared as
+    # logit differences for all 256 patterns in the small-row kernel (codes converted in registers) and in
+    # the large-row regime (bf16 copy)
+    V, d = 256, 32
+    W = np.zeros((V, d), dtype=np.int8); W[:, 5] = np.arange(V, dtype=np.uint8).view(np.int8)
+    from synth import bf16_bits_from_f32
+    for R_rows, M in ((2, 1), (70, 9)):
+        B = R_rows // (M + 1)
+        emb = np.zeros((B, M + 1, d), dtype=np.float32); emb[:, :, 5] = 1.0
+        rng = np.random.default_rng(0)
+        x = {"emb": bf16_bits_from_f32(emb).reshape(emb.shape), "W": W,
+             "w_scale": np.full(V, 1.0 / 32, dtype=np.float32) * (1 + np.arange(V, dtype=np.float32) / 1024),
+             "w_judge": bf16_bits_from_f32(np.ones(d, dtype=np.float32)),
+             "draft_tokens": rng.integers(0, V, size=(B, M)).astype(np.int32),
+             "draft_logits": rng.normal(size=(B, M + 1, V)).astype(np.float32),
+             "uniforms": rng.random((B, M + 1)).astype(np.float32)}
+        ref = oracle_for(x, return_probs=True)
+        got = jd.run_once(x, want_probs=True)
+        compare(got, ref)
+        want = np.log(ref["probs"][0, 0]); have = np.log(got["probs"][0, 0].astype(np.float64))
+        assert np.abs((have - have[1]) - (want - want[1])).max() < 1e-5
+
+
 def test_separate_judge_embedding(jd):
     shape = VerifyShape("t", 3, 6, 256, 900, "bf16", 1.0)
     x = make_inputs(shape, 7)

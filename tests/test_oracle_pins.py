@@ -608,6 +608,44 @@ def test_fp8_weights_are_scaled_rows():
     assert {"C2q", "C3q", "C4q"} <= set(CONFIGS)
 
 
+# ----------------------------------------------------------------------------- INT8 weights
+
+def test_int8_decode_is_twos_complement():
+    # every bit pattern, decoded by the definition of two's complement: value = b - 256 * [b >= 128]
+    pat = np.arange(256, dtype=np.uint8)
+    got = vo.widen(pat.view(np.int8))
+    assert got.dtype == np.float64
+    assert [got[b] for b in (0x00, 0x01, 0x7F, 0x80, 0x81, 0xFF)] == [0.0, 1.0, 127.0, -128.0, -127.0, -1.0]
+    assert np.array_equal(got, np.array([b - 256 * (b >= 128) for b in range(256)], dtype=np.float64))
+    # every integer in [-128, 127] is exactly a bf16 value (what the kernel converts to)
+    assert np.array_equal(got.astype(np.float32).view(np.uint32) & 0xFFFF, np.zeros(256, dtype=np.uint32))
+    # same byte, other reading: the FP8 table must not be used for int8 arrays
+    assert vo.widen(np.array([0x38], dtype=np.uint8))[0] == 1.0 and vo.widen(np.array([0x38], dtype=np.int8))[0] == 56.0
+
+
+def test_int8_weights_are_scaled_rows():
+    from synth import CONFIGS
+    shape = VerifyShape("t", 2, 4, 64, 300, "int8", 1.0)
+    x = make_inputs(shape, 1)
+    assert x["W"].dtype == np.int8 and x["w_scale"].shape == (300,) and x["emb"].dtype == np.uint16
+    # logits by hand for a few entries: integer weights, one scale per vocabulary entry
+    X = vo.widen(x["emb"]).reshape(-1, 64)
+    got = vo.target_logits(x["emb"].reshape(-1, 64), x["W"], temperature=2.0, w_scale=x["w_scale"])
+    for r, v in ((0, 0), (3, 17), (9, 299)):
+        want = sum(float(X[r, k]) * int(x["W"][v, k]) for k in range(64)) * float(x["w_scale"][v]) / 2.0
+        assert abs(got[r, v] - want) <= 1e-12 * max(1.0, abs(want))
+    # the [d, V] layout is the transpose
+    got_t = vo.target_logits(x["emb"].reshape(-1, 64), np.ascontiguousarray(x["W"].T), temperature=2.0, w_layout="dv",
+                             w_scale=x["w_scale"])
+    assert np.array_equal(got, got_t)
+    # the generator's quantisation: symmetric, full range used in every row, error at most half a step
+    assert (np.abs(x["W"].astype(np.int32)).max(axis=1) == 127).all()
+    out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+                    w_scale=x["w_scale"])
+    assert (out["status"] == 0).all()
+    assert {"C2i", "C3i", "C4i"} <= set(CONFIGS)
+
+
 # ----------------------------------------------------------------------------- pre-norm wiring (final RMS norm)
 
 def test_round_to_bf16_hand_cases():
