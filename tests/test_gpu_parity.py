@@ -228,6 +228,34 @@ def test_topk_rule_and_target_resampling(jd):
                 assert (ref["accept_margin"] == 0).any() and not ref["z_stand"].all()   # decided by token id
 
 
+def _random_shapes(n, seed):
+    """Seeded shapes drawn over the dispatch boundaries: row counts on both sides of 64, 176, 352 and 704,
+    hidden sizes with and without a ragged last K chunk, vocabularies with a ragged last group."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    row_targets = [3, 17, 40, 63, 64, 65, 100, 175, 176, 177, 260, 351, 352, 353, 500, 529, 703, 704, 705, 900]
+    for i in range(n):
+        dtype = ("bf16", "fp8", "int8", "bf16", "f32")[i % 5]
+        M = int(rng.integers(1, 21))
+        B = max(1, int(row_targets[i % len(row_targets)] // (M + 1)))
+        step = {"bf16": 8, "fp8": 16, "int8": 16, "f32": 1}[dtype]
+        d = int(rng.integers(1, 48)) * step if dtype != "f32" else int(rng.integers(5, 90))
+        V = int(rng.integers(65, 2600)) if dtype != "f32" else int(rng.integers(9, 700))
+        if dtype == "f32":
+            B = min(B, 12)
+        noise = float(rng.uniform(0.5, 2.5))
+        shapes.append(VerifyShape(f"r{i}_{dtype}_B{B}_M{M}_d{d}_V{V}", B, M, d, V, dtype, noise))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _random_shapes(40, 20250119), ids=lambda s: s.name)
+def test_random_shapes_match_oracle(jd, shape):
+    print(f"[case] {shape.name} R={shape.R}", flush=True)
+    x = make_inputs(shape, 11)
+    rep = compare(jd.run_once(x, want_probs=True), oracle_for(x, return_probs=True))
+    print(rep, flush=True)
+
+
 FP8 = [
     VerifyShape("q_1blk", 1, 5, 256, 1024, "fp8", 1.0),
     VerifyShape("q_2blk", 1, 25, 512, 2048, "fp8", 1.0),
