@@ -24,8 +24,11 @@
  * W_lm and w_judge for the lifetime of the context, everything else for the call.
  * Tensors are dense, row-major, last index contiguous.  Work is enqueued on the
  * caller's HIP stream and NOT synchronised; outputs are valid once the stream has
- * reached the end of the call.  A context is not thread-safe; distinct contexts are
- * independent.  No function throws; every function returns 0 (JD_OK) or a negative
+ * reached the end of the call.  jd_verify_create makes config.device the calling
+ * thread's current device; for every later call on the context the calling thread's
+ * current device must be that device and the stream must belong to it (the library does
+ * not switch devices on the caller's behalf).  A context is not thread-safe; distinct
+ * contexts are independent.  No function throws; every function returns 0 (JD_OK) or a negative
  * JD_ERR_* code, and jd_verify_strerror() names it.
  */
 #ifndef JD_VERIFY_H
