@@ -8,10 +8,11 @@ namespace jd {
 
 // ------------------------------------------------------------------------------- row stats
 
-// grid = (nRows, nSplit).  Each block reduces one contiguous column range of one row.
+// grid = nRows * nSplit, the column ranges of a row adjacent: workgroups that run at the same time stream
+// neighbouring memory.  Each block reduces one contiguous column range of one row.
 __global__ __launch_bounds__(256) void rowstats_kernel(RowStatsArgs a) {
   __shared__ MS red[4];
-  rowstats_block(a, blockIdx.x, blockIdx.y, red);
+  rowstats_block(a, blockIdx.x / a.nSplit, blockIdx.x % a.nSplit, red);
 }
 
 RowStatsArgs make_rowstats_args(const float* base, int rowsUsed, size_t seqStride, size_t rowStride, int V,
@@ -27,7 +28,7 @@ RowStatsArgs make_rowstats_args(const float* base, int rowsUsed, size_t seqStrid
 hipError_t launch_rowstats(const float* base, int nRows, int rowsUsed, size_t seqStride, size_t rowStride, int V,
                            int nSplit, float2* part, hipStream_t st) {
   const RowStatsArgs a = make_rowstats_args(base, rowsUsed, seqStride, rowStride, V, nSplit, part);
-  hipLaunchKernelGGL(rowstats_kernel, dim3(nRows, nSplit), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(rowstats_kernel, dim3((unsigned)nRows * (unsigned)nSplit), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
