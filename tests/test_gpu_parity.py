@@ -57,6 +57,8 @@ EDGE = [
     VerifyShape("e_R352_d8", 44, 7, 8, 300, "bf16", 1.0),        # 352-row tiling at the smallest hidden size (one real K step)
     VerifyShape("e_R300_V9", 30, 9, 40, 9, "bf16", 1.0),         # 352-row tiling with one partial vocabulary group
     VerifyShape("e_V1", 2, 2, 8, 1, "f32", 1.0),                 # single token vocabulary: everything is certain
+    VerifyShape("e_R2816", 256, 10, 256, 3000, "bf16", (0.5, 2.0)),  # eight 352-row tiles: several rounds of workgroups per unit
+    VerifyShape("e_R2640_fp8", 240, 10, 272, 1500, "fp8", (0.5, 2.0)),  # fifteen 176-row tiles, FP8 codes, ragged d
 ]
 
 
