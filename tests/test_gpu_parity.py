@@ -164,6 +164,30 @@ def test_standard_mode_and_delta_one(jd):
         compare(got, oracle_for(x, delta=delta, judge_bias=bias, temperature=T))
 
 
+def test_extreme_temperatures_and_logit_scales(jd):
+    # Sharp and flat target distributions, and logits of magnitude ~1e3 (embeddings scaled up): the softmax
+    # works around the row maximum, so nothing overflows and nothing underflows to a zero row sum.  Near-ties
+    # are excluded by the comparison as everywhere; the point is that every other decision stays identical.
+    for shape in (VerifyShape("x_skinny", 3, 7, 256, 2000, "bf16", 1.0), VerifyShape("x_gemm", 12, 10, 256, 2000, "bf16", 1.5),
+                  VerifyShape("x_fp8", 2, 9, 256, 1200, "fp8", 1.0), VerifyShape("x_f32", 2, 4, 64, 300, "f32", 1.0)):
+        x = make_inputs(shape, 4)
+        for T in (0.02, 0.3, 25.0):
+            rep = compare(jd.run_once(x, temperature=T, want_probs=True), oracle_for(x, temperature=T, return_probs=True))
+            print(f"[case] {shape.name} T={T}", rep, flush=True)
+        # embeddings 64 times larger (exact in bf16 and fp32: a power of two): logits in the hundreds
+        xs = dict(x)
+        if x["emb"].dtype == np.uint16:
+            f = (x["emb"].astype(np.uint32) << np.uint32(16)).view(np.float32) * np.float32(64.0)
+            xs["emb"] = bf16_bits_from_f32(f).reshape(x["emb"].shape)
+        else:
+            xs["emb"] = x["emb"] * np.float32(64.0)
+        ref = oracle_for(xs, return_probs=True)
+        got = jd.run_once(xs, want_probs=True)
+        print(f"[case] {shape.name} x64", compare(got, ref), flush=True)
+        assert np.isfinite(got["probs"]).all() and (got["status"] == 0).all()
+        assert np.abs(got["probs"].astype(np.float64).sum(-1) - 1.0).max() < 1e-3
+
+
 def test_probs_draft_and_dv_layout(jd):
     from paper_2501_19309_amd import binding as jb
     for kind in ("bf16", "f32"):

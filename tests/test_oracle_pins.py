@@ -838,3 +838,46 @@ def test_draft_logit_shift_and_truncated_drafts():
     assert np.array_equal(outt["accept_len"], np.minimum(out["accept_len"], Mp))
     early = out["accept_len"] < Mp
     assert early.any() and np.array_equal(outt["next_token"][early], out["next_token"][early])
+
+
+# ----------------------------------------------------------------------------- the comparison itself
+
+def test_comparison_accepts_the_oracle_and_catches_planted_mistakes():
+    from oracle.compare import compare
+    shape = VerifyShape("t", 4, 6, 64, 300, "bf16", 1.0)
+    x = make_inputs(shape, 2)
+    ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"], return_probs=True)
+
+    def as_library(r):   # the output types of the library
+        o = {k: np.array(v) for k, v in r.items()}
+        for k in ("p_at_draft", "q_at_draft", "judge_logit", "row_max", "row_sumexp", "probs"):
+            o[k] = o[k].astype(np.float32)
+        return o
+
+    compare(as_library(ref), ref)
+
+    def planted(mutate):
+        g = as_library(ref)
+        mutate(g)
+        with pytest.raises(AssertionError):
+            compare(g, ref)
+
+    b = int(np.argmax(ref["accept_len"] < 6))                          # a sequence with a rejection
+    planted(lambda g: g["accept_len"].__setitem__(b, g["accept_len"][b] + 1))
+    planted(lambda g: g["next_token"].__setitem__(0, (g["next_token"][0] + 7) % 300))
+    planted(lambda g: g["p_at_draft"].__setitem__((0, 0), g["p_at_draft"][0, 0] * 1.01))
+    planted(lambda g: g["q_at_draft"].__setitem__((1, 2), g["q_at_draft"][1, 2] * 0.99))
+    planted(lambda g: g["judge_logit"].__setitem__((2, 1), g["judge_logit"][2, 1] + 0.01))
+    planted(lambda g: g["status"].__setitem__(3, 2))
+    planted(lambda g: g["probs"].__setitem__((0, 0, 5), g["probs"][0, 0, 5] * 1.01))
+    j = int(ref["accept_len"][b])                                       # flip the rejecting slot's standard bit
+    if ref["accept_margin"][b, j] >= 1e-5 and not ref["z_judge"][b, j]:
+        planted(lambda g: g["z_stand"].__setitem__((b, j), 1))
+    # values below float32's normal range: the library may return anything that small, nothing larger
+    tiny = {k: np.array(v) for k, v in ref.items()}
+    tiny["p_at_draft"] = tiny["p_at_draft"].copy(); tiny["p_at_draft"][0, 0] = 1e-60
+    g = as_library(tiny); assert g["p_at_draft"][0, 0] == 0.0
+    compare(g, tiny)
+    g["p_at_draft"][0, 0] = 1e-30
+    with pytest.raises(AssertionError):
+        compare(g, tiny)
