@@ -22,6 +22,25 @@ HIPCC_FLAGS = [
 ]
 
 
+CABI_CHECK_SRC = os.path.join(os.path.dirname(HERE), "tests", "cabi_check.cpp")
+CABI_CHECK_PATH = os.path.join(HERE, "jd_cabi_check")
+
+
+def build_cabi_check(verbose: bool = False) -> str:
+    """The stand-alone C++ caller of the C ABI that the GPU tests run (tests/cabi_check.cpp): host code only,
+    linked against libjdverify.so next to it."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall", CABI_CHECK_SRC, "-L" + HERE, "-ljdverify",
+           "-Wl,-rpath,$ORIGIN", "-o", CABI_CHECK_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + res.stderr)
+        raise RuntimeError("hipcc failed building jd_cabi_check")
+    return CABI_CHECK_PATH
+
+
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     srcs = [os.path.join(CSRC, s) for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
@@ -39,3 +58,4 @@ def build_library(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_cabi_check(verbose=True))

@@ -596,6 +596,85 @@ def test_batch_order_and_truncated_drafts_on_gpu(jd, shape):
     assert np.array_equal(gott["accept_len"][firm], np.minimum(got["accept_len"], Mp)[firm])
 
 
+def test_outputs_stay_inside_their_buffers(jd):
+    # Every output tensor sits between two guard zones filled with a sentinel; the context is sized for a
+    # larger batch than the call.  The call must write exactly its B x M (+1) elements and nothing beyond.
+    import torch
+    from paper_2501_19309_amd import binding as jb, harness
+    G = 96
+    for shape, big in ((VerifyShape("g_skinny", 3, 7, 256, 1111, "bf16", 1.0), (5, 9)),
+                       (VerifyShape("g_gemm", 30, 10, 264, 1111, "bf16", 1.5), (40, 12)),
+                       (VerifyShape("g_fp8", 20, 9, 272, 900, "fp8", 1.0), (33, 10)),
+                       (VerifyShape("g_f32", 2, 4, 64, 300, "f32", 1.0), (3, 6))):
+        x = make_inputs(shape, 9)
+        B, M, V = shape.B, shape.M, shape.V
+        dev = harness.to_device(x)
+        ver = harness.make_verifier(dev, max_B=big[0], max_M=big[1])
+        try:
+            plain = ver.alloc_outputs(B, M, True)
+            ver.run(dev["emb"], dev["draft_tokens"], dev["draft_logits"], dev["uniforms"], plain)
+            guarded, backing = {}, {}
+            for name, t in plain.__dict__.items():
+                sentinel = 0x5A if t.dtype == torch.uint8 else (-123456789 if t.dtype == torch.int32 else -7.25)
+                buf = torch.full((t.numel() + 2 * G,), sentinel, dtype=t.dtype, device=t.device)
+                backing[name] = (buf, sentinel)
+                guarded[name] = buf[G:G + t.numel()].view(t.shape)
+                assert guarded[name].is_contiguous()
+            out = jb.VerifyOutputs(**guarded)
+            ver.run(dev["emb"], dev["draft_tokens"], dev["draft_logits"], dev["uniforms"], out)
+            torch.cuda.synchronize()
+            for name, (buf, sentinel) in backing.items():
+                assert bool((buf[:G] == sentinel).all()) and bool((buf[-G:] == sentinel).all()), (shape.name, name)
+                assert torch.equal(guarded[name], getattr(plain, name)), (shape.name, name)
+        finally:
+            ver.destroy()
+
+
+CABI = [
+    (VerifyShape("c_skinny", 2, 7, 512, 4000, "bf16", 1.0), False),
+    (VerifyShape("c_gemm176", 9, 10, 264, 5000, "bf16", (0.5, 2.5)), True),
+    (VerifyShape("c_gemm352", 32, 10, 512, 2100, "bf16", (0.5, 2.0)), False),
+    (VerifyShape("c_fp8", 3, 9, 272, 3000, "fp8", 1.0), True),
+    (VerifyShape("c_int8", 20, 10, 256, 1500, "int8", 1.5), False),
+    (VerifyShape("c_f32", 2, 4, 64, 515, "f32", 1.0), False),
+]
+
+
+@pytest.mark.parametrize("shape,prenorm", CABI, ids=lambda v: v.name if isinstance(v, VerifyShape) else str(v))
+def test_c_abi_from_plain_cpp_matches_oracle(shape, prenorm, tmp_path):
+    # The library called from a C++ program of its own process (tests/cabi_check.cpp, built by build()): no Python
+    # and no torch in that process.  Tensors travel as raw files; the outputs meet the same parity bar.
+    import subprocess
+    from paper_2501_19309_amd import binding as jb
+    from paper_2501_19309_amd.build import CABI_CHECK_PATH
+    import os
+    assert os.path.exists(CABI_CHECK_PATH), "jd_cabi_check is not built: run __graft_entry__.build()"
+    x = make_inputs(shape, 5, prenorm=prenorm)
+    for name in ("emb", "hidden", "gamma", "W", "w_judge", "w_scale", "draft_logits", "draft_tokens", "uniforms"):
+        if name in x:
+            np.ascontiguousarray(x[name]).tofile(tmp_path / f"{name}.bin")
+    wdt = {"f32": jb.JD_F32, "bf16": jb.JD_BF16, "fp8": jb.JD_FP8_E4M3, "int8": jb.JD_INT8}[shape.dtype]
+    cmd = [CABI_CHECK_PATH, str(tmp_path), str(shape.B), str(shape.M), str(shape.d), str(shape.V), str(wdt), str(int(prenorm))]
+    print("[case]", " ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True, timeout=100)
+    print(res.stdout, res.stderr, flush=True)
+    assert res.returncode == 0, res.stdout + res.stderr
+    B, M = shape.B, shape.M
+    kinds = {"accept_len": (np.int32, (B,)), "next_token": (np.int32, (B,)), "status": (np.uint32, (B,)),
+             "z_stand": (np.uint8, (B, M)), "z_judge": (np.uint8, (B, M)), "p_at_draft": (np.float32, (B, M)),
+             "q_at_draft": (np.float32, (B, M)), "judge_logit": (np.float32, (B, M)),
+             "row_max": (np.float32, (B, M + 1)), "row_sumexp": (np.float32, (B, M + 1))}
+    got = {k: np.fromfile(tmp_path / f"{k}.bin", dtype=dt).reshape(sh) for k, (dt, sh) in kinds.items()}
+    kw = {"w_scale": x["w_scale"]} if "w_scale" in x else {}
+    if prenorm:
+        emb, _ = vo.rmsnorm_rows(x["hidden"], x["gamma"], x["rms_eps"])
+        kw["emb_judge"] = x["hidden"]
+    else:
+        emb = x["emb"]
+    ref = vo.verify(emb, x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"], **kw)
+    print(compare(got, ref), flush=True)
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
