@@ -48,6 +48,8 @@ def main() -> int:
                          "C2i..C4i: with INT8 W_lm")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-device-probe", action="store_true",
+                    help="skip the measurement of the device's own MFMA / HBM-read rate after the timed region")
     ap.add_argument("--rule", default="sampling", choices=["sampling", "topk"],
                     help="acceptance rule: Eq. 4 speculative sampling, or top-K verification (Sec. 5 baseline)")
     ap.add_argument("--top-k", type=int, default=1)
@@ -145,6 +147,20 @@ def main() -> int:
         achieved = (w_bytes + x_bytes) / (lm_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)}
+    if not args.no_device_probe:
+        # what this device itself sustains, measured right after the timed region (outside it): a loop of
+        # nothing but independent bf16 MFMAs on N(0,1)-like operands, resp. a pure streaming read of 4 GiB.
+        # `frac` stays achieved / published peak; `frac_of_probe` is achieved / what the probe reached.
+        torch.cuda.synchronize()
+        if roofline["bound"] == "mfma":
+            probe = jb.probe_mfma_bf16(0, 1)
+            roofline["device_probe"] = {"what": "independent v_mfma_f32_16x16x32_bf16 only, N(0,1)-like operands",
+                                        "achieved": probe, "unit": "TFLOP/s", "frac_of_peak": probe / MFMA_BF16_PEAK_TFLOPS}
+        else:
+            probe = jb.probe_hbm_read(0, 4 << 30)
+            roofline["device_probe"] = {"what": "pure streaming read of a 4 GiB buffer, 128-bit loads",
+                                        "achieved": probe, "unit": "GB/s", "frac_of_peak": probe / HBM_PEAK_GBS}
+        roofline["frac_of_probe"] = achieved / probe
     roofline["kernel"] = "lmhead"
     roofline["kernel_ms"] = lm_ms
     roofline["algorithmic_bytes"] = w_bytes + x_bytes

@@ -233,6 +233,23 @@ int jd_verify_workspace_bytes(const jd_verify_ctx* ctx, uint64_t* out_bytes);
  * the device.  Lets callers (and CPU-only tests) probe argument errors without a GPU. */
 int jd_verify_validate_config(const jd_verify_config* cfg);
 
+/*
+ * Two measurements of the device itself, for reading roofline fractions (the bound the north-star
+ * targets are stated against: HBM for the B = 1 shapes, the matrix cores for the batched one).  Not
+ * part of verification.  Both make `device` current, allocate and free their own buffers, run on the
+ * default stream and synchronise; out_* are host pointers.
+ *   jd_verify_probe_mfma_bf16: TFLOP/s that a loop of nothing but independent
+ *       v_mfma_f32_16x16x32_bf16 sustains on all compute units (no memory traffic), i.e. what
+ *       the matrix cores deliver under the board's power limit.  operand_mode 0: all-zero
+ *       operands; 1: values spread like N(0,1), as embeddings and weights are.
+ *   jd_verify_probe_hbm_read: GB/s of a pure streaming read (128-bit loads, grid stride) of a
+ *       zero-filled buffer of `bytes` bytes, 1 MiB <= bytes <= 64 GiB (use >= 2 GiB: smaller buffers
+ *       measure the last-level cache).
+ * Errors: INVALID_ARG (NULL pointer, mode, size), OOM, HIP.
+ */
+int jd_verify_probe_mfma_bf16(int32_t device, int32_t operand_mode, double* out_tflops);
+int jd_verify_probe_hbm_read(int32_t device, uint64_t bytes, double* out_gbs);
+
 #ifdef __cplusplus
 }
 #endif

@@ -32,7 +32,7 @@ EXPORTED_SYMBOLS = (
     "jd_verify_create", "jd_verify_create_scaled", "jd_verify_run", "jd_verify_run_prenorm", "jd_verify_append_tokens",
     "jd_verify_destroy", "jd_verify_strerror", "jd_verify_last_error_detail",
     "jd_verify_profile_begin", "jd_verify_profile_end", "jd_verify_workspace_bytes",
-    "jd_verify_validate_config",
+    "jd_verify_validate_config", "jd_verify_probe_mfma_bf16", "jd_verify_probe_hbm_read",
 )
 
 
@@ -107,6 +107,10 @@ def load_library() -> ctypes.CDLL:
     lib.jd_verify_workspace_bytes.restype = ctypes.c_int
     lib.jd_verify_validate_config.argtypes = [ctypes.POINTER(jd_verify_config)]
     lib.jd_verify_validate_config.restype = ctypes.c_int
+    lib.jd_verify_probe_mfma_bf16.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double)]
+    lib.jd_verify_probe_mfma_bf16.restype = ctypes.c_int
+    lib.jd_verify_probe_hbm_read.argtypes = [i32, ctypes.c_uint64, ctypes.POINTER(ctypes.c_double)]
+    lib.jd_verify_probe_hbm_read.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -128,6 +132,24 @@ def make_config(d, V, max_B, max_M, *, w_dtype=JD_BF16, emb_dtype=None, w_layout
 
 def jd_verify_validate_config(cfg: jd_verify_config) -> int:
     return load_library().jd_verify_validate_config(ctypes.byref(cfg))
+
+
+def probe_mfma_bf16(device: int = 0, operand_mode: int = 1) -> float:
+    """jd_verify_probe_mfma_bf16: TFLOP/s of a loop of nothing but independent bf16 MFMAs on this device."""
+    v = ctypes.c_double()
+    rc = load_library().jd_verify_probe_mfma_bf16(device, operand_mode, ctypes.byref(v))
+    if rc != JD_OK:
+        raise JDError(rc, "jd_verify_probe_mfma_bf16")
+    return float(v.value)
+
+
+def probe_hbm_read(device: int = 0, nbytes: int = 4 << 30) -> float:
+    """jd_verify_probe_hbm_read: GB/s of a pure streaming read of an nbytes buffer on this device."""
+    v = ctypes.c_double()
+    rc = load_library().jd_verify_probe_hbm_read(device, nbytes, ctypes.byref(v))
+    if rc != JD_OK:
+        raise JDError(rc, "jd_verify_probe_hbm_read")
+    return float(v.value)
 
 
 def append_tokens(draft_tokens, accept_len, next_token, token_buf, lengths, stream=None) -> None:

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libjdverify.so")
 
-SOURCES = ["jd_verify_api.hip", "lmhead_skinny.hip", "lmhead_gemm.hip", "lmhead_gemm_dma.hip", "verify_tail.hip"]
+SOURCES = ["jd_verify_api.hip", "lmhead_skinny.hip", "lmhead_gemm.hip", "lmhead_gemm_dma.hip", "verify_tail.hip", "device_probes.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1,0 +1,139 @@
+// Two measurements of the device itself, for reading the library's roofline fractions: what a loop of
+// nothing but independent bf16 MFMAs sustains (the matrix cores under the board's power limit), and what a
+// pure streaming read of a large buffer sustains (HBM).  Diagnostics behind the C ABI; the verification
+// path does not use them.
+#include "../../include/jd_verify.h"
+
+#include <cstdint>
+#include <cstdio>
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kProbeTiles = 32;  // independent accumulator tiles per wavefront: no MFMA waits for another
+
+// Two workgroups of four wavefronts per compute unit: the loop has no memory traffic, so however the
+// dispatcher places them, every SIMD's matrix pipeline has MFMAs waiting.
+// operand_mode 0: all-zero operands; 1: values spread like N(0,1) rounded to bf16, different per lane and
+// element (what embeddings and weights look like to the matrix cores).
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float* out, int iters, int operand_mode) {
+  f32x4 acc[kProbeTiles];
+#pragma unroll
+  for (int i = 0; i < kProbeTiles; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  auto value = [&](unsigned i) -> unsigned {  // bf16 bits of a sum of two uniforms, scaled to unit variance
+    unsigned h = (threadIdx.x * 8u + i + blockIdx.x * 4099u) * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    const float f = (((h & 0xffff) + ((h >> 16) & 0xffff)) * (1.0f / 65536.0f) - 1.0f) * 2.45f;
+    return __float_as_uint(f) >> 16;
+  };
+  auto pair = [&](unsigned i) { return operand_mode == 0 ? 0u : (value(2 * i) | (value(2 * i + 1) << 16)); };
+  const uint4 a4 = make_uint4(pair(0), pair(1), pair(2), pair(3));
+  const uint4 b4 = make_uint4(pair(4), pair(5), pair(6), pair(7));
+  const bf16x8 a = __builtin_bit_cast(bf16x8, a4), b = __builtin_bit_cast(bf16x8, b4);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < kProbeTiles; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kProbeTiles; ++i) s += (acc[i][0] + acc[i][1]) + (acc[i][2] + acc[i][3]);
+  if (s == 12345.678f) out[blockIdx.x * 256 + threadIdx.x] = s;  // keeps the loop alive; practically never taken
+}
+
+// Streaming read: a wavefront reads 8 KiB of consecutive memory per turn (eight 128-bit loads per lane in
+// flight), the wavefronts of the grid read consecutive 8 KiB pieces, and the grid moves through the buffer
+// as one window - the access pattern of the LM-head weight stream.
+__global__ __launch_bounds__(256) void hbm_read_kernel(const uint4* __restrict__ src, size_t n_items, uint4* out) {
+  const size_t lane = threadIdx.x & 63;
+  const size_t n_chunks = n_items / 512;                             // 512 items = 8 KiB
+  const size_t n_waves = (size_t)gridDim.x * 4;
+  uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+  for (size_t c = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6); c < n_chunks; c += n_waves) {
+    const uint4* p = src + c * 512 + lane;
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[u * 64];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) out[blockIdx.x * 256 + threadIdx.x] = acc;  // buffer is zero: never
+}
+
+int fail(hipError_t e) { (void)hipGetLastError(); return e == hipErrorOutOfMemory ? JD_ERR_OOM : JD_ERR_HIP; }
+
+}  // namespace
+
+#define JD_TRY(expr) do { const hipError_t e_ = (expr); if (e_ != hipSuccess) { rc = fail(e_); goto done; } } while (0)
+
+extern "C" int jd_verify_probe_mfma_bf16(int32_t device, int32_t operand_mode, double* out_tflops) {
+  if (!out_tflops || device < 0 || (operand_mode != 0 && operand_mode != 1)) return JD_ERR_INVALID_ARG;
+  *out_tflops = 0.0;
+  int rc = JD_OK;
+  float* out = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipDeviceProp_t prop;
+  int wgs = 0;
+  const int iters = 4000;
+  float ms = 0.f;
+  JD_TRY(hipSetDevice(device));
+  JD_TRY(hipGetDeviceProperties(&prop, device));
+  wgs = 2 * prop.multiProcessorCount;  // 4 wavefronts each: two per SIMD, wherever the dispatcher puts them
+  JD_TRY(hipMalloc(reinterpret_cast<void**>(&out), (size_t)wgs * 256 * sizeof(float)));
+  JD_TRY(hipEventCreate(&e0));
+  JD_TRY(hipEventCreate(&e1));
+  // some launches first: the clock settles only after tens of milliseconds under this load
+  for (int w = 0; w < 10; ++w) hipLaunchKernelGGL(mfma_rate_kernel, dim3(wgs), dim3(256), 0, nullptr, out, iters, operand_mode);
+  JD_TRY(hipGetLastError());
+  JD_TRY(hipEventRecord(e0, nullptr));
+  for (int w = 0; w < 3; ++w) hipLaunchKernelGGL(mfma_rate_kernel, dim3(wgs), dim3(256), 0, nullptr, out, iters, operand_mode);
+  JD_TRY(hipGetLastError());
+  JD_TRY(hipEventRecord(e1, nullptr));
+  JD_TRY(hipEventSynchronize(e1));
+  JD_TRY(hipEventElapsedTime(&ms, e0, e1));
+  *out_tflops = 3.0 * (double)wgs * 4 * iters * kProbeTiles * (2.0 * 16 * 16 * 32) / ((double)ms * 1e-3) / 1e12;
+done:
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (out) (void)hipFree(out);
+  return rc;
+}
+
+extern "C" int jd_verify_probe_hbm_read(int32_t device, uint64_t bytes, double* out_gbs) {
+  if (!out_gbs || device < 0 || bytes < (1ull << 20) || bytes > (64ull << 30)) return JD_ERR_INVALID_ARG;
+  *out_gbs = 0.0;
+  int rc = JD_OK;
+  uint4* buf = nullptr;
+  uint4* out = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipDeviceProp_t prop;
+  int wgs = 0;
+  float ms = 0.f;
+  const size_t n_items = bytes / sizeof(uint4);
+  JD_TRY(hipSetDevice(device));
+  JD_TRY(hipGetDeviceProperties(&prop, device));
+  wgs = prop.multiProcessorCount * 8;
+  JD_TRY(hipMalloc(reinterpret_cast<void**>(&buf), n_items * sizeof(uint4)));
+  JD_TRY(hipMalloc(reinterpret_cast<void**>(&out), (size_t)wgs * 256 * sizeof(uint4)));
+  JD_TRY(hipMemset(buf, 0, n_items * sizeof(uint4)));
+  JD_TRY(hipEventCreate(&e0));
+  JD_TRY(hipEventCreate(&e1));
+  hipLaunchKernelGGL(hbm_read_kernel, dim3(wgs), dim3(256), 0, nullptr, buf, n_items, out);
+  JD_TRY(hipGetLastError());
+  JD_TRY(hipEventRecord(e0, nullptr));
+  for (int w = 0; w < 3; ++w) hipLaunchKernelGGL(hbm_read_kernel, dim3(wgs), dim3(256), 0, nullptr, buf, n_items, out);
+  JD_TRY(hipGetLastError());
+  JD_TRY(hipEventRecord(e1, nullptr));
+  JD_TRY(hipEventSynchronize(e1));
+  JD_TRY(hipEventElapsedTime(&ms, e0, e1));
+  *out_gbs = 3.0 * (double)((n_items / 512) * 512 * sizeof(uint4)) / ((double)ms * 1e-3) / 1e9;
+done:
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (buf) (void)hipFree(buf);
+  if (out) (void)hipFree(out);
+  return rc;
+}

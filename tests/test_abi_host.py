@@ -20,7 +20,7 @@ def lib():
 
 def test_header_symbols_are_exported(lib, repo_root):
     hdr = open(os.path.join(repo_root, "include", "jd_verify.h")).read()
-    declared = set(re.findall(r"\b(jd_verify_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(jd_verify_[a-z0-9_]+)\s*\(", hdr))
     assert {"jd_verify_create", "jd_verify_run", "jd_verify_destroy"} <= declared
     assert declared == set(jb.EXPORTED_SYMBOLS)
     for name in declared:

@@ -675,6 +675,22 @@ def test_c_abi_from_plain_cpp_matches_oracle(shape, prenorm, tmp_path):
     print(compare(got, ref), flush=True)
 
 
+def test_device_probes(jd):
+    # diagnostics behind the C ABI: plausible numbers, argument errors
+    import ctypes
+    from paper_2501_19309_amd import binding as jb
+    lib = jb.load_library()
+    tf = jb.probe_mfma_bf16(0, 1)
+    gbs = jb.probe_hbm_read(0, 2 << 30)
+    print(f"[probe] mfma bf16 {tf:.0f} TFLOP/s, hbm read {gbs:.0f} GB/s", flush=True)
+    assert 300.0 < tf <= 2600.0 and 1000.0 < gbs <= 8200.0      # below the published peaks, far above a broken loop
+    v = ctypes.c_double()
+    assert lib.jd_verify_probe_mfma_bf16(0, 7, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_verify_probe_mfma_bf16(0, 1, None) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_verify_probe_hbm_read(0, 1000, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_verify_probe_hbm_read(-1, 1 << 30, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
