@@ -44,21 +44,43 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(float* out, int iters, i
   if (s == 12345.678f) out[blockIdx.x * 256 + threadIdx.x] = s;  // keeps the loop alive; practically never taken
 }
 
-// Streaming read: a wavefront reads 8 KiB of consecutive memory per turn (eight 128-bit loads per lane in
-// flight), the wavefronts of the grid read consecutive 8 KiB pieces, and the grid moves through the buffer
-// as one window - the access pattern of the LM-head weight stream.
+// Streaming read: a wavefront reads 32 KiB of consecutive memory per turn as four batches of eight 128-bit
+// loads per lane, two batches in flight while a third is folded (straight-line code inside a turn, so the
+// compiler's wait counts are exact); the wavefronts of the grid read consecutive pieces and the grid moves
+// through the buffer as one window - the access pattern of the LM-head weight stream.
 __global__ __launch_bounds__(256) void hbm_read_kernel(const uint4* __restrict__ src, size_t n_items, uint4* out) {
   const size_t lane = threadIdx.x & 63;
-  const size_t n_chunks = n_items / 512;                             // 512 items = 8 KiB
+  const size_t n_chunks = n_items / 2048;                            // 2048 items = 32 KiB
   const size_t n_waves = (size_t)gridDim.x * 4;
   uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-  for (size_t c = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6); c < n_chunks; c += n_waves) {
-    const uint4* p = src + c * 512 + lane;
-    uint4 v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = p[u * 64];
+  auto fold = [&](const uint4 (&v)[8]) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+  };
+  for (size_t c = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6); c < n_chunks; c += n_waves) {
+    const uint4* p = src + c * 2048 + lane;
+    uint4 a[8], b[8], x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a[u] = p[u * 64];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) b[u] = p[512 + u * 64];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[u] = a[u];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a[u] = p[1024 + u * 64];
+    __builtin_amdgcn_sched_barrier(0);
+    fold(x);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[u] = b[u];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) b[u] = p[1536 + u * 64];
+    __builtin_amdgcn_sched_barrier(0);
+    fold(x);
+    fold(a);
+    fold(b);
   }
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) out[blockIdx.x * 256 + threadIdx.x] = acc;  // buffer is zero: never
 }
@@ -129,7 +151,7 @@ extern "C" int jd_verify_probe_hbm_read(int32_t device, uint64_t bytes, double* 
   JD_TRY(hipEventRecord(e1, nullptr));
   JD_TRY(hipEventSynchronize(e1));
   JD_TRY(hipEventElapsedTime(&ms, e0, e1));
-  *out_gbs = 3.0 * (double)((n_items / 512) * 512 * sizeof(uint4)) / ((double)ms * 1e-3) / 1e9;
+  *out_gbs = 3.0 * (double)((n_items / 2048) * 2048 * sizeof(uint4)) / ((double)ms * 1e-3) / 1e9;
 done:
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
