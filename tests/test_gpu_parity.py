@@ -691,6 +691,35 @@ def test_device_probes(jd):
     assert lib.jd_verify_probe_hbm_read(-1, 1 << 30, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
 
 
+def test_bench_json_contract(repo_root):
+    # bench.py prints ONE JSON line with the keys the harness reads; the smallest workload keeps this quick
+    import json, subprocess, sys, os
+    res = subprocess.run([sys.executable, os.path.join(repo_root, "bench.py"), "--config", "C1", "--steps", "5", "--warmup", "2"],
+                         capture_output=True, text=True, timeout=110, cwd=repo_root)
+    assert res.returncode == 0, res.stderr[-2000:]
+    lines = [l for l in res.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1, lines
+    r = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert k in r, k
+    assert r["n_gpus"] == 1 and r["steps"] == 5 and r["warmup"] == 2 and r["higher_is_better"] is True
+    assert r["vs_baseline"] is None and r["data"] == "synthetic" and "workload" in r["config"]
+    assert r["value"] > 0 and abs(r["value"] - 5 / (r["ms_per_step"] * 1e-3)) < 1e-6 * r["value"]   # B*M = 5 positions per call
+    rf = r["roofline"]
+    for k in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
+        assert k in rf, k
+    assert rf["bound"] in ("hbm", "mfma", "alu") and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-9
+    cb = r["cpu_baseline"]
+    for k in ("value", "unit", "cores", "kind", "sample"):
+        assert k in cb, k
+    assert cb["kind"] == "oracle" and cb["value"] > 0 and r["parity"]["ok"] is True
+    # more than one GPU is refused with a message
+    res2 = subprocess.run([sys.executable, os.path.join(repo_root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                          timeout=60, cwd=repo_root)
+    assert res2.returncode != 0 and "one GPU" in (res2.stdout + res2.stderr)
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
