@@ -720,6 +720,37 @@ def test_bench_json_contract(repo_root):
     assert res2.returncode != 0 and "one GPU" in (res2.stdout + res2.stderr)
 
 
+def test_create_destroy_returns_all_device_memory(jd):
+    # every buffer a context allocates (re-tiled weights, logits, pooled row arrays, profiling events) goes back
+    import torch
+    from paper_2501_19309_amd import harness
+    shapes = (VerifyShape("l_bf16", 40, 10, 512, 6000, "bf16", 1.0), VerifyShape("l_fp8", 40, 10, 512, 6000, "fp8", 1.0),
+              VerifyShape("l_int8", 40, 10, 512, 6000, "int8", 1.0), VerifyShape("l_f32", 2, 4, 64, 515, "f32", 1.0))
+    devs = [harness.to_device(make_inputs(sh, 1)) for sh in shapes]
+    def one_round(it):
+        for sh, dev in zip(shapes, devs):
+            ver = harness.make_verifier(dev, rule=(1 if it % 2 else 0), top_k=3)
+            out = ver.alloc_outputs(sh.B, sh.M)
+            ver.profile_begin(2)
+            ver.run(dev["emb"], dev["draft_tokens"], dev["draft_logits"], dev["uniforms"], out)
+            torch.cuda.synchronize()
+            ver.profile_end()
+            ver.destroy()
+            del out
+
+    for it in range(2):      # first use loads the kernels' code and lets the runtime and torch set up their pools
+        one_round(it)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free0, _ = torch.cuda.mem_get_info()
+    for it in range(12):
+        one_round(it)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < (4 << 20), (free0, free1)   # nothing of the contexts' ~100 MB per round is left behind
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
