@@ -130,6 +130,19 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_events = (time.perf_counter() - t0) * 1e3 / K
     kernel_ms, n_prof = ver.profile_end()
+
+    # spread of single calls: an event pair around each of (up to 200) further calls on the same stream
+    n_spread = min(K, 200)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_spread)]
+    torch.cuda.synchronize()
+    for a_ev, b_ev in ev:
+        a_ev.record()
+        step()
+        b_ev.record()
+    torch.cuda.synchronize()
+    call_ms = sorted(a_ev.elapsed_time(b_ev) for a_ev, b_ev in ev)
+    pct = lambda q: call_ms[min(len(call_ms) - 1, int(q * len(call_ms)))]
+    call_spread = {"n": n_spread, "min": call_ms[0], "p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "max": call_ms[-1]}
     log(f"[bench] ms/step {ms_per_step:.4f} (with per-kernel events {ms_events:.4f}); kernels {kernel_ms}")
 
     got = out.to_numpy()
@@ -188,7 +201,7 @@ def main() -> int:
         "whole_call": {"ms_per_step_with_kernel_events": ms_events, "algorithmic_bytes": call_bytes,
                        "gbs": call_bytes / (ms_per_step * 1e-3) / 1e9,
                        "frac_hbm_peak": call_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                       "kernel_ms": kernel_ms},
+                       "kernel_ms": kernel_ms, "single_call_ms": call_spread},
     }
 
     if not args.no_cpu_baseline:
