@@ -126,8 +126,9 @@ typedef struct {                /* device pointers; the first three are required
  * [max_B*(max_M+1), V], reduction partials) and, for bf16 weights, builds a private
  * copy of W_lm re-tiled into MFMA operand order (one extra W_lm-sized allocation,
  * one-time cost).  d_W_lm and d_w_judge must stay valid and unchanged until destroy.
- * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_DTYPE (checked before any HIP call), OOM, HIP.
- * On error *out_ctx is set to NULL.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_DTYPE (checked before any HIP call), OOM, HIP (also when
+ * cfg->device is not a gfx950 device: the library holds code for that architecture only).
+ * On error *out_ctx is set to NULL; jd_verify_last_error_detail() says which runtime call failed.
  */
 int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void* d_w_judge,
                      jd_verify_ctx** out_ctx);

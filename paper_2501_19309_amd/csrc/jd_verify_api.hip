@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <new>
 #include <vector>
 
@@ -16,7 +17,6 @@ using namespace jd;
 struct jd_verify_ctx {
   jd_verify_config cfg;
   Geometry geo;
-  int num_cus;
   const void* W;
   const void* wj;
   void* Wp;             // re-tiled bf16 weights (bf16 weights; INT8 weights only for the large-row regime)
@@ -138,6 +138,11 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
   JD_HIP(hipSetDevice(cfg->device));
   hipDeviceProp_t prop;
   JD_HIP(hipGetDeviceProperties(&prop, cfg->device));
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {   // the library holds gfx950 code only
+    std::snprintf(g_detail, sizeof g_detail, "device %d is %s; this library is built for gfx950 (MI355X) only",
+                  cfg->device, prop.gcnArchName);
+    return JD_ERR_HIP;
+  }
   // The launchers report hipGetLastError(); a stale code left in this thread by an earlier, unrelated
   // runtime call of the caller (an event query that was "not ready", say) must not be taken for theirs.
   (void)hipGetLastError();
@@ -146,7 +151,6 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
   if (!c) return JD_ERR_OOM;
   c->cfg = *cfg;
   c->geo = make_geometry(cfg->d, cfg->V);
-  c->num_cus = prop.multiProcessorCount;
   c->W = d_W_lm; c->wj = d_w_judge; c->wscale = d_w_scale;
   c->judge_threshold = (cfg->delta >= 1.0f) ? INFINITY : std::log(cfg->delta / (1.0f - cfg->delta));
   c->prof_on = false; c->prof_max = c->prof_n = 0;
