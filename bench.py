@@ -29,9 +29,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
 # what the same counter reads for a plain 1 GiB copy (profiles/lmhead_skinny_C4_hbm_traffic.md,
-# profiles/lmhead_gemm_C5_counters.md, profiles/verify_call_C4q_fp8_kernel_stats_and_traffic.md);
+# profiles/lmhead_gemm_C5_counters.md, profiles/verify_call_C4q_fp8_kernel_stats_and_traffic.md,
+# profiles/verify_call_C4q_C4i_C5q_8bit_kernel_stats.md);
 # None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 4.2533e9, "C4q": 2.1496e9, "C5": 2.855e9}  # fetched + written
+MEASURED_TRAFFIC_BYTES = {"C4": 4.2533e9, "C4q": 2.1496e9, "C4i": 2.1499e9, "C5": 2.855e9, "C5q": 1.8058e9}  # fetched + written
 
 
 def log(*a):
