@@ -751,6 +751,30 @@ def test_create_destroy_returns_all_device_memory(jd):
     assert free0 - free1 < (4 << 20), (free0, free1)   # nothing of the contexts' ~100 MB per round is left behind
 
 
+def test_draft_tensor_without_the_bonus_row(jd):
+    # the draft model has no distribution for the bonus position: a draft tensor of M rows per sequence
+    # (draft_rows = M) gives the same call as one with an ignored trailing row, logits and probabilities alike
+    from paper_2501_19309_amd import binding as jb
+    for shape in (VerifyShape("dr_skinny", 3, 6, 256, 1500, "bf16", 1.0), VerifyShape("dr_gemm", 12, 10, 256, 1500, "bf16", 1.5),
+                  VerifyShape("dr_fp8", 2, 9, 256, 1200, "fp8", 1.0), VerifyShape("dr_f32", 2, 4, 64, 300, "f32", 1.0)):
+        x = make_inputs(shape, 8)
+        M = shape.M
+        xm = dict(x); xm["draft_logits"] = np.ascontiguousarray(x["draft_logits"][:, :M])
+        assert xm["draft_logits"].shape[1] == M
+        full = jd.run_once(x, want_probs=True)
+        cut = jd.run_once(xm, want_probs=True)
+        for k in full:
+            assert np.array_equal(full[k], cut[k]), (shape.name, k)
+        compare(cut, oracle_for(xm, return_probs=True))
+        D = x["draft_logits"].astype(np.float64)
+        Q = np.exp(D - D.max(-1, keepdims=True)); Q /= Q.sum(-1, keepdims=True)
+        xq = dict(x); xq["draft_probs"] = np.ascontiguousarray(Q[:, :M].astype(np.float32))
+        kw = {"w_scale": x["w_scale"]} if "w_scale" in x else {}
+        ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], xq["draft_probs"], x["uniforms"],
+                        draft_kind=vo.DRAFT_PROBS, **kw)
+        compare(jd.run_once(xq, draft_kind=jb.JD_DRAFT_PROBS), ref)
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
