@@ -775,6 +775,27 @@ def test_draft_tensor_without_the_bonus_row(jd):
         compare(jd.run_once(xq, draft_kind=jb.JD_DRAFT_PROBS), ref)
 
 
+def test_dv_weight_layout_for_every_weight_type(jd):
+    # W_lm handed over as [d][V] (the transpose of the checkpoint layout): every re-tiling kernel and the fp32
+    # LM head read it through their layout switch; same integer outputs and probabilities as [V][d]
+    from paper_2501_19309_amd import binding as jb
+    for shape in (VerifyShape("dv_fp8_skinny", 2, 9, 272, 1000, "fp8", 2.0),           # Wp8
+                  VerifyShape("dv_fp8_176", 9, 10, 272, 1000, "fp8", (0.5, 2.5)),      # Wp8 in the 176-row kernel
+                  VerifyShape("dv_fp8_352", 32, 10, 272, 1000, "fp8", (0.5, 2.5)),     # Wg8
+                  VerifyShape("dv_int8_352", 32, 10, 272, 1000, "int8", (0.5, 2.5)),   # bf16 copy from INT8
+                  VerifyShape("dv_bf16_352", 32, 10, 264, 1000, "bf16", (0.5, 2.5)),
+                  VerifyShape("dv_f32", 3, 5, 100, 515, "f32", 1.0)):
+        x = make_inputs(shape, 3)
+        xt = dict(x); xt["W"] = np.ascontiguousarray(x["W"].T)
+        a = jd.run_once(x, want_probs=True)
+        b = jd.run_once(xt, want_probs=True, w_layout=jb.JD_W_DV)
+        for k in a:
+            assert np.array_equal(a[k], b[k]), (shape.name, k)
+        ref = vo.verify(x["emb"], xt["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+                        w_layout="dv", return_probs=True, **({"w_scale": x["w_scale"]} if "w_scale" in x else {}))
+        compare(b, ref)
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
