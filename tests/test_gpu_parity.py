@@ -796,6 +796,31 @@ def test_dv_weight_layout_for_every_weight_type(jd):
         compare(b, ref)
 
 
+def test_options_in_the_large_row_regime(jd):
+    # the rule / mode / draft-kind / resampling switches on top of the 176-row and 352-row LM-head kernels
+    from paper_2501_19309_amd import binding as jb
+    for shape in (VerifyShape("o_176", 9, 10, 264, 2100, "bf16", (0.5, 2.5)), VerifyShape("o_352", 32, 10, 264, 2100, "bf16", (0.5, 2.5)),
+                  VerifyShape("o_352_fp8", 32, 10, 272, 2100, "fp8", (0.5, 2.5))):
+        x = make_inputs(shape, 21)
+        kw = {"w_scale": x["w_scale"]} if "w_scale" in x else {}
+        for K in (1, 5):
+            got = jd.run_once(x, rule=jb.JD_RULE_TOPK, top_k=K)
+            compare(got, oracle_for(x, rule=vo.RULE_TOPK, top_k=K), rule_topk=True)
+        got = jd.run_once(x, resample=jb.JD_RESAMPLE_TARGET, mode=jb.JD_MODE_STANDARD, temperature=0.8)
+        compare(got, oracle_for(x, resample=vo.RESAMPLE_TARGET, mode=vo.MODE_STANDARD, temperature=0.8), mode_judge=False)
+        got = jd.run_once(x, delta=0.7, judge_bias=0.4)
+        compare(got, oracle_for(x, delta=0.7, judge_bias=0.4))
+        D = x["draft_logits"].astype(np.float64)
+        Q = np.exp(D - D.max(-1, keepdims=True)); Q /= Q.sum(-1, keepdims=True)
+        xq = dict(x); xq["draft_probs"] = Q.astype(np.float32)
+        ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], xq["draft_probs"], x["uniforms"],
+                        draft_kind=vo.DRAFT_PROBS, **kw)
+        compare(jd.run_once(xq, draft_kind=jb.JD_DRAFT_PROBS), ref)
+        ej = make_inputs(shape, 22)["emb"]
+        xj = dict(x); xj["emb_judge"] = ej
+        compare(jd.run_once(xj), oracle_for(x, emb_judge=ej))
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
