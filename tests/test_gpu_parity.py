@@ -821,6 +821,31 @@ def test_options_in_the_large_row_regime(jd):
         compare(jd.run_once(xj), oracle_for(x, emb_judge=ej))
 
 
+def test_nan_status_in_every_lm_head_kernel(jd):
+    # a NaN in one sequence's embeddings (bf16 0x7FC0) or in one weight row must raise that sequence's
+    # (resp. every sequence's) NaN bit through the small-row, the 176-row and the 352-row LM-head kernels,
+    # and leave the clean sequences' results as the oracle has them
+    for shape in (VerifyShape("nan_skinny", 4, 9, 256, 1500, "bf16", 1.0), VerifyShape("nan_176", 9, 10, 256, 1500, "bf16", 1.0),
+                  VerifyShape("nan_352", 32, 10, 256, 1500, "bf16", 1.0), VerifyShape("nan_352_fp8", 32, 10, 256, 1500, "fp8", 1.0)):
+        x = make_inputs(shape, 17)
+        x["emb"] = x["emb"].copy()
+        x["emb"][2, 3, 100] = 0x7FC0            # row 3 of sequence 2: its LM-head row and judge slot 2 become NaN
+        ref = oracle_for(x)
+        got = jd.run_once(x)
+        st = got["status"].astype(np.int64) & 0xFFFFFFFF
+        assert st.tolist() == ref["status"].tolist(), shape.name
+        assert st[2] & 2 and not (np.delete(st, 2) & 2).any()
+        clean = [b for b in range(shape.B) if b != 2]
+        assert np.array_equal(got["accept_len"][clean], ref["accept_len"][clean])
+        assert np.array_equal(got["next_token"][clean], ref["next_token"][clean])
+        if shape.dtype == "bf16":              # a NaN weight: every row's softmax is NaN
+            y = make_inputs(shape, 17)
+            y["W"] = y["W"].copy(); y["W"][777, 5] = 0x7FC0
+            refy = oracle_for(y)
+            goty = jd.run_once(y)
+            assert (refy["status"] & 2).all() and ((goty["status"].astype(np.int64) & 2) != 0).all()
+
+
 def test_run_argument_errors(jd):
     import ctypes
     from paper_2501_19309_amd import binding as jb, harness
