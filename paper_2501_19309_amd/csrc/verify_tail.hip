@@ -183,6 +183,36 @@ struct MassRow {
   }
 };
 
+// Masses of the four consecutive tokens v0 .. v0+3 (v0 a multiple of 4; tokens >= V get 0).  When the row
+// pointers allow it the logits come as one 128-bit load per tensor instead of four 32-bit ones; the values
+// and everything computed from them are the same either way.
+__device__ __forceinline__ void mass4(const MassRow& row, int v0, int V, double (&out)[4]) {
+  const bool vec = v0 + 3 < V && ((reinterpret_cast<uintptr_t>(row.l + v0) | reinterpret_cast<uintptr_t>(row.dq + v0)) & 15) == 0;
+  if (vec) {
+    const float4 l = *reinterpret_cast<const float4*>(row.l + v0);
+    const float lv[4] = {l.x, l.y, l.z, l.w};
+    float qv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (row.use_q) {
+      const float4 q = *reinterpret_cast<const float4*>(row.dq + v0);
+      qv[0] = q.x; qv[1] = q.y; qv[2] = q.z; qv[3] = q.w;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float p = __expf(lv[i] - row.tm) * row.tinv;
+      float m = p;
+      if (row.use_q) {
+        const float q = row.q_is_logits ? __expf(qv[i] - row.qm) * row.qinv : qv[i];
+        const float r = p - q;
+        m = (r < 0.f) ? 0.f : r;  // not fmaxf: a NaN must stay visible in the sum
+      }
+      out[i] = (double)m;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = (v0 + i < V) ? (double)row(v0 + i) : 0.0;
+  }
+}
+
 __device__ __forceinline__ MassRow make_mass_row(const SamplerArgs& a, int b, bool plain) {
   const int Mp1 = a.M + 1;
   const int m = a.accept_len[b];
@@ -205,10 +235,11 @@ __device__ __forceinline__ MassRow make_mass_row(const SamplerArgs& a, int b, bo
 __device__ __forceinline__ double chunk_sum(const MassRow& row, int chunk, int V, double* red /*[256]*/) {
   const int tid = threadIdx.x;
   const int v0 = chunk * kSamplerChunk + tid * 4;
+  double m[4];
+  mass4(row, v0, V, m);
   double s = 0.0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-    if (v0 + i < V) s += (double)row(v0 + i);
+  for (int i = 0; i < 4; ++i) s += m[i];
   red[tid] = s;
   __syncthreads();
   for (int o = 128; o > 0; o >>= 1) {
@@ -345,12 +376,10 @@ __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
   const int chunk = found;
   const int v0 = chunk * kSamplerChunk + tid * 4;
   double mv[4];
+  mass4(row, v0, a.V, mv);
   double local = 0.0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    mv[i] = (v0 + i < a.V) ? (double)row(v0 + i) : 0.0;
-    local += mv[i];
-  }
+  for (int i = 0; i < 4; ++i) local += mv[i];
   red[tid] = local;
   __syncthreads();
   for (int o = 1; o < 256; o <<= 1) {  // inclusive scan over threads
