@@ -434,8 +434,30 @@ __global__ __launch_bounds__(256) void rank_kernel(const float* __restrict__ L, 
   if (c >= 0 && c < V) {
     const float* row = L + (size_t)(b * (M + 1) + j) * Lld;
     const float lc = row[c];
+    // splitLen is a multiple of 4 and rows of L are 256-byte aligned: 128-bit loads, four per thread in
+    // flight before anything is compared (the count is an integer: the order does not matter)
     const int c0 = split * splitLen, c1 = min(V, c0 + splitLen);
-    for (int v = c0 + tid; v < c1; v += 256) {
+    const int nvec = (c1 > c0) ? (c1 - c0) / 4 : 0;
+    const float4* row4 = reinterpret_cast<const float4*>(row + c0);
+    constexpr int kBatch = 4;
+    for (int i0 = 0; i0 < nvec; i0 += 256 * kBatch) {
+      float4 x[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int i = i0 + u * 256 + tid;
+        x[u] = (i < nvec) ? row4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        if (i0 + u * 256 + tid >= nvec) continue;
+        const int v = c0 + (i0 + u * 256 + tid) * 4;
+        cnt += (x[u].x > lc) || (x[u].x == lc && v < c);
+        cnt += (x[u].y > lc) || (x[u].y == lc && v + 1 < c);
+        cnt += (x[u].z > lc) || (x[u].z == lc && v + 2 < c);
+        cnt += (x[u].w > lc) || (x[u].w == lc && v + 3 < c);
+      }
+    }
+    for (int v = c0 + nvec * 4 + tid; v < c1; v += 256) {
       const float l = row[v];
       cnt += (l > lc) || (l == lc && v < c);
     }
@@ -449,7 +471,7 @@ __global__ __launch_bounds__(256) void rank_kernel(const float* __restrict__ L, 
 
 hipError_t launch_rank(const float* L, int Lld, const int32_t* tokens, int B, int M, int V, int* rankpart,
                        hipStream_t st) {
-  const int splitLen = (V + kRankSplits - 1) / kRankSplits;
+  const int splitLen = ((V + kRankSplits - 1) / kRankSplits + 3) / 4 * 4;
   hipLaunchKernelGGL(rank_kernel, dim3(B * M, kRankSplits), dim3(256), 0, st, L, Lld, tokens, M, V, splitLen,
                      rankpart);
   return hipGetLastError();
