@@ -66,7 +66,6 @@ def main() -> int:
               "single MI355X; no collectives exist). Re-run with --gpus 1.", file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
 
     from paper_2501_19309_amd import binding as jb, harness
