@@ -241,8 +241,9 @@ int jd_verify_validate_config(const jd_verify_config* cfg);
  * default stream and synchronise; out_* are host pointers.
  *   jd_verify_probe_mfma_bf16: TFLOP/s that a loop of nothing but independent
  *       v_mfma_f32_16x16x32_bf16 sustains on all compute units (no memory traffic), i.e. what
- *       the matrix cores deliver under the board's power limit.  operand_mode 0: all-zero
- *       operands; 1: values spread like N(0,1), as embeddings and weights are.
+ *       the matrix cores deliver at the clock the board grants them.  operand_mode 0: all-zero
+ *       operands; 1: values spread like N(0,1), as embeddings and weights are (lower: the power
+ *       drawn, hence the clock, depends on the data).
  *   jd_verify_probe_hbm_read: GB/s of a pure streaming read (128-bit loads, grid stride) of a
  *       zero-filled buffer of `bytes` bytes, 1 MiB <= bytes <= 64 GiB (use >= 2 GiB: smaller buffers
  *       measure the last-level cache).

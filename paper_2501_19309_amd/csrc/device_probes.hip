@@ -1,5 +1,5 @@
 // Two measurements of the device itself, for reading the library's roofline fractions: what a loop of
-// nothing but independent bf16 MFMAs sustains (the matrix cores under the board's power limit), and what a
+// nothing but independent bf16 MFMAs sustains (the matrix cores at the clock the board grants them), and what a
 // pure streaming read of a large buffer sustains (HBM).  Diagnostics behind the C ABI; the verification
 // path does not use them.
 #include "../../include/jd_verify.h"
@@ -12,12 +12,15 @@
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kProbeTiles = 32;  // independent accumulator tiles per wavefront: no MFMA waits for another
+constexpr int kProbeTiles = 24;  // independent accumulator tiles per wavefront: no MFMA waits for another
 
-// Two workgroups of four wavefronts per compute unit: the loop has no memory traffic, so however the
-// dispatcher places them, every SIMD's matrix pipeline has MFMAs waiting.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// Several wavefronts per SIMD (the kernel needs about 110 registers), each a loop of nothing but independent
+// MFMAs that accumulate in place (inline assembly: left to the compiler the loop gets register copies and
+// wait states between the MFMAs, and then measures those).  The loop has no memory traffic, so however the
+// dispatcher places the workgroups, every SIMD's matrix pipeline always has an MFMA waiting.
 // operand_mode 0: all-zero operands; 1: values spread like N(0,1) rounded to bf16, different per lane and
 // element (what embeddings and weights look like to the matrix cores).
 __global__ __launch_bounds__(256) void mfma_rate_kernel(float* out, int iters, int operand_mode) {
@@ -31,13 +34,14 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(float* out, int iters, i
     return __float_as_uint(f) >> 16;
   };
   auto pair = [&](unsigned i) { return operand_mode == 0 ? 0u : (value(2 * i) | (value(2 * i + 1) << 16)); };
-  const uint4 a4 = make_uint4(pair(0), pair(1), pair(2), pair(3));
-  const uint4 b4 = make_uint4(pair(4), pair(5), pair(6), pair(7));
-  const bf16x8 a = __builtin_bit_cast(bf16x8, a4), b = __builtin_bit_cast(bf16x8, b4);
+  const u32x4 a = {pair(0), pair(1), pair(2), pair(3)};
+  const u32x4 b = {pair(4), pair(5), pair(6), pair(7)};
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < kProbeTiles; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+    for (int i = 0; i < kProbeTiles; ++i)
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
   }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMAs leave the pipeline before their tiles are read
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < kProbeTiles; ++i) s += (acc[i][0] + acc[i][1]) + (acc[i][2] + acc[i][3]);
@@ -103,7 +107,7 @@ extern "C" int jd_verify_probe_mfma_bf16(int32_t device, int32_t operand_mode, d
   float ms = 0.f;
   JD_TRY(hipSetDevice(device));
   JD_TRY(hipGetDeviceProperties(&prop, device));
-  wgs = 2 * prop.multiProcessorCount;  // 4 wavefronts each: two per SIMD, wherever the dispatcher puts them
+  wgs = 4 * prop.multiProcessorCount;  // 4 wavefronts each: several per SIMD, wherever the dispatcher puts them
   JD_TRY(hipMalloc(reinterpret_cast<void**>(&out), (size_t)wgs * 256 * sizeof(float)));
   JD_TRY(hipEventCreate(&e0));
   JD_TRY(hipEventCreate(&e1));
