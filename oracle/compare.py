@@ -5,8 +5,10 @@ line).  Takes two dicts of numpy arrays and applies the parity bar:
 
   * accept_len and next_token bit-exact, except
       - slots where |p/q - eps| < 1e-5 or the judge logit is within 1e-4 of its
-        threshold (a flipped mask bit there is counted, not failed, and the sequence's
-        accept_len / next_token are then excluded),
+        threshold (a flipped mask bit there is counted, not failed; the sequence's
+        accept_len then follows from the library's own masks, and its next_token is held
+        to what the oracle's step 7 gives for THAT prefix when the caller supplies
+        ``replay``, and left unchecked otherwise),
       - sampler draws whose threshold lies within SAMPLER_BAND of a CDF edge, and only
         if the other side returned the neighbouring token that carries mass;
   * p and q at the drafted tokens, row sum-exp and (if present) the full softmax within
@@ -19,7 +21,7 @@ line).  Takes two dicts of numpy arrays and applies the parity bar:
 
 from __future__ import annotations
 
-from typing import Dict
+from typing import Callable, Dict, Optional, Tuple
 
 import numpy as np
 
@@ -33,8 +35,13 @@ JUDGE_ABS_TOL = 1e-3
 
 
 def compare(gpu: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], mode_judge: bool = True,
-            rule_topk: bool = False) -> Dict[str, int]:
+            rule_topk: bool = False,
+            replay: Optional[Callable[[int, int], Tuple[int, float, int, int]]] = None) -> Dict[str, int]:
     """Raise AssertionError on any violation; return counts of excused near-ties.
+
+    ``replay(b, m)`` (optional) returns the oracle's (token, margin, neighbour below, neighbour above)
+    for row b of these dicts under a forced accepted prefix m (verify_oracle.new_token_for_prefix); with
+    it, a sequence whose masks differ inside a band still has its next_token checked.
 
     With ``rule_topk`` the oracle's accept_margin / sampler_margin are logit distances (top-K
     boundary, gap between the two largest logits) and the band is TOPK_BAND for both."""
@@ -62,14 +69,23 @@ def compare(gpu: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], mode_judge: 
         # the library's own prefix must be the leading ones of its own masks, always
         lead = int(np.argmin(np.append(z_gpu[b], False)))
         assert int(gpu["accept_len"][b]) == lead, (b, gpu["accept_len"][b], z_gpu[b])
+        r, margin = int(ref["next_token"][b]), float(ref["sampler_margin"][b])
+        nbrs = (int(ref["next_below"][b]), int(ref["next_above"][b]))
         if (z_gpu[b] != z_ref[b]).any():
+            # a mask bit inside a band went the other way (checked above): the library's prefix is the one of its
+            # own masks (checked above); its token must be right for that prefix
             rep["excluded_sequences"] += 1
-            continue
-        assert int(gpu["accept_len"][b]) == int(ref["accept_len"][b]), (b, gpu["accept_len"][b], ref["accept_len"][b])
-        g, r = int(gpu["next_token"][b]), int(ref["next_token"][b])
+            if replay is None or not clean[b]:
+                continue
+            r, margin, lo, hi = replay(b, lead)
+            nbrs = (int(lo), int(hi))
+            rep["replayed_sequences"] = rep.get("replayed_sequences", 0) + 1
+        else:
+            assert int(gpu["accept_len"][b]) == int(ref["accept_len"][b]), (b, gpu["accept_len"][b], ref["accept_len"][b])
+        g = int(gpu["next_token"][b])
         if g != r:
-            near = ref["sampler_margin"][b] < sampler_band and g in (int(ref["next_below"][b]), int(ref["next_above"][b]))
-            assert near, f"next_token differs at b={b}: {g} vs {r}, margin {ref['sampler_margin'][b]:.3e}"
+            near = margin < sampler_band and g >= 0 and g in nbrs
+            assert near, f"next_token differs at b={b}: {g} vs {r}, margin {margin:.3e}"
             rep["near_tie_sampler"] += 1
 
     def rel_close(name, a, r, mask=None):

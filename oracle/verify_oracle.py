@@ -281,6 +281,51 @@ def mass_neighbours(mass: np.ndarray, v: int):
     return (int(below[-1]) if below.size else -1), (int(above[0]) + v + 1 if above.size else -1)
 
 
+def new_token(L: np.ndarray, P: np.ndarray, Q: np.ndarray, m: int, M: int, u_s: float, rule: int = RULE_SAMPLING,
+              resample: int = RESAMPLE_RESIDUAL):
+    """Step 7 for one sequence whose accepted prefix is m (Sec. 3.1, paragraph after Eq. 4): the
+    replacement token from norm(max(0, p_{m+1} - q_{m+1})) if m < M, the bonus token from p_{M+1} if
+    m == M; under RULE_TOPK the greedy token argmax p (lowest id on ties).  L, P are the M+1 target
+    logit / probability rows, Q the M draft probability rows.
+    Returns (token, margin, neighbour below, neighbour above, status bits)."""
+    status = 0
+    if rule == RULE_TOPK:                                      # greedy target: argmax of row m
+        tok, runner_up, smargin = argmax_lowest_id(L[m])
+        return tok, smargin, -1, runner_up, status
+    if m < M and resample == RESAMPLE_RESIDUAL:
+        mass = residual(P[m], Q[m])
+        if np.sum(mass) == 0:
+            status |= STATUS_ZERO_RESIDUAL
+            mass = P[m]
+    else:
+        mass = P[m]                                            # bonus row, or "sample from p_i"
+    tok, smargin = inverse_cdf(mass, u_s)
+    below, above = mass_neighbours(mass, tok)
+    return tok, smargin, below, above, status
+
+
+def new_token_for_prefix(emb, W, draft, uniforms, b: int, m: int, *, draft_kind: int = DRAFT_LOGITS,
+                         temperature: float = 1.0, w_layout: str = "vd", rule: int = RULE_SAMPLING,
+                         resample: int = RESAMPLE_RESIDUAL, w_scale: Optional[np.ndarray] = None):
+    """Step 7 alone, for sequence b with a GIVEN accepted prefix m (0 <= m <= M): what ``verify`` would
+    emit as the new token had its masks produced that prefix.  The comparison uses it where a mask bit
+    inside a near-tie band moved the library's prefix: the library's token must then still be the right
+    one for its own prefix.  Returns (token, margin, neighbour below, neighbour above)."""
+    emb = np.asarray(emb)
+    M = emb.shape[1] - 1
+    if not (0 <= m <= M):
+        raise ValueError("prefix outside [0, M]")
+    L = target_logits(emb[b, m:m + 1], W, temperature, w_layout, w_scale)       # only row m is needed
+    P = softmax_rows(L)[0]
+    Q = np.zeros((1, L.shape[1]))
+    if m < M:
+        Dm = np.asarray(draft[b, m:m + 1], dtype=np.float64)
+        Q = softmax_rows(Dm)[0] if draft_kind == DRAFT_LOGITS else Dm
+    # rows re-indexed so that row 0 is row m; M - m > 0 iff a draft row exists
+    tok, margin, below, above, _ = new_token(L, P, Q, 0, 1 if m < M else 0, float(uniforms[b, M]), rule, resample)
+    return tok, margin, below, above
+
+
 # --------------------------------------------------------------------------- main entry
 
 def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
@@ -377,19 +422,8 @@ def verify(emb: np.ndarray, W: np.ndarray, w_judge: np.ndarray,
             out["z_stand"][i, j], out["z_judge"][i, j] = zs, zj
             z.append(zs or (mode == MODE_JUDGE and zj))            # step 5
         m = accepted_prefix(z)                                     # step 6
-        if rule == RULE_TOPK:                                      # greedy target: argmax of row m
-            tok, runner_up, smargin = argmax_lowest_id(L[m])
-            below, above = -1, runner_up
-        else:
-            if m < M and resample == RESAMPLE_RESIDUAL:            # step 7
-                mass = residual(P[m], Q[m])
-                if np.sum(mass) == 0:
-                    status |= STATUS_ZERO_RESIDUAL
-                    mass = P[m]
-            else:
-                mass = P[m]                                        # bonus row, or "sample from p_i"
-            tok, smargin = inverse_cdf(mass, float(uniforms[b, M]))
-            below, above = mass_neighbours(mass, tok)
+        tok, smargin, below, above, st7 = new_token(L, P, Q, m, M, float(uniforms[b, M]), rule, resample)   # step 7
+        status |= st7
         out["accept_len"][i], out["next_token"][i], out["status"][i] = m, tok, status
         out["row_max"][i], out["row_sumexp"][i] = rmax, rsum
         out["sampler_margin"][i] = smargin

@@ -881,3 +881,269 @@ def test_comparison_accepts_the_oracle_and_catches_planted_mistakes():
     g["p_at_draft"][0, 0] = 1e-30
     with pytest.raises(AssertionError):
         compare(g, tiny)
+
+
+# ----------------------------------------------------------------------------- the helpers that decide what parity may excuse
+
+def _py_first_over(mass, thresh):
+    """Ascending-id scan with a running sum (the order numpy's cumsum uses): first token whose cumulative
+    mass exceeds thresh, else the last token with mass."""
+    run, last = 0.0, -1
+    for v, x in enumerate(mass):
+        run += float(x)
+        if x > 0:
+            last = v
+        if run > thresh:
+            return v
+    return last
+
+
+def test_mass_neighbours_against_a_scan():
+    # zero runs at both ends and in the middle, single-token support, empty support
+    cases = [
+        [0, 0, 3, 0, 0, 1, 2, 0, 0, 0, 5, 0, 0],
+        [1, 0, 0, 0, 0, 0, 0, 1],
+        [0, 0, 0, 4, 0, 0],
+        [2, 3, 4],
+        [0, 0, 0],
+    ]
+    rng = np.random.default_rng(31)
+    for _ in range(30):
+        cases.append((rng.random(40) * (rng.random(40) > 0.6)).tolist())
+    for mass in cases:
+        mass = np.asarray(mass, dtype=np.float64)
+        for v in range(len(mass)):
+            below = -1
+            for t in range(v - 1, -1, -1):
+                if mass[t] > 0:
+                    below = t
+                    break
+            above = -1
+            for t in range(v + 1, len(mass)):
+                if mass[t] > 0:
+                    above = t
+                    break
+            assert vo.mass_neighbours(mass, v) == (below, above), (mass, v)
+    # the neighbour is NOT simply the adjacent id
+    assert vo.mass_neighbours(np.array([1.0, 0.0, 0.0, 2.0, 0.0, 3.0]), 3) == (0, 5)
+
+
+def test_inverse_cdf_margin_is_the_distance_to_the_nearest_edge():
+    # Moving the threshold by just more than margin * S towards the nearer edge changes the token, to the
+    # neighbour that carries mass on that side; by just less, in either direction, it does not.
+    rng = np.random.default_rng(32)
+    moved_up = moved_down = 0
+    for trial in range(300):
+        V = int(rng.integers(3, 60))
+        mass = rng.random(V) * (rng.random(V) > 0.4)
+        if not (mass > 0).any():
+            continue
+        S = float(np.sum(mass))
+        u = float(rng.random())
+        tok, margin = vo.inverse_cdf(mass, u)
+        thresh = u * S
+        assert tok == _py_first_over(mass, thresh)
+        below, above = vo.mass_neighbours(mass, tok)
+        if margin < 1e-6:
+            continue
+        step_in, step_out = margin * S * (1 - 1e-6), margin * S * (1 + 1e-6)
+        first = lambda t: _py_first_over(mass, t) if t >= 0 else tok   # a threshold u * S is never negative
+        assert first(thresh + step_in) == tok and first(thresh - step_in) == tok
+        up, down = first(thresh + step_out), first(thresh - step_out)
+        if up == tok and down == tok:
+            # only possible for the last token with mass when its upper edge (the total mass, which no u < 1
+            # reaches) is the nearer one: the margin then understates, never overstates, the room
+            run = 0.0
+            for t in mass:
+                run += float(t)
+            assert above < 0 and thresh + step_out >= run * (1 - 1e-12), "margin overstates the distance to both edges"
+        if up != tok:
+            assert up == above, (mass, u, tok, up, above)   # for the last token with mass the scan falls back to it
+            moved_up += 1
+        if down != tok:
+            assert down == below and below >= 0
+            moved_down += 1
+        if below < 0:   # nothing below carries mass: only the upper edge counts
+            assert down == tok
+            cum = float(np.cumsum(mass)[tok])
+            assert abs(margin - (cum - thresh) / S) < 1e-15
+    assert moved_up > 30 and moved_down > 30
+    # hand case: mass 1, 0, 2, 1 (S = 4), u = 0.3: threshold 1.2 lies 0.2 above the edge at 1 and 1.8 below the edge at 3
+    tok, margin = vo.inverse_cdf(np.array([1.0, 0.0, 2.0, 1.0]), 0.3)
+    assert tok == 2 and abs(margin - 0.2 / 4) < 1e-15
+    # the last token with mass has no upper neighbour: crossing its upper edge is impossible (u < 1)
+    tok, margin = vo.inverse_cdf(np.array([1.0, 3.0, 0.0]), 0.9)
+    assert tok == 1 and abs(margin - 0.1) < 1e-12 and vo.mass_neighbours(np.array([1.0, 3.0, 0.0]), 1) == (0, -1)
+
+
+def _py_rank(row, c):
+    order = sorted(range(len(row)), key=lambda v: (-float(row[v]), v))   # ties: lower id first
+    return order.index(c)
+
+
+def test_topk_margin_for_every_k_with_ties():
+    # Quarter-integer logits: many exact ties, exact float64 arithmetic.  Shifting L[c] by just more than the
+    # margin across the boundary flips "c is among the top K", by just less it does not.
+    rng = np.random.default_rng(33)
+    flips = 0
+    for trial in range(60):
+        V = int(rng.integers(2, 12))
+        row = rng.integers(-6, 7, size=V).astype(np.float64) / 4.0
+        for c in range(V):
+            for K in range(1, V + 1):
+                accepted = _py_rank(row, c) < K
+                assert (vo.rank_of(row, c) < K) == accepted
+                mg = vo.topk_margin(row, c, K)
+                assert mg >= 0
+                if K == V:
+                    assert accepted and mg == math.inf   # nothing can push c out of the top V
+                    continue
+                sign = -1.0 if accepted else 1.0         # direction that crosses the boundary
+                over, under = row.copy(), row.copy()
+                over[c] += sign * (mg + 1e-9)
+                assert (_py_rank(over, c) < K) != accepted, (row, c, K, mg)
+                flips += 1
+                if mg > 1e-9:
+                    under[c] += sign * (mg - 1e-9)
+                    assert (_py_rank(under, c) < K) == accepted, (row, c, K, mg)
+                else:
+                    # margin 0 = an exact tie at the boundary, decided by the token ids
+                    others = sorted((float(x) for i, x in enumerate(row) if i != c), reverse=True)
+                    assert others[K - 1] == row[c]
+    assert flips > 1000
+    # hand case: logits 5, 3, 3, 1, K = 2: token 1 (3.0, wins the tie by id) is in, token 2 is out, both by margin 0;
+    # token 0 is in by 2 (the 2nd largest other is 3), token 3 is out by 2
+    row = np.array([5.0, 3.0, 3.0, 1.0])
+    assert [vo.topk_margin(row, c, 2) for c in range(4)] == [2.0, 0.0, 0.0, 2.0]
+    assert [vo.rank_of(row, c) < 2 for c in range(4)] == [True, True, False, False]
+
+
+def test_new_token_for_a_given_prefix():
+    # new_token_for_prefix(b, m) is step 7 with the prefix forced to m: equal to verify()'s token at verify()'s own
+    # prefix, and equal to a scalar evaluation of the definition at every other prefix
+    shape = VerifyShape("t", 12, 5, 32, 90, "f32", 1.5)
+    x = make_inputs(shape, 3)
+    args = (x["emb"], x["W"], x["draft_logits"], x["uniforms"])
+    out = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"])
+    assert len(set(out["accept_len"].tolist())) >= 3
+    Wd = x["W"].astype(np.float64)
+    for b in range(shape.B):
+        tok, margin, lo, hi = vo.new_token_for_prefix(*args, b, int(out["accept_len"][b]))
+        assert (tok, lo, hi) == (int(out["next_token"][b]), int(out["next_below"][b]), int(out["next_above"][b]))
+        assert abs(margin - out["sampler_margin"][b]) < 1e-12      # a one-row product may sum in another order
+        for m in range(shape.M + 1):
+            p = py_softmax([float(np.dot(x["emb"][b, m].astype(np.float64), Wd[v])) for v in range(shape.V)])
+            if m < shape.M:
+                q = py_softmax([float(t) for t in x["draft_logits"][b, m]])
+                mass = [max(0.0, pv - qv) for pv, qv in zip(p, q)]
+            else:
+                mass = p
+            S = 0.0
+            for t in mass:
+                S += t
+            want = _py_first_over(mass, float(x["uniforms"][b, shape.M]) * S)
+            got = vo.new_token_for_prefix(*args, b, m)
+            assert got[0] == want or got[1] < 1e-12, (b, m)
+    # plain-p replacement and the greedy rule go through the same wrapper
+    t_res = vo.new_token_for_prefix(*args, 0, 0)[0]
+    t_tgt = vo.new_token_for_prefix(*args, 0, 0, resample=vo.RESAMPLE_TARGET)[0]
+    ref_tgt = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+                        resample=vo.RESAMPLE_TARGET, seqs=[0])
+    if int(ref_tgt["accept_len"][0]) == 0:
+        assert t_tgt == int(ref_tgt["next_token"][0])
+    L0 = vo.target_logits(x["emb"][0, 2:3], x["W"])[0]
+    assert vo.new_token_for_prefix(*args, 0, 2, rule=vo.RULE_TOPK)[0] == int(np.argmax(L0))
+    assert isinstance(t_res, int)
+    with pytest.raises(ValueError):
+        vo.new_token_for_prefix(*args, 0, shape.M + 1)
+
+
+def _library_types(r):
+    o = {k: np.array(v) for k, v in r.items()}
+    for k in ("p_at_draft", "q_at_draft", "judge_logit", "row_max", "row_sumexp"):
+        o[k] = o[k].astype(np.float32)
+    return o
+
+
+def test_comparison_bands_have_the_stated_widths():
+    # A flipped mask bit is excused only inside the stated band (|p/q - eps| < 1e-5; judge logit within 1e-4 of
+    # its threshold), a different new token only inside the sampler band (1e-5 of the total mass) AND only for
+    # the neighbouring token that carries mass.
+    from oracle.compare import compare
+    V, M = 8, 2
+    P0 = [.2, .05, .3, .35, .02, .03, .03, .02]
+    Q0 = [.1, .15, .1, .05, .12, .13, .2, .15]      # residual of row 0: .1, 0, .2, .3, 0, 0, 0, 0 (S = .6)
+    P1 = [.25] + [.75 / 7] * 7
+    Q1 = [.5] + [.5 / 7] * 7                          # token 0 at slot 1: p/q = 0.5
+    P2 = [.125] * 8
+    P, Q = np.array([P0, P1, P2]), np.array([Q0, Q1])
+
+    def case(tokens, jbits, u, **kw):
+        return direct_case(P, Q, jbits, tokens, u, **kw)
+
+    def flipped(ref, key, idx):
+        g = _library_types(ref)
+        g[key][idx] = 1 - g[key][idx]
+        z = g["z_stand"].astype(bool) | g["z_judge"].astype(bool)
+        g["accept_len"][0] = int(np.argmin(np.append(z[0], False)))
+        return g
+
+    # --- standard test, slot 1: ratio 0.5, u = 0.5 + 2e-5 is outside the band, 0.5 + 5e-6 inside
+    far = case([[2, 0]], [1, 0], [0.3, 0.5 + 2e-5, 0.7])
+    near = case([[2, 0]], [1, 0], [0.3, 0.5 + 5e-6, 0.7])
+    assert not far["z_stand"][0, 1] and not near["z_stand"][0, 1]
+    assert 1.9e-5 < far["accept_margin"][0, 1] < 2.1e-5 and 4e-6 < near["accept_margin"][0, 1] < 6e-6
+    with pytest.raises(AssertionError):
+        compare(flipped(far, "z_stand", (0, 1)), far)
+    rep = compare(flipped(near, "z_stand", (0, 1)), near)
+    assert rep["near_tie_stand"] == 1 and rep["excluded_sequences"] == 1
+    # --- judge test, slot 1: logit = 1 + bias against threshold 0
+    farj = case([[2, 0]], [1, 1], [0.3, 0.9, 0.7], judge_bias=-1.0 + 2e-4)
+    nearj = case([[2, 0]], [1, 1], [0.3, 0.9, 0.7], judge_bias=-1.0 + 5e-5)
+    assert farj["z_judge"][0, 1] and nearj["z_judge"][0, 1] and not farj["z_stand"][0, 1]
+    assert 1.9e-4 < farj["judge_margin"][0, 1] < 2.1e-4 and 4e-5 < nearj["judge_margin"][0, 1] < 6e-5
+    with pytest.raises(AssertionError):
+        compare(flipped(farj, "z_judge", (0, 1)), farj)
+    rep = compare(flipped(nearj, "z_judge", (0, 1)), nearj)
+    assert rep["near_tie_judge"] == 1 and rep["excluded_sequences"] == 1
+    # slot 0 of the same cases is decided far from its threshold (logit -1 + bias): never excused
+    with pytest.raises(AssertionError):
+        compare(flipped(nearj, "z_stand", (0, 0)), nearj)
+    # --- sampler: reject slot 0 (token 1: p/q = 1/3, u = 0.9, judge says no); residual CDF edges .1 .1 .3 .6
+    s_near = case([[1, 0]], [0, 0], [0.9, 0.5, 0.5 + 5e-6])      # threshold 5e-6 * S above the edge at .3
+    s_far = case([[1, 0]], [0, 0], [0.9, 0.5, 0.5 + 2e-5])
+    for r in (s_near, s_far):
+        assert int(r["accept_len"][0]) == 0 and int(r["next_token"][0]) == 3
+        assert (int(r["next_below"][0]), int(r["next_above"][0])) == (2, -1)
+    assert 4e-6 < s_near["sampler_margin"][0] < 6e-6 and 1.9e-5 < s_far["sampler_margin"][0] < 2.1e-5
+
+    def with_token(ref, tok):
+        g = _library_types(ref)
+        g["next_token"][0] = tok
+        return g
+
+    assert compare(with_token(s_near, 2), s_near)["near_tie_sampler"] == 1   # the neighbour with mass, inside the band
+    for tok in (1, 0, 4, 7):   # the adjacent id without mass, a token two edges away, tokens above
+        with pytest.raises(AssertionError):
+            compare(with_token(s_near, tok), s_near)
+    with pytest.raises(AssertionError):   # the same neighbour, outside the band
+        compare(with_token(s_far, 2), s_far)
+    # --- a flipped bit inside the band moves the prefix: with replay the token is held to that prefix
+    g = flipped(near, "z_stand", (0, 1))            # library accepts slot 1 too: prefix 2, bonus token from P2
+    assert int(g["accept_len"][0]) == 2 and int(near["accept_len"][0]) == 1
+    emb = np.log(P).astype(np.float32)[None]
+    Qd = np.concatenate([Q, np.zeros((1, V))]).astype(np.float32)[None]
+    unif = np.array([[0.3, 0.5 + 5e-6, 0.7]], dtype=np.float32)
+
+    def replay(b, m):
+        return vo.new_token_for_prefix(emb, np.eye(V, dtype=np.float32), Qd, unif, b, m, draft_kind=vo.DRAFT_PROBS)
+
+    want = replay(0, 2)[0]
+    assert want == 5                                # uniform P2, u_s = 0.7 -> floor(0.7 * 8)
+    g["next_token"][0] = want
+    rep = compare(g, near, replay=replay)
+    assert rep["replayed_sequences"] == 1 and rep["excluded_sequences"] == 1
+    g["next_token"][0] = int(near["next_token"][0]) if int(near["next_token"][0]) != want else 0
+    compare(g, near)                                # without replay the token of an excluded sequence is not looked at
+    with pytest.raises(AssertionError):
+        compare(g, near, replay=replay)
