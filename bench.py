@@ -246,8 +246,12 @@ def main() -> int:
             record["parity"] = {"ok": False, "error": str(e)[:300]}
 
     ver.destroy()
+    parity_failed = record.get("parity", {}).get("ok") is False
+    if parity_failed:   # a head that no longer matches the oracle delivers no headline number
+        record["invalid"] = "parity check against the oracle failed"
+        record["value_unchecked"], record["value"] = record["value"], None
     print(json.dumps(record))
-    return 0
+    return 3 if parity_failed else 0
 
 
 if __name__ == "__main__":

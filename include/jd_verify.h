@@ -21,7 +21,8 @@
  * its standard test reads LM-head row j, its judge test reads embedding row j+1.
  *
  * All tensor arguments are DEVICE pointers owned by the caller and only borrowed:
- * W_lm and w_judge for the lifetime of the context, everything else for the call.
+ * w_judge (and the weight scales) for the lifetime of the context, W_lm for the lifetime of the
+ * context if it is fp32 and only until create returns otherwise, everything else for the call.
  * Tensors are dense, row-major, last index contiguous.  Work is enqueued on the
  * caller's HIP stream and NOT synchronised; outputs are valid once the stream has
  * reached the end of the call.  jd_verify_create makes config.device the calling
@@ -125,7 +126,10 @@ typedef struct {                /* device pointers; the first three are required
  * Validates cfg, selects the device, allocates the workspace (fp32 logits
  * [max_B*(max_M+1), V], reduction partials) and, for bf16 weights, builds a private
  * copy of W_lm re-tiled into MFMA operand order (one extra W_lm-sized allocation,
- * one-time cost).  d_W_lm and d_w_judge must stay valid and unchanged until destroy.
+ * one-time cost).  d_w_judge must stay valid and unchanged until destroy.  d_W_lm likewise for
+ * JD_F32 weights, which are read in place by every call; for JD_BF16 / JD_FP8_E4M3 / JD_INT8 the
+ * library works from its own copies only, create has finished reading d_W_lm when it returns, and
+ * the caller may release or overwrite it then (a 405B-sized head need not be held twice).
  * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_DTYPE (checked before any HIP call), OOM, HIP (also when
  * cfg->device is not a gfx950 device: the library holds code for that architecture only).
  * On error *out_ctx is set to NULL; jd_verify_last_error_detail() says which runtime call failed.
@@ -136,7 +140,8 @@ int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void
 /*
  * Same as jd_verify_create for quantised weights (w_dtype JD_FP8_E4M3 or JD_INT8; the paper's targets run
  * with 8-bit weights, Table 1 / App. B.3): the effective LM head is W[v,:] = d_w_scale[v] * decode(code[v,:]).
- *   d_w_scale   [V] fp32 device pointer, borrowed for the lifetime of the context; NULL means all ones.
+ *   d_w_scale   [V] fp32 device pointer, borrowed for the lifetime of the context (every call reads it);
+ *               NULL means all ones.
  *               Must be NULL for JD_F32 / JD_BF16 weights (INVALID_ARG otherwise).
  * The library builds a re-tiled copy of the codes (V*d bytes) and, if max_B*(max_M+1) > 64, for the
  * large-row kernels a second FP8 copy in their fragment order (another V*d bytes) resp. a bf16 copy of the

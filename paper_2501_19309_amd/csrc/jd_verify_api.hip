@@ -17,7 +17,7 @@ using namespace jd;
 struct jd_verify_ctx {
   jd_verify_config cfg;
   Geometry geo;
-  const void* W;
+  const void* W;        // the caller's W_lm: kept (and read by every call) for fp32 weights only, else NULL
   const void* wj;
   void* Wp;             // re-tiled bf16 weights (bf16 weights; INT8 weights only for the large-row regime)
   void* Wp8;            // re-tiled one-byte codes (FP8 and INT8 weights)
@@ -52,7 +52,8 @@ static int hip_fail(const char* what, hipError_t e) {
   return e == hipErrorOutOfMemory ? JD_ERR_OOM : JD_ERR_HIP;
 }
 #define JD_HIP(expr) do { const hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(#expr, e_); } while (0)
-#define JD_HIP_RC(expr) do { const hipError_t e_ = (expr); if (rc == JD_OK && e_ != hipSuccess) rc = hip_fail(#expr, e_); } while (0)
+// Evaluates expr only while rc is still JD_OK: after a failed allocation nothing is launched on its (NULL) result.
+#define JD_HIP_RC(expr) do { if (rc == JD_OK) { const hipError_t e_ = (expr); if (e_ != hipSuccess) rc = hip_fail(#expr, e_); } } while (0)
 
 extern "C" const char* jd_verify_last_error_detail(void) { return g_detail; }
 
@@ -152,7 +153,10 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
   c->cfg = *cfg;
   c->geo = make_geometry(cfg->d, cfg->V);
   c->W = d_W_lm; c->wj = d_w_judge; c->wscale = d_w_scale;
-  c->judge_threshold = (cfg->delta >= 1.0f) ? INFINITY : std::log(cfg->delta / (1.0f - cfg->delta));
+  // logit(delta) in double from the float the ABI carries, rounded once (near delta = 1 a float32 evaluation of
+  // delta / (1 - delta) is off by more than the judge logits' own precision)
+  c->judge_threshold = (cfg->delta >= 1.0f) ? INFINITY
+                                            : (float)std::log((double)cfg->delta / (1.0 - (double)cfg->delta));
   c->prof_on = false; c->prof_max = c->prof_n = 0;
   c->bytes = 0;
 
@@ -230,6 +234,9 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
     c->Xn = xn;
   }
   if (rc != JD_OK) { free_ctx(c); return rc; }
+  // bf16 and 8-bit weights now live in the library's own re-tiled copies (the pack kernels have finished):
+  // the caller's tensor is not read again and may be released
+  if (bf16) c->W = nullptr;
   *out_ctx = c;
   return JD_OK;
 }

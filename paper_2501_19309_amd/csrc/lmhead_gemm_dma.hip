@@ -340,6 +340,7 @@ __global__ __launch_bounds__(256) void pack_w8g_kernel(const uint8_t* __restrict
 }
 
 hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* Wg8, hipStream_t st) {
+  if (!W8 || !Wg8) return hipErrorInvalidValue;
   const size_t total = (size_t)(g.dpad / kKStep) * g.nVGalloc * 256;
   const size_t blocks = (total + 255) / 256;
   if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;

@@ -73,6 +73,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
 }
 
 hipError_t launch_pack_w(const void* W, int layout, int src_code, const Geometry& g, void* Wp, hipStream_t st) {
+  if (!W || !Wp) return hipErrorInvalidValue;  // the kernel writes every element of Wp unconditionally
   const int KS = g.dpad / kKStep;
   const size_t total = (size_t)g.nVGalloc * KS * 256;
   const size_t blocks = (total + 255) / 256;
@@ -106,6 +107,7 @@ __global__ __launch_bounds__(256) void pack_w8_kernel(const uint8_t* __restrict_
 }
 
 hipError_t launch_pack_w8(const void* W8, int layout, const Geometry& g, void* Wp8, hipStream_t st) {
+  if (!W8 || !Wp8) return hipErrorInvalidValue;
   const int KP = g.dpad / kKStep / 2;
   const size_t total = (size_t)g.nVGalloc * KP * 256;
   const size_t blocks = (total + 255) / 256;

@@ -253,7 +253,7 @@ __device__ __forceinline__ double chunk_sum(const MassRow& row, int chunk, int V
 
 __global__ __launch_bounds__(256) void sampler_mass_kernel(SamplerArgs a) {
   __shared__ double red[256];
-  const int b = blockIdx.y, chunk = blockIdx.x;
+  const int b = blockIdx.x / a.nChunk, chunk = blockIdx.x % a.nChunk;  // 1-D grid: B is not bounded by 65535
   const MassRow row = make_mass_row(a, b, false);
   const double s = chunk_sum(row, chunk, a.V, red);
   if (threadIdx.x == 0) a.chunk_mass[(size_t)b * a.nChunk + chunk] = s;
@@ -326,6 +326,9 @@ __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
   double S = total_chunk_mass(cm, a.nChunk, red);
   const bool plain = !(S > 0.0);
   if (tid == 0 && S == 0.0 && a.accept_len[b] < a.M && !a.resample_target) atomicOr(&a.status[b], 4u);
+  // a NaN in the sampled row (target or draft: with draft probabilities nothing else has looked at the
+  // whole draft row) must not disappear behind the fallback to p below
+  if (tid == 0 && !(S == S)) atomicOr(&a.status[b], 2u);
   if (plain) {
     // No residual mass (q == p at the cut), or NaN: recompute the chunk masses from p itself.
     const MassRow prow = make_mass_row(a, b, true);
@@ -412,7 +415,8 @@ __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
 }
 
 hipError_t launch_sampler(const SamplerArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(sampler_mass_kernel, dim3(a.nChunk, a.B), dim3(256), 0, st, a);
+  if ((size_t)a.nChunk * (size_t)a.B > 0x7fffffffULL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(sampler_mass_kernel, dim3((unsigned)(a.nChunk * a.B)), dim3(256), 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(sampler_pick_kernel, dim3(a.B), dim3(256), 0, st, a);
@@ -481,9 +485,9 @@ hipError_t launch_rank(const float* L, int Lld, const int32_t* tokens, int B, in
 __global__ __launch_bounds__(256) void argmax_chunk_kernel(const float* __restrict__ L, int Lld,
                                                             const float* __restrict__ t_max,
                                                             const int32_t* __restrict__ accept_len, int M, int V,
-                                                            int* __restrict__ chunk_arg) {
+                                                            int nChunk, int* __restrict__ chunk_arg) {
   __shared__ int s_min;
-  const int b = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x;
+  const int b = blockIdx.x / nChunk, chunk = blockIdx.x % nChunk, tid = threadIdx.x;  // 1-D grid, as the sampler's
   const int r = b * (M + 1) + accept_len[b];
   const float tm = t_max[r];
   const float* row = L + (size_t)r * Lld;
@@ -496,7 +500,7 @@ __global__ __launch_bounds__(256) void argmax_chunk_kernel(const float* __restri
     if (v0 + i < V && row[v0 + i] == tm) cand = v0 + i;
   if (cand != 0x7fffffff) atomicMin(&s_min, cand);
   __syncthreads();
-  if (tid == 0) chunk_arg[(size_t)b * gridDim.x + chunk] = s_min;
+  if (tid == 0) chunk_arg[(size_t)b * nChunk + chunk] = s_min;
 }
 
 __global__ __launch_bounds__(256) void argmax_pick_kernel(const int* __restrict__ chunk_arg, int nChunk,
@@ -514,8 +518,9 @@ __global__ __launch_bounds__(256) void argmax_pick_kernel(const int* __restrict_
 
 hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const int32_t* accept_len, int B, int M,
                          int V, int* chunk_arg, int nChunk, int32_t* next_token, hipStream_t st) {
-  hipLaunchKernelGGL(argmax_chunk_kernel, dim3(nChunk, B), dim3(256), 0, st, L, Lld, t_max, accept_len, M, V,
-                     chunk_arg);
+  if ((size_t)nChunk * (size_t)B > 0x7fffffffULL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(argmax_chunk_kernel, dim3((unsigned)(nChunk * B)), dim3(256), 0, st, L, Lld, t_max, accept_len, M,
+                     V, nChunk, chunk_arg);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(argmax_pick_kernel, dim3(B), dim3(256), 0, st, chunk_arg, nChunk, next_token);
@@ -526,17 +531,20 @@ hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const int3
 
 __global__ __launch_bounds__(256) void probs_kernel(const float* __restrict__ L, int Lld,
                                                      const float* __restrict__ t_max,
-                                                     const float* __restrict__ t_sum, int V,
+                                                     const float* __restrict__ t_sum, int V, int nColBlocks,
                                                      float* __restrict__ probs) {
-  const int r = blockIdx.y;
-  const int v = blockIdx.x * 256 + threadIdx.x;
+  const int r = blockIdx.x / nColBlocks;  // 1-D grid: the row count is not bounded by 65535
+  const int v = (blockIdx.x % nColBlocks) * 256 + threadIdx.x;
   if (v >= V) return;
   probs[(size_t)r * V + v] = expf(L[(size_t)r * Lld + v] - t_max[r]) / t_sum[r];
 }
 
 hipError_t launch_probs(const float* L, int Lld, const float* t_max, const float* t_sum, int R, int V, float* probs,
                         hipStream_t st) {
-  hipLaunchKernelGGL(probs_kernel, dim3((V + 255) / 256, R), dim3(256), 0, st, L, Lld, t_max, t_sum, V, probs);
+  const int nColBlocks = (V + 255) / 256;
+  if ((size_t)nColBlocks * (size_t)R > 0x7fffffffULL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(probs_kernel, dim3((unsigned)(nColBlocks * R)), dim3(256), 0, st, L, Lld, t_max, t_sum, V,
+                     nColBlocks, probs);
   return hipGetLastError();
 }
 
