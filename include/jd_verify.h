@@ -206,6 +206,34 @@ int jd_verify_append_tokens(int32_t B, int32_t M, const int32_t* d_draft_tokens,
                             const int32_t* d_next_token, int32_t* d_token_buf, int32_t cap, int32_t* d_lengths,
                             void* hip_stream);
 
+/*
+ * jd_verify_run for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  No context: the workspace that jd_verify_create would allocate
+ * (fp32 logits [B*(M+1), V rounded up to 64], reduction partials, row statistics, sampler chunk masses) lives in
+ * a static device array of JD_NOALLOC_SCRATCH_BYTES bytes inside the library, which every device that loads
+ * the library holds until the process ends.  The call allocates and frees nothing, on the device or through
+ * any library, and does not synchronise.
+ *   cfg            as for jd_verify_create; w_dtype and emb_dtype must both be JD_F32, the one weight type the
+ *                  LM head multiplies in place from the caller's tensor (bf16 and 8-bit weights run from a
+ *                  re-tiled copy that only a context can hold: UNSUPPORTED_DTYPE).  max_B / max_M only bound
+ *                  B and M here; cfg->device must be the calling thread's current device (INVALID_ARG).
+ *   d_W_lm, d_w_judge   device pointers as for jd_verify_create, borrowed for the call only
+ *   everything else as for jd_verify_run.
+ * Limit: the workspace of the call must fit the array - roughly 4 * B*(M+1) * (V+63)/64*64 bytes plus 256 KiB,
+ * e.g. 26 rows at V = 128256, or 704 rows at V = 5000; beyond it the call returns JD_ERR_SHAPE and
+ * jd_verify_last_error_detail() gives the two sizes.  Nothing in the array needs to start at zero: every
+ * kernel writes what later kernels of the same call read.  All calls on one device share that device's
+ * array, so two calls that overlap in time on one device (two streams, two threads) race; calls on one
+ * stream, or otherwise ordered, are safe, and so are calls on different devices.  The first call on a device
+ * looks up the array's device address (hipGetSymbolAddress); make that call, or create any context on the
+ * device, before capturing.  Errors otherwise as for jd_verify_create (host-side checks) and jd_verify_run.
+ */
+#define JD_NOALLOC_SCRATCH_BYTES (16u << 20)
+int jd_verify_run_noalloc(const jd_verify_config* cfg, const void* d_W_lm, const void* d_w_judge,
+                          int32_t B, int32_t M, const void* d_emb, const void* d_emb_judge,
+                          const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
+                          const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream);
+
 /* Free the workspace and the context.  destroy(NULL) is a no-op returning JD_OK.
  * Caller memory is never freed. */
 int jd_verify_destroy(jd_verify_ctx* ctx);

@@ -33,7 +33,9 @@ EXPORTED_SYMBOLS = (
     "jd_verify_destroy", "jd_verify_strerror", "jd_verify_last_error_detail",
     "jd_verify_profile_begin", "jd_verify_profile_end", "jd_verify_workspace_bytes",
     "jd_verify_validate_config", "jd_verify_probe_mfma_bf16", "jd_verify_probe_hbm_read",
+    "jd_verify_run_noalloc",
 )
+JD_NOALLOC_SCRATCH_BYTES = 16 << 20
 
 
 class jd_verify_config(ctypes.Structure):
@@ -91,6 +93,9 @@ def load_library() -> ctypes.CDLL:
     lib.jd_verify_run_prenorm.argtypes = [vp, i32, i32, vp, vp, ctypes.c_double, vp, vp, i32, vp,
                                           ctypes.POINTER(jd_verify_outputs), vp]
     lib.jd_verify_run_prenorm.restype = ctypes.c_int
+    lib.jd_verify_run_noalloc.argtypes = [ctypes.POINTER(jd_verify_config), vp, vp, i32, i32, vp, vp, vp, vp, i32, vp,
+                                          ctypes.POINTER(jd_verify_outputs), vp]
+    lib.jd_verify_run_noalloc.restype = ctypes.c_int
     lib.jd_verify_append_tokens.argtypes = [i32, i32, vp, vp, vp, vp, i32, vp, vp]
     lib.jd_verify_append_tokens.restype = ctypes.c_int
     lib.jd_verify_destroy.argtypes = [vp]
@@ -169,6 +174,48 @@ def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
+def alloc_outputs(B: int, M: int, V: int = 0, want_probs: bool = False, device: int = 0) -> "VerifyOutputs":
+    """Device tensors for the outputs of one verify call."""
+    import torch as t
+    dev = t.device("cuda", device)
+    f = lambda *s: t.zeros(*s, dtype=t.float32, device=dev)
+    return VerifyOutputs(
+        accept_len=t.zeros(B, dtype=t.int32, device=dev), next_token=t.zeros(B, dtype=t.int32, device=dev),
+        status=t.zeros(B, dtype=t.int32, device=dev),
+        z_stand=t.zeros(B, M, dtype=t.uint8, device=dev), z_judge=t.zeros(B, M, dtype=t.uint8, device=dev),
+        p_at_draft=f(B, M), q_at_draft=f(B, M), judge_logit=f(B, M), row_max=f(B, M + 1),
+        row_sumexp=f(B, M + 1), probs=f(B, M + 1, V) if want_probs else None)
+
+
+def outputs_struct(out: "VerifyOutputs") -> jd_verify_outputs:
+    return jd_verify_outputs(*[_ptr(getattr(out, n)) for n in (
+        "accept_len", "next_token", "status", "z_stand", "z_judge", "p_at_draft", "q_at_draft",
+        "judge_logit", "row_max", "row_sumexp", "probs")])
+
+
+def run_noalloc_raw(cfg: jd_verify_config, W_lm, w_judge, B, M, emb, emb_judge, draft_tokens, draft, draft_rows,
+                    uniforms, outputs: Optional[jd_verify_outputs], stream=0) -> int:
+    """jd_verify_run_noalloc with raw device pointers (ints or None); returns the error code."""
+    return load_library().jd_verify_run_noalloc(ctypes.byref(cfg), W_lm, w_judge, B, M, emb, emb_judge, draft_tokens,
+                                                draft, draft_rows, uniforms,
+                                                ctypes.byref(outputs) if outputs is not None else None,
+                                                ctypes.c_void_p(stream))
+
+
+def run_noalloc(cfg: jd_verify_config, W_lm, w_judge, emb, draft_tokens, draft, uniforms, out: "VerifyOutputs", *,
+                emb_judge=None, stream=None) -> None:
+    """jd_verify_run_noalloc on torch device tensors: one verify call without a context (fp32 weights), the
+    workspace in the library's static device array."""
+    import torch
+    B, M = emb.shape[0], emb.shape[1] - 1
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    rc = run_noalloc_raw(cfg, _ptr(W_lm), _ptr(w_judge), B, M, _ptr(emb), _ptr(emb_judge), _ptr(draft_tokens),
+                         _ptr(draft), draft.shape[1], _ptr(uniforms), outputs_struct(out), stream)
+    if rc != JD_OK:
+        raise JDError(rc, "jd_verify_run_noalloc")
+
+
 @dataclass
 class VerifyOutputs:
     """Device tensors written by one jd_verify_run call."""
@@ -214,15 +261,7 @@ class JDVerify:
 
     # -- jd_verify_run
     def alloc_outputs(self, B: int, M: int, want_probs: bool = False) -> VerifyOutputs:
-        t = self._torch
-        dev = t.device("cuda", self.cfg.device)
-        f = lambda *s: t.zeros(*s, dtype=t.float32, device=dev)
-        return VerifyOutputs(
-            accept_len=t.zeros(B, dtype=t.int32, device=dev), next_token=t.zeros(B, dtype=t.int32, device=dev),
-            status=t.zeros(B, dtype=t.int32, device=dev),
-            z_stand=t.zeros(B, M, dtype=t.uint8, device=dev), z_judge=t.zeros(B, M, dtype=t.uint8, device=dev),
-            p_at_draft=f(B, M), q_at_draft=f(B, M), judge_logit=f(B, M), row_max=f(B, M + 1),
-            row_sumexp=f(B, M + 1), probs=f(B, M + 1, self.cfg.V) if want_probs else None)
+        return alloc_outputs(B, M, self.cfg.V, want_probs, self.cfg.device)
 
     def run(self, emb, draft_tokens, draft, uniforms, out: VerifyOutputs, *, emb_judge=None, stream=None) -> None:
         B, Mp1 = emb.shape[0], emb.shape[1]

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -57,6 +58,40 @@ static int hip_fail(const char* what, hipError_t e) {
 
 extern "C" const char* jd_verify_last_error_detail(void) { return g_detail; }
 
+// ---- workspace of the entry point that allocates nothing (jd_verify_run_noalloc) ------------------
+// Every device the library's code is loaded on holds its own copy of this array, at its own address, until
+// the process ends.  On the host the name `scratch` is only a handle for hipGetSymbolAddress: the address a
+// kernel can use is looked up once per device, with that device current, and kept in g_scratch[device].
+// (No __attribute__((used)) here: the compiler keeps the array, and gives its device-side symbol the external
+// linkage the runtime's look-up needs, because host code refers to it; with that attribute the symbol stays
+// internal to the code object and the look-up ends the process.)
+static __device__ __align__(256) unsigned char scratch[JD_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch[kMaxDevices];  // zero-initialised: not looked up yet
+
+// Device address of `scratch` on `device`, which must be the calling thread's current device and a gfx950.
+static int scratch_for_device(int device, unsigned char** out) {
+  if (device < 0 || device >= kMaxDevices) return JD_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch[device]) {
+    hipDeviceProp_t prop;
+    JD_HIP(hipGetDeviceProperties(&prop, device));
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+      std::snprintf(g_detail, sizeof g_detail, "device %d is %s; this library is built for gfx950 (MI355X) only",
+                    device, prop.gcnArchName);
+      return JD_ERR_HIP;
+    }
+    void* p = nullptr;
+    JD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return hip_fail("hipGetSymbolAddress(scratch) returned NULL", hipErrorInvalidSymbol);
+    g_scratch[device] = p;
+  }
+  *out = static_cast<unsigned char*>(g_scratch[device]);
+  return JD_OK;
+}
+
 extern "C" const char* jd_verify_strerror(int code) {
   switch (code) {
     case JD_OK: return "ok";
@@ -96,6 +131,12 @@ extern "C" int jd_verify_validate_config(const jd_verify_config* c) {
   }
   if (c->w_dtype == JD_BF16 && (c->d % 8) != 0) return JD_ERR_SHAPE;  // 128-bit operand loads
   return JD_OK;
+}
+
+// logit(delta) in double from the float the ABI carries, rounded once (near delta = 1 a float32 evaluation of
+// delta / (1 - delta) is off by more than the judge logits' own precision); delta = 1 never accepts
+static float judge_threshold_of(float delta) {
+  return (delta >= 1.0f) ? INFINITY : (float)std::log((double)delta / (1.0 - (double)delta));
 }
 
 static void free_ctx(jd_verify_ctx* c) {
@@ -144,6 +185,11 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
                   cfg->device, prop.gcnArchName);
     return JD_ERR_HIP;
   }
+  {  // look up this device's copy of the no-allocation workspace now, so that a caller who has created a context
+     // can use jd_verify_run_noalloc under stream capture; contexts themselves do not need it
+    unsigned char* unused = nullptr;
+    (void)scratch_for_device(cfg->device, &unused);
+  }
   // The launchers report hipGetLastError(); a stale code left in this thread by an earlier, unrelated
   // runtime call of the caller (an event query that was "not ready", say) must not be taken for theirs.
   (void)hipGetLastError();
@@ -153,10 +199,7 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
   c->cfg = *cfg;
   c->geo = make_geometry(cfg->d, cfg->V);
   c->W = d_W_lm; c->wj = d_w_judge; c->wscale = d_w_scale;
-  // logit(delta) in double from the float the ABI carries, rounded once (near delta = 1 a float32 evaluation of
-  // delta / (1 - delta) is off by more than the judge logits' own precision)
-  c->judge_threshold = (cfg->delta >= 1.0f) ? INFINITY
-                                            : (float)std::log((double)cfg->delta / (1.0 - (double)cfg->delta));
+  c->judge_threshold = judge_threshold_of(cfg->delta);
   c->prof_on = false; c->prof_max = c->prof_n = 0;
   c->bytes = 0;
 
@@ -429,4 +472,72 @@ extern "C" int jd_verify_append_tokens(int32_t B, int32_t M, const int32_t* d_dr
   JD_HIP(launch_append_tokens(B, M, d_draft_tokens, d_accept_len, d_next_token, d_token_buf, cap, d_lengths,
                               static_cast<hipStream_t>(hip_stream)));
   return JD_OK;
+}
+
+// jd_verify_run for fp32 weights without a context: the workspace that jd_verify_create would allocate is laid
+// out in the device's `scratch` array, the LM head reads the caller's W_lm in place, and the same kernels run.
+extern "C" int jd_verify_run_noalloc(const jd_verify_config* cfg, const void* d_W_lm, const void* d_w_judge, int32_t B,
+                                     int32_t M, const void* d_emb, const void* d_emb_judge,
+                                     const int32_t* d_draft_tokens, const float* d_draft, int32_t draft_rows,
+                                     const float* d_uniforms, const jd_verify_outputs* out, void* hip_stream) {
+  int rc = jd_verify_validate_config(cfg);
+  if (rc != JD_OK) return rc;
+  if (!d_W_lm || !d_w_judge || !d_emb) return JD_ERR_INVALID_ARG;
+  // bf16 and 8-bit weights are multiplied from a re-tiled copy, which only a context can hold
+  if (cfg->w_dtype != JD_F32 || cfg->emb_dtype != JD_F32) return JD_ERR_UNSUPPORTED_DTYPE;
+  if (B < 1 || M < 1 || B > cfg->max_B || M > cfg->max_M) return JD_ERR_SHAPE;
+
+  // the workspace of THIS call (its B and M, not the config's maxima), carved out of the scratch array
+  const Geometry geo = make_geometry(cfg->d, cfg->V);
+  const size_t R = (size_t)B * (M + 1), S = (size_t)B * M;
+  const int nChunk = (cfg->V + kSamplerChunk - 1) / kSamplerChunk;
+  const bool topk = cfg->rule == JD_RULE_TOPK;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+  const size_t o_L = take(R * (size_t)geo.Vpad * sizeof(float));
+  const size_t o_tpart = take(R * (size_t)kF32Splits * sizeof(float2));
+  const size_t o_dpart = take(S * (size_t)kDraftSplits * sizeof(float2));
+  const size_t o_tmax = take(R * sizeof(float)), o_tsum = take(R * sizeof(float));
+  const size_t o_qmax = take(S * sizeof(float)), o_qsum = take(S * sizeof(float));
+  const size_t o_g = take(S * sizeof(float));
+  const size_t o_cm = take((size_t)B * nChunk * sizeof(double));
+  const size_t o_rank = take(topk ? S * (size_t)kRankSplits * sizeof(int) : 0);
+  if (off > (size_t)JD_NOALLOC_SCRATCH_BYTES) {
+    std::snprintf(g_detail, sizeof g_detail, "jd_verify_run_noalloc: this call needs %zu bytes of workspace, the "
+                  "static scratch array holds %zu", off, (size_t)JD_NOALLOC_SCRATCH_BYTES);
+    return JD_ERR_SHAPE;
+  }
+
+  int cur = -1;
+  JD_HIP(hipGetDevice(&cur));
+  if (cur != cfg->device) {
+    std::snprintf(g_detail, sizeof g_detail, "jd_verify_run_noalloc: current device is %d, config.device is %d", cur,
+                  cfg->device);
+    return JD_ERR_INVALID_ARG;
+  }
+  unsigned char* base = nullptr;
+  rc = scratch_for_device(cfg->device, &base);
+  if (rc != JD_OK) return rc;
+
+  // a context on the host stack that owns nothing: run_impl only reads it
+  jd_verify_ctx c;
+  c.cfg = *cfg;
+  c.cfg.max_B = B; c.cfg.max_M = M;
+  c.geo = geo;
+  c.W = d_W_lm; c.wj = d_w_judge; c.wscale = nullptr;
+  c.Wp = c.Wp8 = c.Wg8 = c.Xp = c.Xn = c.pool = nullptr;
+  c.L = reinterpret_cast<float*>(base + o_L);
+  c.tpart = reinterpret_cast<float2*>(base + o_tpart);
+  c.dpart = reinterpret_cast<float2*>(base + o_dpart);
+  c.t_max = reinterpret_cast<float*>(base + o_tmax); c.t_sum = reinterpret_cast<float*>(base + o_tsum);
+  c.q_max = reinterpret_cast<float*>(base + o_qmax); c.q_sum = reinterpret_cast<float*>(base + o_qsum);
+  c.g = reinterpret_cast<float*>(base + o_g);
+  c.chunk_mass = reinterpret_cast<double*>(base + o_cm);
+  c.rankpart = topk ? reinterpret_cast<int*>(base + o_rank) : nullptr;
+  c.nPartT = kF32Splits; c.nPartD = kDraftSplits; c.nChunk = nChunk;
+  c.bytes = 0;
+  c.judge_threshold = judge_threshold_of(cfg->delta);
+  c.prof_on = false; c.prof_max = c.prof_n = 0;
+  return run_impl(&c, B, M, d_emb, d_emb_judge, nullptr, nullptr, 0.0, d_draft_tokens, d_draft, draft_rows, d_uniforms,
+                  out, hip_stream);
 }
