@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the batched verification head on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4] [--seed 0] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4] [--seed 0] [--no-cpu-baseline] [--no-secondary]
 
 One step = one jd_verify_run call (LM head, vocabulary softmax, draft statistics, accept
 tests, judge, OR, accepted prefix, residual/bonus sampler) on one batch of seeded
@@ -10,6 +10,9 @@ synthetic inputs that are already resident in HBM.  Prints ONE JSON line.
 The headline workload is the Llama-3.1-405B-shaped head (B=1, M=25, d=16384, V=128256,
 bf16 weights): the metric "verified draft positions/s" = B*M / time per call, with the
 fraction of the 8 TB/s HBM roofline reached by the LM-head kernel that dominates it.
+When the headline workload is the one being run, the same line carries a `secondary`
+list with the other Llama-shaped workloads measured the same way in the same process:
+C5 (B=64, the MFMA-bound shape, against the bf16 matrix-core peak), C2 and C3 (HBM bound).
 """
 
 from __future__ import annotations
@@ -27,53 +30,34 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
-# HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
-# what the same counter reads for a plain 1 GiB copy (profiles/lmhead_skinny_C4_hbm_traffic.md,
-# profiles/lmhead_gemm_C5_counters.md, profiles/verify_call_C4q_fp8_kernel_stats_and_traffic.md,
-# profiles/verify_call_C4q_C4i_C5q_8bit_kernel_stats.md);
-# None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 4.2533e9, "C4q": 2.1496e9, "C4i": 2.1499e9, "C5": 2.855e9, "C5q": 1.8058e9}  # fetched + written
+# HBM bytes per LM-head launch (fetched + written) as read with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by what the same counter reads for a plain 1 GiB copy; (bytes, where the reading is recorded).  A run of
+# bench.py cannot read hardware counters itself: the figure belongs to the kernel build named in that file and is
+# re-measured when the LM-head kernels change.  Workloads without an entry report null.
+MEASURED_TRAFFIC = {
+    "C4": (4.2533e9, "profiles/lmhead_skinny_C4_hbm_traffic.md: lmhead_skinny_kernel<2,4,0>"),
+    "C4q": (2.1496e9, "profiles/verify_call_C4q_fp8_kernel_stats_and_traffic.md: lmhead_skinny_kernel<2,4,1>"),
+    "C4i": (2.1499e9, "profiles/verify_call_C4q_C4i_C5q_8bit_kernel_stats.md: lmhead_skinny_kernel<2,4,2>"),
+    "C5": (2.855e9, "profiles/lmhead_gemm_C5_counters.md: lmhead_gemm_dma_kernel<false>"),
+    "C5q": (1.8058e9, "profiles/verify_call_C4q_C4i_C5q_8bit_kernel_stats.md: lmhead_gemm_dma_kernel<true>"),
+}
+MFMA_BOUND = ("C5", "C5q", "C5i")
+SECONDARY = ("C5", "C2", "C3")   # measured after the headline workload C4, in the same process
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "C2q", "C3q", "C4q", "C5q", "C2i", "C3i", "C4i"],
-                    help="C2..C5: bf16 W_lm (C4 is the headline); C2q..C5q: the same shapes with FP8 E4M3 W_lm; "
-                         "C2i..C4i: with INT8 W_lm")
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-device-probe", action="store_true",
-                    help="skip the measurement of the device's own MFMA / HBM-read rate after the timed region")
-    ap.add_argument("--rule", default="sampling", choices=["sampling", "topk"],
-                    help="acceptance rule: Eq. 4 speculative sampling, or top-K verification (Sec. 5 baseline)")
-    ap.add_argument("--top-k", type=int, default=1)
-    ap.add_argument("--prenorm", action="store_true",
-                    help="the paper's wiring (Sec. 4.1): hand over pre-norm hidden states; the library applies the "
-                         "final RMS normalisation for the LM head and the judge reads the hidden states")
-    ap.add_argument("--calibration-copy-mib", type=int, default=0,
-                    help="also run one plain device copy of this many MiB before the timed region, so that "
-                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the verification head is built and measured on a "
-              "single MI355X; no collectives exist). Re-run with --gpus 1.", file=sys.stderr)
-        return 2
-
+def measure(name: str, args, *, cpu_baseline: bool, spread: bool) -> dict:
+    """Build one workload in HBM, time K verify calls on it, check the outputs against the oracle on a bounded
+    sample, and return its record."""
     import torch
 
     from paper_2501_19309_amd import binding as jb, harness
     from synth import CONFIGS, make_inputs
 
-    jb.load_library()  # no fallback: raises when the HIP library is not built
-    assert torch.cuda.is_available(), "bench.py needs a HIP device"
-    shape = CONFIGS[args.config]
+    shape = CONFIGS[name]
     B, M, d, V = shape.B, shape.M, shape.d, shape.V
     R = B * (M + 1)
 
@@ -131,19 +115,21 @@ def main() -> int:
     ms_events = (time.perf_counter() - t0) * 1e3 / K
     kernel_ms, n_prof = ver.profile_end()
 
-    # spread of single calls: an event pair around each of (up to 200) further calls on the same stream
-    n_spread = min(K, 200)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_spread)]
-    torch.cuda.synchronize()
-    for a_ev, b_ev in ev:
-        a_ev.record()
-        step()
-        b_ev.record()
-    torch.cuda.synchronize()
-    call_ms = sorted(a_ev.elapsed_time(b_ev) for a_ev, b_ev in ev)
-    pct = lambda q: call_ms[min(len(call_ms) - 1, int(q * len(call_ms)))]
-    call_spread = {"n": n_spread, "min": call_ms[0], "p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "max": call_ms[-1]}
-    log(f"[bench] ms/step {ms_per_step:.4f} (with per-kernel events {ms_events:.4f}); kernels {kernel_ms}")
+    call_spread = None
+    if spread:
+        # spread of single calls: an event pair around each of (up to 200) further calls on the same stream
+        n_spread = min(K, 200)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_spread)]
+        torch.cuda.synchronize()
+        for a_ev, b_ev in ev:
+            a_ev.record()
+            step()
+            b_ev.record()
+        torch.cuda.synchronize()
+        call_ms = sorted(a_ev.elapsed_time(b_ev) for a_ev, b_ev in ev)
+        pct = lambda q: call_ms[min(len(call_ms) - 1, int(q * len(call_ms)))]
+        call_spread = {"n": n_spread, "min": call_ms[0], "p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "max": call_ms[-1]}
+    log(f"[bench] {shape.name}: ms/step {ms_per_step:.4f} (with per-kernel events {ms_events:.4f}); kernels {kernel_ms}")
 
     got = out.to_numpy()
     elem = {"bf16": 2, "fp8": 2, "int8": 2, "f32": 4}[shape.dtype]      # embeddings / judge weight
@@ -152,14 +138,16 @@ def main() -> int:
     x_bytes = R * d * elem
     lm_ms = kernel_ms["lmhead"]
     flops = 2.0 * R * d * V
-    if args.config in ("C5", "C5q"):  # MFMA-bound regime
+    traffic, traffic_source = MEASURED_TRAFFIC.get(name, (None, None))
+    if name in MFMA_BOUND:
         achieved = flops / (lm_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)}
+                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic}
     else:
         achieved = (w_bytes + x_bytes) / (lm_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)}
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic}
+    roofline["traffic_source"] = traffic_source
     if not args.no_device_probe:
         # what this device itself sustains, measured right after the timed region (outside it): a loop of
         # nothing but independent bf16 MFMAs on N(0,1)-like operands, resp. a pure streaming read of 4 GiB.
@@ -213,45 +201,110 @@ def main() -> int:
         except Exception:
             blas_threads = 1
         cores = len(os.sched_getaffinity(0))
-        # bounded sample: whole call when B == 1, else the first sequences up to ~26 rows
-        seqs = list(range(B)) if R <= 32 else list(range(max(1, 26 // (M + 1))))
+        # bounded sample: whole call when B == 1, else sequences spread over the batch, up to ~26 rows
+        n_seq = B if R <= 32 else max(1, 26 // (M + 1))
+        seqs = list(range(B)) if n_seq == B else sorted({(i * (B - 1)) // max(1, n_seq - 1) for i in range(n_seq)})
         okw = {} if args.rule == "sampling" else {"rule": vo.RULE_TOPK, "top_k": args.top_k}
         if args.prenorm:
             okw["emb_judge"] = x["hidden"]
+        emb_ref = [None]
 
         def oracle_call():
-            emb_ref = vo.rmsnorm_rows(x["hidden"], x["gamma"], x["rms_eps"])[0] if args.prenorm else x["emb"]
-            return vo.verify(emb_ref, x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
+            emb_ref[0] = vo.rmsnorm_rows(x["hidden"], x["gamma"], x["rms_eps"])[0] if args.prenorm else x["emb"]
+            return vo.verify(emb_ref[0], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"],
                              seqs=seqs, w_scale=x.get("w_scale"), **okw)
 
-        # the oracle as it stands, repeated on the same sample until about 10 s of CPU work have been timed
+        # the oracle as it stands; for the cpu_baseline repeated on the same sample until about 10 s of CPU work
+        # have been timed (the secondary workloads run it once, for the parity check only)
         t0 = time.perf_counter()
         ref = oracle_call()
         t_first = time.perf_counter() - t0
-        reps = 1 + max(0, min(15, int(10.0 / max(t_first, 1e-3)) - 1))
-        for _ in range(reps - 1):
-            oracle_call()
-        t_cpu = (time.perf_counter() - t0) / reps
-        record["cpu_baseline"] = {
-            "value": len(seqs) * M / t_cpu, "unit": "positions/s", "cores": min(cores, blas_threads),
-            "kind": "oracle", "seconds": t_cpu * reps, "calls_timed": reps,
-            "sample": (f"{reps} x the oracle's verify call on {len(seqs)} of the {B} sequences of the same workload "
-                       f"({len(seqs) * (M + 1)} rows, all {V} vocabulary entries), float64 numpy"),
-        }
+        if cpu_baseline:
+            reps = 1 + max(0, min(15, int(10.0 / max(t_first, 1e-3)) - 1))
+            for _ in range(reps - 1):
+                oracle_call()
+            t_cpu = (time.perf_counter() - t0) / reps
+            record["cpu_baseline"] = {
+                "value": len(seqs) * M / t_cpu, "unit": "positions/s", "cores": min(cores, blas_threads),
+                "kind": "oracle", "seconds": t_cpu * reps, "calls_timed": reps,
+                "sample": (f"{reps} x the oracle's verify call on {len(seqs)} of the {B} sequences of the same workload "
+                           f"({len(seqs) * (M + 1)} rows, all {V} vocabulary entries), float64 numpy"),
+            }
         sub = {k: v[seqs] for k, v in got.items()}
+        step7 = {k: okw[k] for k in ("rule",) if k in okw}
+        replay = lambda b, m: vo.new_token_for_prefix(emb_ref[0], x["W"], x["draft_logits"], x["uniforms"], seqs[b], m,
+                                                      w_scale=x.get("w_scale"), **step7)
         try:
-            rep = compare(sub, ref, rule_topk=(args.rule == "topk"))
-            record["parity"] = {"ok": True, **{k: v for k, v in rep.items()}}
+            rep = compare(sub, ref, rule_topk=(args.rule == "topk"), replay=replay)
+            record["parity"] = {"ok": True, "sequences_checked": seqs if len(seqs) <= 8 else len(seqs),
+                                **{k: v for k, v in rep.items()}}
         except AssertionError as e:
             record["parity"] = {"ok": False, "error": str(e)[:300]}
 
     ver.destroy()
-    parity_failed = record.get("parity", {}).get("ok") is False
-    if parity_failed:   # a head that no longer matches the oracle delivers no headline number
+    del dev, out, ver
+    torch.cuda.empty_cache()
+    return record
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "C2q", "C3q", "C4q", "C5q", "C2i", "C3i", "C4i", "C5i"],
+                    help="C2..C5: bf16 W_lm (C4 is the headline); C2q..C5q: the same shapes with FP8 E4M3 W_lm; "
+                         "C2i..C5i: with INT8 W_lm")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle (no cpu_baseline, no parity check)")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="headline workload only: do not measure C5, C2 and C3 after it")
+    ap.add_argument("--no-device-probe", action="store_true",
+                    help="skip the measurement of the device's own MFMA / HBM-read rate after the timed region")
+    ap.add_argument("--rule", default="sampling", choices=["sampling", "topk"],
+                    help="acceptance rule: Eq. 4 speculative sampling, or top-K verification (Sec. 5 baseline)")
+    ap.add_argument("--top-k", type=int, default=1)
+    ap.add_argument("--prenorm", action="store_true",
+                    help="the paper's wiring (Sec. 4.1): hand over pre-norm hidden states; the library applies the "
+                         "final RMS normalisation for the LM head and the judge reads the hidden states")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB before the timed region, so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the verification head is built and measured on a "
+              "single MI355X; no collectives exist). Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2501_19309_amd import binding as jb
+
+    jb.load_library()  # no fallback: raises when the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a HIP device"
+
+    record = measure(args.config, args, cpu_baseline=True, spread=True)
+    failed = record.get("parity", {}).get("ok") is False
+
+    plain = args.rule == "sampling" and not args.prenorm and args.calibration_copy_mib == 0
+    if args.config == "C4" and plain and not args.no_secondary:
+        secondary = []
+        for name in SECONDARY:
+            r = measure(name, args, cpu_baseline=False, spread=False)
+            failed = failed or r.get("parity", {}).get("ok") is False
+            secondary.append({
+                "workload": r["config"]["workload"], "rows": r["config"]["rows"],
+                "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"],
+                "kernel_ms": r["whole_call"]["kernel_ms"], "roofline": r["roofline"],
+                "whole_call_frac_hbm_peak": r["whole_call"]["frac_hbm_peak"], "parity": r.get("parity"),
+            })
+        record["secondary"] = secondary
+
+    if failed:   # a head that no longer matches the oracle delivers no headline number
         record["invalid"] = "parity check against the oracle failed"
         record["value_unchecked"], record["value"] = record["value"], None
     print(json.dumps(record))
-    return 3 if parity_failed else 0
+    return 3 if failed else 0
 
 
 if __name__ == "__main__":

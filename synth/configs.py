@@ -72,6 +72,7 @@ CONFIGS: Dict[str, VerifyShape] = {
     "C2i": VerifyShape("C2i", 1, 5, 4096, 128256, "int8", 1.5, "Llama-3.1-8B-shaped head, INT8 W_lm"),
     "C3i": VerifyShape("C3i", 1, 25, 8192, 128256, "int8", 1.0, "Llama-3.1-70B-shaped head, INT8 W_lm"),
     "C4i": VerifyShape("C4i", 1, 25, 16384, 128256, "int8", 2.0, "Llama-3.1-405B-shaped head, INT8 W_lm"),
+    "C5i": VerifyShape("C5i", 64, 10, 8192, 128256, "int8", (0.5, 2.5), "batched verification, INT8 W_lm"),
 }
 
 
