@@ -84,8 +84,8 @@ extern "C" {
 /* kernels whose durations jd_verify_profile_end() reports */
 #define JD_K_LMHEAD    0              /* LM-head contraction + per-tile softmax partials              */
 #define JD_K_DRAFTSTAT 1              /* draft-logit row statistics                                   */
-#define JD_K_ACCEPT    2              /* combine, judge, accept tests, ballot, accepted prefix        */
-#define JD_K_SAMPLER   3              /* residual / bonus inverse-CDF sampler (both passes)           */
+#define JD_K_ACCEPT    2              /* second softmax pass, judge, the two accept tests per slot    */
+#define JD_K_SAMPLER   3              /* mask OR, ballot, accepted prefix, inverse-CDF sampler        */
 #define JD_NUM_KERNELS 4
 
 typedef struct jd_verify_ctx jd_verify_ctx;   /* opaque, owned by the library */

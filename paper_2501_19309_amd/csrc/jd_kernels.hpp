@@ -189,11 +189,13 @@ struct AcceptArgs {
   float* t_max; float* t_sum;          // [R]
   float* q_max; float* q_sum;          // [B*M]
   float* g;                            // [B*M] judge logits
+  uint8_t* zflags;                     // [R] test bits and error flags of every slot, for the sampler kernels
   // outputs
-  int32_t* accept_len; uint32_t* status;
   uint8_t* z_stand; uint8_t* z_judge;
   float* p_at; float* q_at; float* judge_logit; float* row_max; float* row_sumexp;
 };
+// Second softmax pass, judge, both accept tests per slot (one launch; the OR, the ballot and the prefix cut are
+// done by the sampler / argmax kernels from zflags).
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);
 
 struct SamplerArgs {
@@ -204,9 +206,9 @@ struct SamplerArgs {
   const float* D; int draft_rows;
   const float* uniforms;
   const float* t_max; const float* t_sum; const float* q_max; const float* q_sum;
-  const int32_t* accept_len;
+  const uint8_t* zflags; int mode_judge;   // per-slot test bits of launch_accept; z = stand OR (mode_judge AND judge)
   double* chunk_mass; int nChunk;      // [B][nChunk]
-  int32_t* next_token; uint32_t* status;
+  int32_t* accept_len; int32_t* next_token; uint32_t* status;   // outputs: prefix, new token, JD_STATUS_* bits
 };
 constexpr int kSamplerChunk = 1024;     // tokens per sampler chunk
 hipError_t launch_sampler(const SamplerArgs& a, hipStream_t st);
@@ -217,10 +219,12 @@ constexpr int kRankSplits = 16;
 hipError_t launch_rank(const float* L, int Lld, const int32_t* tokens, int B, int M, int V, int* rankpart,
                        hipStream_t st);
 
-// Greedy new token for the top-K rule: next_token[b] = lowest id attaining the maximum of row
-// accept_len[b] of the target logits.  `chunk_arg` is [B][nChunk] ints of scratch.
-hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const int32_t* accept_len, int B, int M,
-                         int V, int* chunk_arg, int nChunk, int32_t* next_token, hipStream_t st);
+// Greedy new token for the top-K rule: accepted prefix from zflags (written to accept_len, status), then
+// next_token[b] = lowest id attaining the maximum of that row of the target logits.  `chunk_arg` is
+// [B][nChunk] ints of scratch.
+hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const uint8_t* zflags, int mode_judge,
+                         int32_t* accept_len, uint32_t* status, int B, int M, int V, int* chunk_arg, int nChunk,
+                         int32_t* next_token, hipStream_t st);
 
 // Final RMS normalisation of R rows of d values (Sec. 4.1: the LM head reads the embedding after it):
 // Xn[r][k] = round(H[r][k] * gamma[k] / sqrt(mean_k H[r][k]^2 + eps)), float64 arithmetic, one

@@ -30,6 +30,7 @@ struct jd_verify_ctx {
   float* t_max; float* t_sum; float* q_max; float* q_sum; float* g;
   double* chunk_mass;   // [max_B][nChunk] (the top-K rule reuses it as ints)
   int* rankpart;        // [max_B*max_M][kRankSplits], top-K rule only
+  uint8_t* zflags;      // [maxR] per-slot test bits and error flags (row kernel -> sampler kernels)
   void* Xp;             // packed embeddings for the GEMM regime
   void* Xn;             // [max_R][d] normalised embeddings of the pre-norm entry point
   void* pool;           // one allocation behind tpart .. rankpart (see create)
@@ -226,6 +227,7 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
     const size_t o_g = take(maxS * sizeof(float));
     const size_t o_cm = take((size_t)cfg->max_B * c->nChunk * sizeof(double));
     const size_t o_rank = take(topk ? maxS * (size_t)kRankSplits * sizeof(int) : 0);
+    const size_t o_zf = take(maxR);
     uint8_t* pool = nullptr;
     rc = dev_alloc(c, &pool, off);
     c->pool = pool;
@@ -237,6 +239,7 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
       c->g = reinterpret_cast<float*>(pool + o_g);
       c->chunk_mass = reinterpret_cast<double*>(pool + o_cm);
       c->rankpart = topk ? reinterpret_cast<int*>(pool + o_rank) : nullptr;
+      c->zflags = pool + o_zf;
     }
   }
   if (rc == JD_OK && (fp8 || int8)) {
@@ -401,7 +404,7 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
                            c->dpart, st));
   if (ev) JD_HIP(hipEventRecord(ev[2], st));
 
-  // steps 3-6: accept tests, judge, OR, accepted prefix
+  // steps 3, 4 (and the second softmax pass): per-slot accept tests and judge
   const bool topk = cfg.rule == JD_RULE_TOPK;
   if (topk) JD_HIP(launch_rank(c->L, g.Vpad, d_draft_tokens, B, M, cfg.V, c->rankpart, st));
   AcceptArgs a;
@@ -418,24 +421,24 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
   a.tokens = d_draft_tokens; a.uniforms = d_uniforms;
   a.emb_judge = d_emb_judge ? d_emb_judge : d_emb; a.w_judge = c->wj;
   a.t_max = c->t_max; a.t_sum = c->t_sum; a.q_max = c->q_max; a.q_sum = c->q_sum; a.g = c->g;
-  a.accept_len = out->d_accept_len; a.status = out->d_status;
+  a.zflags = c->zflags;
   a.z_stand = out->d_z_stand; a.z_judge = out->d_z_judge;
   a.p_at = out->d_p_at_draft; a.q_at = out->d_q_at_draft; a.judge_logit = out->d_judge_logit;
   a.row_max = out->d_row_max; a.row_sumexp = out->d_row_sumexp;
   JD_HIP(launch_accept(a, st));
   if (ev) JD_HIP(hipEventRecord(ev[3], st));
 
-  // step 7: replacement / bonus token
+  // steps 5-7: OR of the masks, accepted prefix, replacement / bonus token
   SamplerArgs s;
   s.B = B; s.M = M; s.V = cfg.V; s.draft_is_logits = logits;
   s.L = c->L; s.Lld = g.Vpad; s.D = d_draft; s.draft_rows = draft_rows; s.uniforms = d_uniforms;
   s.t_max = c->t_max; s.t_sum = c->t_sum; s.q_max = c->q_max; s.q_sum = c->q_sum;
-  s.accept_len = out->d_accept_len;
+  s.zflags = c->zflags; s.mode_judge = cfg.mode == JD_MODE_JUDGE;
   s.chunk_mass = c->chunk_mass; s.nChunk = c->nChunk;
-  s.next_token = out->d_next_token; s.status = out->d_status;
+  s.accept_len = out->d_accept_len; s.next_token = out->d_next_token; s.status = out->d_status;
   s.resample_target = cfg.resample == JD_RESAMPLE_TARGET;
   if (topk) {
-    JD_HIP(launch_argmax(c->L, g.Vpad, c->t_max, out->d_accept_len, B, M, cfg.V,
+    JD_HIP(launch_argmax(c->L, g.Vpad, c->t_max, c->zflags, s.mode_judge, out->d_accept_len, out->d_status, B, M, cfg.V,
                          reinterpret_cast<int*>(c->chunk_mass), c->nChunk, out->d_next_token, st));
   } else {
     JD_HIP(launch_sampler(s, st));
@@ -502,6 +505,7 @@ extern "C" int jd_verify_run_noalloc(const jd_verify_config* cfg, const void* d_
   const size_t o_g = take(S * sizeof(float));
   const size_t o_cm = take((size_t)B * nChunk * sizeof(double));
   const size_t o_rank = take(topk ? S * (size_t)kRankSplits * sizeof(int) : 0);
+  const size_t o_zf = take(R);
   if (off > (size_t)JD_NOALLOC_SCRATCH_BYTES) {
     std::snprintf(g_detail, sizeof g_detail, "jd_verify_run_noalloc: this call needs %zu bytes of workspace, the "
                   "static scratch array holds %zu", off, (size_t)JD_NOALLOC_SCRATCH_BYTES);
@@ -534,6 +538,7 @@ extern "C" int jd_verify_run_noalloc(const jd_verify_config* cfg, const void* d_
   c.g = reinterpret_cast<float*>(base + o_g);
   c.chunk_mass = reinterpret_cast<double*>(base + o_cm);
   c.rankpart = topk ? reinterpret_cast<int*>(base + o_rank) : nullptr;
+  c.zflags = base + o_zf;
   c.nPartT = kF32Splits; c.nPartD = kDraftSplits; c.nChunk = nChunk;
   c.bytes = 0;
   c.judge_threshold = judge_threshold_of(cfg->delta);

@@ -106,8 +106,8 @@ __device__ __forceinline__ void rowstats_block(const RowStatsArgs& a, int row, i
 }
 
 // Judge logit of draft slot blk = b*M + j:  g = w_judge . e[b, j+1, :] + bias  (Sec. 4.1; App. B.1).
-// 256 threads; thread 0 writes a.g[blk].
-__device__ __forceinline__ void judge_block(const JudgeArgs& a, int blk, float* redf /*[4]*/) {
+// 256 threads; thread 0 writes a.g[blk] and returns it (other threads return 0).
+__device__ __forceinline__ float judge_block(const JudgeArgs& a, int blk, float* redf /*[4]*/) {
   const int tid = threadIdx.x;
   const int b = blk / a.M, j = blk % a.M;
   const size_t e0 = ((size_t)b * (a.M + 1) + j + 1) * a.d;
@@ -125,7 +125,12 @@ __device__ __forceinline__ void judge_block(const JudgeArgs& a, int blk, float* 
   for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
   if ((tid & 63) == 0) redf[tid >> 6] = acc;
   __syncthreads();
-  if (tid == 0) a.g[blk] = (redf[0] + redf[1]) + (redf[2] + redf[3]) + a.bias;
+  float g = 0.f;
+  if (tid == 0) {
+    g = (redf[0] + redf[1]) + (redf[2] + redf[3]) + a.bias;
+    a.g[blk] = g;
+  }
+  return g;
 }
 
 // Workgroups [0, nStatBlocks) do row statistics, [nStatBlocks, nStatBlocks + nJudgeBlocks) judge dots.
@@ -133,7 +138,7 @@ __device__ __forceinline__ void side_work_block(const SideWork& w, int blk, void
   if (blk < w.nStatBlocks) {
     rowstats_block(w.stats, blk / w.stats.nSplit, blk % w.stats.nSplit, static_cast<MS*>(smem16));
   } else if (blk - w.nStatBlocks < w.nJudgeBlocks) {
-    judge_block(w.judge, blk - w.nStatBlocks, static_cast<float*>(smem16));
+    (void)judge_block(w.judge, blk - w.nStatBlocks, static_cast<float*>(smem16));
   }
 }
 

@@ -34,13 +34,9 @@ hipError_t launch_rowstats(const float* base, int nRows, int rowsUsed, size_t se
 
 // ------------------------------------------------------------------------------- accept
 
-// Second pass of the two-pass vocabulary softmax and the judge head, one workgroup per
-// row so that the work spreads over the chip:
-//   blocks [0, R)        combine the LM-head partials of target row r  -> t_max, t_sum
-//   blocks [R, R+S)      combine the partials of draft row (b, j)      -> q_max, q_sum
-//   blocks [R+S, R+2S)   judge logit g = w_judge . e[b, j+1] + bias    (Sec. 4.1; App. B.1),
-//                        unless they were already computed beside the LM head
-// with R = B*(M+1), S = B*M.
+// Per-slot flags handed from the row kernel to the sampler kernels: zflags[b*(M+1) + r].
+constexpr uint8_t kZStand = 1, kZJudge = 2, kZBadToken = 4, kZNan = 8;
+
 // One thread's share (every 256th) of n (max, sum exp) partials.  The partials were written by another
 // kernel and come from HBM, so eight loads are put in flight before anything is combined, and a batch
 // is combined around its common maximum (independent exps, no serial chain).
@@ -71,96 +67,113 @@ __device__ __forceinline__ MS combine_partials(const float2* __restrict__ p, int
   return st;
 }
 
-__global__ __launch_bounds__(256) void reduce_rows_kernel(AcceptArgs a) {
+// Second pass of the two-pass vocabulary softmax, the judge head and the two accept tests, one workgroup per
+// target row (b, r) so that the work spreads over the chip:
+//   all rows      combine the LM-head partials of the row                     -> t_max, t_sum
+//   rows r < M    (= draft slot j = r) combine the partials of draft row j    -> q_max, q_sum
+//                 judge logit g = w_judge . e[b, j+1] + bias (Sec. 4.1; App. B.1), unless it was already
+//                 computed beside the LM head
+//                 standard test eps*q[c] < p[c] (Eq. 4; or the top-K rule of Sec. 5), judge test g > logit(delta)
+// The two test bits and the slot's error flags go to zflags[b*(M+1) + r]; the sampler kernels OR them, ballot
+// and cut the prefix.  The gathers of L[c] and D[c] are requested first, so that they travel while the
+// partials are combined.
+__global__ __launch_bounds__(256) void rows_kernel(AcceptArgs a) {
   __shared__ MS red[4];
   __shared__ float redf[4];
   const int tid = threadIdx.x;
-  const int R = a.B * (a.M + 1), S = a.B * a.M;
-  int blk = blockIdx.x;
-  if (blk < R) {
-    MS st = combine_partials(a.tpart + (size_t)blk * a.nPartT, a.nPartT, tid);
-    st = ms_block_reduce(st, red);
-    if (tid == 0) {
-      a.t_max[blk] = st.m; a.t_sum[blk] = st.s;
-      if (a.row_max) a.row_max[blk] = st.m;
-      if (a.row_sumexp) a.row_sumexp[blk] = st.s;
+  const int M = a.M, Mp1 = a.M + 1;
+  const int row = blockIdx.x;          // b*(M+1) + r
+  const int b = row / Mp1, r = row % Mp1;
+  const int slot = b * M + r;          // meaningful for r < M
+  const bool has_slot = r < M;
+
+  int c = -1;
+  float l_c = 0.f, d_c = 0.f, u = 0.f;
+  bool tok_ok = false;
+  if (has_slot && tid == 0) {
+    c = a.tokens[slot];
+    tok_ok = c >= 0 && c < a.V;
+    if (tok_ok) {
+      l_c = a.L[(size_t)row * a.Lld + c];
+      d_c = a.D[((size_t)b * a.draft_rows + r) * a.V + c];
     }
+    u = a.uniforms[b * Mp1 + r];
+  }
+
+  MS t = combine_partials(a.tpart + (size_t)row * a.nPartT, a.nPartT, tid);
+  t = ms_block_reduce(t, red);
+  if (tid == 0) {
+    a.t_max[row] = t.m; a.t_sum[row] = t.s;
+    if (a.row_max) a.row_max[row] = t.m;
+    if (a.row_sumexp) a.row_sumexp[row] = t.s;
+  }
+  if (!has_slot) {
+    if (tid == 0) a.zflags[row] = isnan(t.s) ? kZNan : 0;
     return;
   }
-  blk -= R;
-  if (blk < S) {
-    if (!a.draft_is_logits) return;
-    MS st = combine_partials(a.dpart + (size_t)blk * a.nPartD, a.nPartD, tid);
-    st = ms_block_reduce(st, red);
-    if (tid == 0) { a.q_max[blk] = st.m; a.q_sum[blk] = st.s; }
-    return;
+
+  MS q{0.f, 1.f};
+  if (a.draft_is_logits) {
+    __syncthreads();  // red is reused
+    q = combine_partials(a.dpart + (size_t)slot * a.nPartD, a.nPartD, tid);
+    q = ms_block_reduce(q, red);
+    if (tid == 0) { a.q_max[slot] = q.m; a.q_sum[slot] = q.s; }
   }
-  blk -= S;
-  if (a.judge_done) return;  // judge logits were computed beside the LM head
-  JudgeArgs ja;
-  ja.emb_judge = a.emb_judge; ja.w_judge = a.w_judge; ja.emb_is_bf16 = a.emb_is_bf16;
-  ja.d = a.d; ja.M = a.M; ja.bias = a.judge_bias; ja.g = a.g;
-  judge_block(ja, blk, redf);
+  float g;
+  if (a.judge_done) {
+    g = (tid == 0) ? a.g[slot] : 0.f;  // computed beside the LM head
+  } else {
+    JudgeArgs ja;
+    ja.emb_judge = a.emb_judge; ja.w_judge = a.w_judge; ja.emb_is_bf16 = a.emb_is_bf16;
+    ja.d = a.d; ja.M = a.M; ja.bias = a.judge_bias; ja.g = a.g;
+    g = judge_block(ja, slot, redf);   // valid on thread 0
+  }
+  if (tid != 0) return;
+
+  bool zs = false, zj = false;
+  float p_c = 0.f, q_c = 0.f;
+  uint8_t flags = 0;
+  if (tok_ok) {
+    p_c = expf(l_c - t.m) / t.s;
+    q_c = a.draft_is_logits ? expf(d_c - q.m) / q.s : d_c;
+    if (a.rule_topk) {  // Sec. 5: among the top_k most probable tokens of p
+      int rank = 0;
+      for (int s = 0; s < a.nRankSplit; ++s) rank += a.rankpart[(size_t)slot * a.nRankSplit + s];
+      zs = rank < a.top_k;
+    } else {
+      zs = u * q_c < p_c;   // Eq. 4, division-free and strict
+    }
+    zj = g > a.judge_threshold;
+  } else {
+    flags |= kZBadToken;
+  }
+  if (isnan(g) || isnan(t.s) || isnan(q.s) || isnan(q_c)) flags |= kZNan;
+  a.zflags[row] = flags | (zs ? kZStand : 0) | (zj ? kZJudge : 0);
+  if (a.z_stand) a.z_stand[slot] = zs;
+  if (a.z_judge) a.z_judge[slot] = zj;
+  if (a.p_at) a.p_at[slot] = p_c;
+  if (a.q_at) a.q_at[slot] = q_c;
+  if (a.judge_logit) a.judge_logit[slot] = g;
 }
 
-// One wavefront per sequence, lane j = draft slot j: standard test eps*q[c] < p[c] (Eq. 4),
-// judge test g > logit(delta), OR of the two masks (Sec. 4.1), then one wavefront ballot
-// whose trailing ones are the accepted prefix (Eq. 4; App. B.2, Fig. 8).
-__global__ __launch_bounds__(64) void accept_kernel(AcceptArgs a) {
-  const int b = blockIdx.x;
-  const int j = threadIdx.x;
-  const int M = a.M, Mp1 = a.M + 1;
-  bool z = false;
-  uint32_t flags = 0;
-  if (j < M) {
-    const int c = a.tokens[b * M + j];
-    const float g = a.g[b * M + j];
-    const float tm = a.t_max[b * Mp1 + j], ts = a.t_sum[b * Mp1 + j];
-    const float qm = a.draft_is_logits ? a.q_max[b * M + j] : 0.f;
-    const float qs = a.draft_is_logits ? a.q_sum[b * M + j] : 1.f;
-    bool zs = false, zj = false;
-    float p_c = 0.f, q_c = 0.f;
-    if (c >= 0 && c < a.V) {
-      const float l = a.L[(size_t)(b * Mp1 + j) * a.Lld + c];
-      p_c = expf(l - tm) / ts;
-      const float dv = a.D[((size_t)b * a.draft_rows + j) * a.V + c];
-      q_c = a.draft_is_logits ? expf(dv - qm) / qs : dv;
-      if (a.rule_topk) {  // Sec. 5: among the top_k most probable tokens of p
-        int rank = 0;
-        for (int s = 0; s < a.nRankSplit; ++s) rank += a.rankpart[(size_t)(b * M + j) * a.nRankSplit + s];
-        zs = rank < a.top_k;
-      } else {
-        zs = a.uniforms[b * Mp1 + j] * q_c < p_c;
-      }
-      zj = g > a.judge_threshold;
-    } else {
-      flags |= 1u;  // bad token id
-    }
-    if (isnan(g) || isnan(ts) || isnan(qs) || isnan(q_c)) flags |= 2u;
-    z = zs || (a.mode_judge && zj);
-    if (a.z_stand) a.z_stand[b * M + j] = zs;
-    if (a.z_judge) a.z_judge[b * M + j] = zj;
-    if (a.p_at) a.p_at[b * M + j] = p_c;
-    if (a.q_at) a.q_at[b * M + j] = q_c;
-    if (a.judge_logit) a.judge_logit[b * M + j] = g;
-  }
-  if (j == M && isnan(a.t_sum[b * Mp1 + M])) flags |= 2u;
+// z = z_stand OR z_judge (Sec. 4.1), one wavefront ballot whose trailing ones are the accepted prefix (Eq. 4;
+// App. B.2, Fig. 8), and the OR of the sequence's error flags as JD_STATUS_* bits.  Every lane of the calling
+// wavefront gets both results; M <= 63, so lanes 0..M hold the M slots and the bonus row.
+__device__ __forceinline__ int prefix_from_flags(const uint8_t* __restrict__ zflags, int b, int M, int mode_judge,
+                                                 uint32_t* status) {
+  const int lane = threadIdx.x & 63;
+  const uint8_t f = (lane <= M) ? zflags[b * (M + 1) + lane] : (uint8_t)0;
+  const bool z = lane < M && ((f & kZStand) || (mode_judge && (f & kZJudge)));
   const unsigned long long mask = __ballot(z);
-  const int mstar = __ffsll((long long)~mask) - 1;  // lanes >= M vote 0, so mstar <= M
+  uint32_t st = ((f & kZBadToken) ? 1u : 0u) | ((f & kZNan) ? 2u : 0u);
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) flags |= __shfl_xor(flags, o);
-  if (j == 0) {
-    a.accept_len[b] = mstar;
-    a.status[b] = flags;
-  }
+  for (int o = 32; o > 0; o >>= 1) st |= __shfl_xor(st, o);
+  *status = st;
+  return __ffsll((long long)~mask) - 1;  // lanes >= M vote 0, so the result is <= M
 }
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
-  const int R = a.B * (a.M + 1), S = a.B * a.M;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(R + S + (a.judge_done ? 0 : S)), dim3(256), 0, st, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(accept_kernel, dim3(a.B), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(rows_kernel, dim3(a.B * (a.M + 1)), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -213,9 +226,8 @@ __device__ __forceinline__ void mass4(const MassRow& row, int v0, int V, double 
   }
 }
 
-__device__ __forceinline__ MassRow make_mass_row(const SamplerArgs& a, int b, bool plain) {
+__device__ __forceinline__ MassRow make_mass_row(const SamplerArgs& a, int b, int m, bool plain) {
   const int Mp1 = a.M + 1;
-  const int m = a.accept_len[b];
   MassRow r;
   r.l = a.L + (size_t)(b * Mp1 + m) * a.Lld;
   r.tm = a.t_max[b * Mp1 + m];
@@ -254,7 +266,10 @@ __device__ __forceinline__ double chunk_sum(const MassRow& row, int chunk, int V
 __global__ __launch_bounds__(256) void sampler_mass_kernel(SamplerArgs a) {
   __shared__ double red[256];
   const int b = blockIdx.x / a.nChunk, chunk = blockIdx.x % a.nChunk;  // 1-D grid: B is not bounded by 65535
-  const MassRow row = make_mass_row(a, b, false);
+  uint32_t status;
+  const int m = prefix_from_flags(a.zflags, b, a.M, a.mode_judge, &status);  // steps 5, 6, in every wavefront
+  if (chunk == 0 && threadIdx.x == 0) { a.accept_len[b] = m; a.status[b] = status; }
+  const MassRow row = make_mass_row(a, b, m, false);
   const double s = chunk_sum(row, chunk, a.V, red);
   if (threadIdx.x == 0) a.chunk_mass[(size_t)b * a.nChunk + chunk] = s;
 }
@@ -318,20 +333,22 @@ __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
   const int b = blockIdx.x, tid = threadIdx.x;
   double* cm = a.chunk_mass + (size_t)b * a.nChunk;
 
-  // Requested before the first barrier, so that these two levels of dependent loads (accepted prefix,
-  // then the statistics of its row) travel while the chunk masses are summed.
-  MassRow row = make_mass_row(a, b, false);
+  // Requested before the first barrier, so that these two levels of dependent loads (the slot flags that give
+  // the accepted prefix, then the statistics of its row) travel while the chunk masses are summed.
+  uint32_t status_unused;
+  const int m = prefix_from_flags(a.zflags, b, a.M, a.mode_judge, &status_unused);
+  MassRow row = make_mass_row(a, b, m, false);
   const float u_s = a.uniforms[b * (a.M + 1) + a.M];
 
   double S = total_chunk_mass(cm, a.nChunk, red);
   const bool plain = !(S > 0.0);
-  if (tid == 0 && S == 0.0 && a.accept_len[b] < a.M && !a.resample_target) atomicOr(&a.status[b], 4u);
+  if (tid == 0 && S == 0.0 && m < a.M && !a.resample_target) atomicOr(&a.status[b], 4u);
   // a NaN in the sampled row (target or draft: with draft probabilities nothing else has looked at the
   // whole draft row) must not disappear behind the fallback to p below
   if (tid == 0 && !(S == S)) atomicOr(&a.status[b], 2u);
   if (plain) {
     // No residual mass (q == p at the cut), or NaN: recompute the chunk masses from p itself.
-    const MassRow prow = make_mass_row(a, b, true);
+    const MassRow prow = make_mass_row(a, b, m, true);
     for (int ch = 0; ch < a.nChunk; ++ch) {
       const double s = chunk_sum(prow, ch, a.V, red);
       if (tid == 0) cm[ch] = s;
@@ -484,11 +501,16 @@ hipError_t launch_rank(const float* L, int Lld, const int32_t* tokens, int B, in
 // grid = (nChunk, B): lowest id in the chunk whose logit equals the row maximum (INT_MAX if none).
 __global__ __launch_bounds__(256) void argmax_chunk_kernel(const float* __restrict__ L, int Lld,
                                                             const float* __restrict__ t_max,
-                                                            const int32_t* __restrict__ accept_len, int M, int V,
+                                                            const uint8_t* __restrict__ zflags, int mode_judge,
+                                                            int32_t* __restrict__ accept_len,
+                                                            uint32_t* __restrict__ status, int M, int V,
                                                             int nChunk, int* __restrict__ chunk_arg) {
   __shared__ int s_min;
   const int b = blockIdx.x / nChunk, chunk = blockIdx.x % nChunk, tid = threadIdx.x;  // 1-D grid, as the sampler's
-  const int r = b * (M + 1) + accept_len[b];
+  uint32_t st;
+  const int m = prefix_from_flags(zflags, b, M, mode_judge, &st);
+  if (chunk == 0 && tid == 0) { accept_len[b] = m; status[b] = st; }
+  const int r = b * (M + 1) + m;
   const float tm = t_max[r];
   const float* row = L + (size_t)r * Lld;
   if (tid == 0) s_min = 0x7fffffff;
@@ -516,11 +538,12 @@ __global__ __launch_bounds__(256) void argmax_pick_kernel(const int* __restrict_
   if (tid == 0) next_token[b] = (s_min == 0x7fffffff) ? 0 : s_min;  // no finite maximum (NaN row): token 0
 }
 
-hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const int32_t* accept_len, int B, int M,
-                         int V, int* chunk_arg, int nChunk, int32_t* next_token, hipStream_t st) {
+hipError_t launch_argmax(const float* L, int Lld, const float* t_max, const uint8_t* zflags, int mode_judge,
+                         int32_t* accept_len, uint32_t* status, int B, int M, int V, int* chunk_arg, int nChunk,
+                         int32_t* next_token, hipStream_t st) {
   if ((size_t)nChunk * (size_t)B > 0x7fffffffULL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(argmax_chunk_kernel, dim3((unsigned)(nChunk * B)), dim3(256), 0, st, L, Lld, t_max, accept_len, M,
-                     V, nChunk, chunk_arg);
+  hipLaunchKernelGGL(argmax_chunk_kernel, dim3((unsigned)(nChunk * B)), dim3(256), 0, st, L, Lld, t_max, zflags,
+                     mode_judge, accept_len, status, M, V, nChunk, chunk_arg);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(argmax_pick_kernel, dim3(B), dim3(256), 0, st, chunk_arg, nChunk, next_token);
