@@ -16,6 +16,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kProbeTiles = 24;  // independent accumulator tiles per wavefront: no MFMA waits for another
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+constexpr int kProbeTiles32 = 6;  // independent 32 x 32 tiles (96 accumulator registers, as the 24 tiles of 16 x 16)
 
 // Several wavefronts per SIMD (the kernel needs about 110 registers), each a loop of nothing but independent
 // MFMAs that accumulate in place (inline assembly: left to the compiler the loop gets register copies and
@@ -46,6 +48,38 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(float* out, int iters, i
 #pragma unroll
   for (int i = 0; i < kProbeTiles; ++i) s += (acc[i][0] + acc[i][1]) + (acc[i][2] + acc[i][3]);
   if (s == 12345.678f) out[blockIdx.x * 256 + threadIdx.x] = s;  // keeps the loop alive; practically never taken
+}
+
+// The same loop on the other bf16 MFMA shape, v_mfma_f32_32x32x16_bf16 (twice the flops per instruction and per
+// operand fragment, four times the accumulator registers per tile), N(0,1)-like operands: which of the two shapes
+// the matrix cores sustain at the higher rate decides the tile shape of the large-row LM-head kernels.
+__global__ __launch_bounds__(256) void mfma_rate_32x32_kernel(float* out, int iters) {
+  f32x16 acc[kProbeTiles32];
+#pragma unroll
+  for (int i = 0; i < kProbeTiles32; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  auto value = [&](unsigned i) -> unsigned {
+    unsigned h = (threadIdx.x * 8u + i + blockIdx.x * 4099u) * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    const float f = (((h & 0xffff) + ((h >> 16) & 0xffff)) * (1.0f / 65536.0f) - 1.0f) * 2.45f;
+    return __float_as_uint(f) >> 16;
+  };
+  auto pair = [&](unsigned i) { return value(2 * i) | (value(2 * i + 1) << 16); };
+  const u32x4 a = {pair(0), pair(1), pair(2), pair(3)};
+  const u32x4 b = {pair(4), pair(5), pair(6), pair(7)};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < kProbeTiles32; ++i)
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
+  }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kProbeTiles32; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s += acc[i][j];
+  if (s == 12345.678f) out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
 // Streaming read: a wavefront reads 32 KiB of consecutive memory per turn as four batches of eight 128-bit
@@ -96,7 +130,7 @@ int fail(hipError_t e) { (void)hipGetLastError(); return e == hipErrorOutOfMemor
 #define JD_TRY(expr) do { const hipError_t e_ = (expr); if (e_ != hipSuccess) { rc = fail(e_); goto done; } } while (0)
 
 extern "C" int jd_verify_probe_mfma_bf16(int32_t device, int32_t operand_mode, double* out_tflops) {
-  if (!out_tflops || device < 0 || (operand_mode != 0 && operand_mode != 1)) return JD_ERR_INVALID_ARG;
+  if (!out_tflops || device < 0 || operand_mode < 0 || operand_mode > 2) return JD_ERR_INVALID_ARG;
   *out_tflops = 0.0;
   int rc = JD_OK;
   float* out = nullptr;
@@ -112,15 +146,21 @@ extern "C" int jd_verify_probe_mfma_bf16(int32_t device, int32_t operand_mode, d
   JD_TRY(hipEventCreate(&e0));
   JD_TRY(hipEventCreate(&e1));
   // some launches first: the clock settles only after tens of milliseconds under this load
-  for (int w = 0; w < 10; ++w) hipLaunchKernelGGL(mfma_rate_kernel, dim3(wgs), dim3(256), 0, nullptr, out, iters, operand_mode);
-  JD_TRY(hipGetLastError());
-  JD_TRY(hipEventRecord(e0, nullptr));
-  for (int w = 0; w < 3; ++w) hipLaunchKernelGGL(mfma_rate_kernel, dim3(wgs), dim3(256), 0, nullptr, out, iters, operand_mode);
+  for (int w = 0; w < 13; ++w) {
+    if (w == 10) JD_TRY(hipEventRecord(e0, nullptr));  // the last three launches are the timed ones
+    if (operand_mode == 2)
+      hipLaunchKernelGGL(mfma_rate_32x32_kernel, dim3(wgs), dim3(256), 0, nullptr, out, iters);
+    else
+      hipLaunchKernelGGL(mfma_rate_kernel, dim3(wgs), dim3(256), 0, nullptr, out, iters, operand_mode);
+  }
   JD_TRY(hipGetLastError());
   JD_TRY(hipEventRecord(e1, nullptr));
   JD_TRY(hipEventSynchronize(e1));
   JD_TRY(hipEventElapsedTime(&ms, e0, e1));
-  *out_tflops = 3.0 * (double)wgs * 4 * iters * kProbeTiles * (2.0 * 16 * 16 * 32) / ((double)ms * 1e-3) / 1e12;
+  {
+    const double flops_per_wave_iter = operand_mode == 2 ? kProbeTiles32 * (2.0 * 32 * 32 * 16) : kProbeTiles * (2.0 * 16 * 16 * 32);
+    *out_tflops = 3.0 * (double)wgs * 4 * iters * flops_per_wave_iter / ((double)ms * 1e-3) / 1e12;
+  }
 done:
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);

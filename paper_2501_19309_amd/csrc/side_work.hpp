@@ -85,11 +85,15 @@ __device__ __forceinline__ void rowstats_block(const RowStatsArgs& a, int row, i
       float mb = -INFINITY;
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) mb = fmaxf(mb, fmaxf(fmaxf(x[u].x, x[u].y), fmaxf(x[u].z, x[u].w)));
-      bool nan = false;
+      if (mb == -INFINITY) {
+        // padding or logits of -inf (probability zero) - or nothing but NaNs, which fmaxf drops: only this rare
+        // case needs a look at every element.  With a finite maximum a NaN reaches the sum through its own exp.
+        bool nan = false;
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) nan = nan || (x[u].x != x[u].x) || (x[u].y != x[u].y) || (x[u].z != x[u].z) || (x[u].w != x[u].w);
-      if (nan) { st.s = NAN; continue; }     // fmaxf drops NaNs: keep them visible in the sum
-      if (mb == -INFINITY) continue;          // padding, or logits of -inf: probability zero
+        for (int u = 0; u < kBatch; ++u) nan = nan || (x[u].x != x[u].x) || (x[u].y != x[u].y) || (x[u].z != x[u].z) || (x[u].w != x[u].w);
+        if (nan) st.s = NAN;
+        continue;
+      }
       if (mb > st.m) { st.s *= __expf(st.m - mb); st.m = mb; }
       float add = 0.f;
 #pragma unroll

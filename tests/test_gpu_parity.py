@@ -767,8 +767,10 @@ def test_device_probes(jd):
     lib = jb.load_library()
     tf = jb.probe_mfma_bf16(0, 1)
     gbs = jb.probe_hbm_read(0, 2 << 30)
-    print(f"[probe] mfma bf16 {tf:.0f} TFLOP/s, hbm read {gbs:.0f} GB/s", flush=True)
+    tf32 = jb.probe_mfma_bf16(0, 2)
+    print(f"[probe] mfma bf16 16x16x32 {tf:.0f} TFLOP/s, 32x32x16 {tf32:.0f} TFLOP/s, hbm read {gbs:.0f} GB/s", flush=True)
     assert 300.0 < tf <= 2600.0 and 1000.0 < gbs <= 8200.0      # below the published peaks, far above a broken loop
+    assert 300.0 < tf32 <= 2600.0
     v = ctypes.c_double()
     assert lib.jd_verify_probe_mfma_bf16(0, 7, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_verify_probe_mfma_bf16(0, 1, None) == jb.JD_ERR_INVALID_ARG

@@ -78,3 +78,43 @@ def test_noalloc_rejects_what_it_cannot_hold():
     assert call(jb.make_config(8, 8, 1, 1, w_dtype=jb.JD_F32, device=1)) in (jb.JD_ERR_INVALID_ARG, jb.JD_ERR_HIP)
     del fits
     torch.cuda.synchronize()
+
+
+def test_noalloc_under_graph_capture():
+    # what the entry point is for: captured into a HIP graph (no allocation, no synchronisation, no memset node) and
+    # replayed with fresh inputs, eager work and synchronisations between the replays; every replay must equal the
+    # eager result and satisfy the parity bar against the oracle
+    import torch
+    from paper_2501_19309_amd import binding as jb, harness
+    jb.load_library()
+    shape = VerifyShape("na_graph", 4, 6, 96, 1500, "f32", 1.2)
+    xs = [make_inputs(shape, 50 + k, weights_seed=50) for k in range(2)]
+    dev = harness.to_device(xs[0])
+    cfg = jb.make_config(shape.d, shape.V, shape.B, shape.M, w_dtype=jb.JD_F32)
+    out = jb.alloc_outputs(shape.B, shape.M, shape.V)
+
+    def call():
+        jb.run_noalloc(cfg, dev["W"], dev["w_judge"], dev["emb"], dev["draft_tokens"], dev["draft_logits"], dev["uniforms"], out)
+
+    call()   # eager once: also the first call on the device, which looks up the workspace's address
+    torch.cuda.synchronize()
+    eager0 = out.to_numpy()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for it, k in enumerate((1, 0, 1)):
+        x = xs[k]
+        fresh = harness.to_device({n: x[n] for n in ("emb", "draft_tokens", "draft_logits", "uniforms")})
+        for n, t in fresh.items():
+            dev[n].copy_(t)      # eager work between the replays
+        for t in (out.accept_len, out.next_token, out.status):
+            t.fill_(-7)          # a replay that did nothing would be noticed
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.to_numpy()
+        ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"])
+        print("replay", it, compare(got, ref), flush=True)
+        if k == 0:
+            for name, v in got.items():
+                assert np.array_equal(v, eager0[name], equal_nan=True), (it, name)
