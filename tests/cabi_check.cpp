@@ -3,7 +3,8 @@
 // jd_verify_create / jd_verify_run (or jd_verify_run_prenorm) / jd_verify_destroy, writes the outputs
 // back as raw files.  The GPU test-suite compares those with the float64 oracle.
 //
-//   jd_cabi_check <dir> B M d V w_dtype prenorm
+//   jd_cabi_check <dir> B M d V w_dtype mode        mode 0: jd_verify_run, 1: jd_verify_run_prenorm,
+//                                                   2: jd_verify_run_noalloc (fp32 only, no context at all)
 //
 // Inputs in <dir> (little endian, dense): emb.bin or hidden.bin + gamma.bin (bf16 or fp32, as w_dtype
 // implies), W.bin, w_judge.bin, w_scale.bin (8-bit weights only), draft_logits.bin (fp32 [B][M+1][V]),
@@ -78,11 +79,12 @@ static bool download(const char* name, const void* d, size_t bytes) {
 
 int main(int argc, char** argv) {
   std::setvbuf(stdout, nullptr, _IONBF, 0);
-  if (argc != 8) { std::printf("usage: %s <dir> B M d V w_dtype prenorm\n", argv[0]); return 1; }
+  if (argc != 8) { std::printf("usage: %s <dir> B M d V w_dtype mode\n", argv[0]); return 1; }
   g_dir = argv[1];
   const int B = std::atoi(argv[2]), M = std::atoi(argv[3]), d = std::atoi(argv[4]), V = std::atoi(argv[5]);
   const int wdt = std::atoi(argv[6]);
-  const bool prenorm = std::atoi(argv[7]) != 0;
+  const int mode = std::atoi(argv[7]);
+  const bool prenorm = mode == 1, noalloc = mode == 2;
 
   jd_verify_config c = {};
   c.d = d; c.V = V; c.max_B = B; c.max_M = M;
@@ -123,12 +125,17 @@ int main(int argc, char** argv) {
       !o.d_q_at_draft || !o.d_judge_logit || !o.d_row_max || !o.d_row_sumexp) return 4;
 
   jd_verify_ctx* ctx = nullptr;
-  if (scaled) JD(jd_verify_create_scaled(&c, dW, static_cast<const float*>(dScale), dJ, &ctx));
-  else JD(jd_verify_create(&c, dW, dJ, &ctx));
+  if (!noalloc) {
+    if (scaled) JD(jd_verify_create_scaled(&c, dW, static_cast<const float*>(dScale), dJ, &ctx));
+    else JD(jd_verify_create(&c, dW, dJ, &ctx));
+  }
 
   hipStream_t st;
   CK(hipStreamCreate(&st));   // default priority
-  if (prenorm)
+  if (noalloc)   // no context: the workspace is the library's static device array
+    JD(jd_verify_run_noalloc(&c, dW, dJ, B, M, dE, nullptr, static_cast<const int32_t*>(dT), static_cast<const float*>(dD),
+                             M + 1, static_cast<const float*>(dU), &o, st));
+  else if (prenorm)
     JD(jd_verify_run_prenorm(ctx, B, M, dE, dG, 1e-5, static_cast<const int32_t*>(dT), static_cast<const float*>(dD),
                              M + 1, static_cast<const float*>(dU), &o, st));
   else
@@ -142,14 +149,14 @@ int main(int argc, char** argv) {
             download("q_at_draft.bin", o.d_q_at_draft, S * 4) && download("judge_logit.bin", o.d_judge_logit, S * 4) &&
             download("row_max.bin", o.d_row_max, R * 4) && download("row_sumexp.bin", o.d_row_sumexp, R * 4);
   uint64_t ws = 0;
-  JD(jd_verify_workspace_bytes(ctx, &ws));
+  if (ctx) JD(jd_verify_workspace_bytes(ctx, &ws));
   JD(jd_verify_destroy(ctx));
   CK(hipStreamDestroy(st));
   void* all[] = {dW, dJ, dScale, dE, dG, dD, dT, dU, o.d_accept_len, o.d_next_token, o.d_status, o.d_z_stand,
                  o.d_z_judge, o.d_p_at_draft, o.d_q_at_draft, o.d_judge_logit, o.d_row_max, o.d_row_sumexp};
   for (void* p : all)
     if (p) CK(hipFree(p));
-  std::printf("jd_cabi_check: B=%d M=%d d=%d V=%d w_dtype=%d prenorm=%d workspace=%llu bytes %s\n", B, M, d, V, wdt,
-              (int)prenorm, (unsigned long long)ws, ok ? "ok" : "FAILED to write outputs");
+  std::printf("jd_cabi_check: B=%d M=%d d=%d V=%d w_dtype=%d mode=%d workspace=%llu bytes %s\n", B, M, d, V, wdt,
+              mode, (unsigned long long)ws, ok ? "ok" : "FAILED to write outputs");
   return ok ? 0 : 5;
 }

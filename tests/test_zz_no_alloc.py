@@ -118,3 +118,30 @@ def test_noalloc_under_graph_capture():
         if k == 0:
             for name, v in got.items():
                 assert np.array_equal(v, eager0[name], equal_nan=True), (it, name)
+
+
+def test_noalloc_from_a_plain_cpp_process(tmp_path):
+    # the same entry point called from tests/cabi_check.cpp: a process with the HIP runtime and this library only
+    # (no torch, no context ever created), so the look-up of the static workspace happens on its very first call
+    import os
+    import subprocess
+    from paper_2501_19309_amd import binding as jb
+    from paper_2501_19309_amd.build import CABI_CHECK_PATH
+    assert os.path.exists(CABI_CHECK_PATH), "jd_cabi_check is not built: run __graft_entry__.build()"
+    shape = VerifyShape("na_cpp", 3, 6, 72, 1030, "f32", 1.0)
+    x = make_inputs(shape, 8)
+    for name in ("emb", "W", "w_judge", "draft_logits", "draft_tokens", "uniforms"):
+        np.ascontiguousarray(x[name]).tofile(tmp_path / f"{name}.bin")
+    cmd = [CABI_CHECK_PATH, str(tmp_path), str(shape.B), str(shape.M), str(shape.d), str(shape.V), str(jb.JD_F32), "2"]
+    print("[case]", " ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True, timeout=100)
+    print(res.stdout, res.stderr, flush=True)
+    assert res.returncode == 0, res.stdout + res.stderr
+    B, M = shape.B, shape.M
+    kinds = {"accept_len": (np.int32, (B,)), "next_token": (np.int32, (B,)), "status": (np.uint32, (B,)),
+             "z_stand": (np.uint8, (B, M)), "z_judge": (np.uint8, (B, M)), "p_at_draft": (np.float32, (B, M)),
+             "q_at_draft": (np.float32, (B, M)), "judge_logit": (np.float32, (B, M)),
+             "row_max": (np.float32, (B, M + 1)), "row_sumexp": (np.float32, (B, M + 1))}
+    got = {k: np.fromfile(tmp_path / f"{k}.bin", dtype=dt).reshape(sh) for k, (dt, sh) in kinds.items()}
+    ref = vo.verify(x["emb"], x["W"], x["w_judge"], x["draft_tokens"], x["draft_logits"], x["uniforms"])
+    print(compare(got, ref), flush=True)
