@@ -88,6 +88,9 @@ EDGE = [
     VerifyShape("e_V1", 2, 2, 8, 1, "f32", 1.0),                 # single token vocabulary: everything is certain
     VerifyShape("e_R2816", 256, 10, 256, 3000, "bf16", (0.5, 2.0)),  # eight 352-row tiles: several rounds of workgroups per unit
     VerifyShape("e_R2640_fp8", 240, 10, 272, 1500, "fp8", (0.5, 2.0)),  # fifteen 176-row tiles, FP8 codes, ragged d
+    VerifyShape("e_B70000", 70000, 1, 16, 40, "bf16", 1.0),      # more sequences (and rows) than a grid's y dimension holds
+    VerifyShape("e_R264", 24, 10, 264, 2100, "bf16", (0.5, 2.0)),  # 264 rows: a 352-row tile three quarters full
+    VerifyShape("e_R528", 48, 10, 264, 2100, "bf16", (0.5, 2.0)),  # 528 rows: three 176-row tiles
 ]
 
 
