@@ -118,9 +118,10 @@ hipError_t launch_pack_w8(const void* W8, int layout, const Geometry& g, void* W
 
 // Small-row regime LM head (R <= 64): streams Wp once, MFMA, writes fp32 logits
 // L[r*Lld + v] = (x_r . w_v) * invT for r < R, v < Vpad, and one softmax partial
-// (max, sum exp) per (row, vocabulary group): part[r*nVG + vg].
+// (max, sum exp) per (row, workgroup of four vocabulary groups): part[r*skinny_parts(g) + wg].
 // `side` (may be empty) is executed by extra workgroups of the same launch.
 // w_code kWFp8 / kWInt8: Wp is Wp8 and vscale (fp32 per vocabulary entry, or NULL = 1) multiplies the logits.
+inline int skinny_parts(const Geometry& g) { return (g.nVG + 3) / 4; }   // partials per row of that launch
 hipError_t launch_lmhead_skinny(const void* Wp, int w_code, const float* vscale, const void* X, int R,
                                 const Geometry& g, float invT, float* L, float2* part, const SideWork& side,
                                 hipStream_t st);
@@ -212,6 +213,10 @@ struct SamplerArgs {
 };
 constexpr int kSamplerChunk = 1024;     // tokens per sampler chunk
 hipError_t launch_sampler(const SamplerArgs& a, hipStream_t st);
+// Small-row regime with the judge logits already in a.g (sampling rule only): launch_accept and the first of the
+// sampler's two kernels as ONE launch, followed by launch_sampler_pick.
+hipError_t launch_rows_mass(const AcceptArgs& a, const SamplerArgs& s, hipStream_t st);
+hipError_t launch_sampler_pick(const SamplerArgs& a, hipStream_t st);
 
 // Top-K rule (Sec. 5): partial counts of the tokens that rank before the drafted one in its
 // target row (larger logit, or equal logit and lower id): rankpart[(b*M+j)*nSplit + s].

@@ -415,7 +415,7 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
   a.judge_done = fused_side;
   a.judge_threshold = c->judge_threshold; a.judge_bias = cfg.judge_bias;
   a.L = c->L; a.Lld = g.Vpad;
-  a.tpart = c->tpart; a.nPartT = c->nPartT;
+  a.tpart = c->tpart; a.nPartT = fused_side ? skinny_parts(g) : c->nPartT;  // the small-row launch hands over one partial per workgroup
   a.dpart = c->dpart; a.nPartD = c->nPartD;
   a.D = d_draft; a.draft_rows = draft_rows;
   a.tokens = d_draft_tokens; a.uniforms = d_uniforms;
@@ -425,8 +425,6 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
   a.z_stand = out->d_z_stand; a.z_judge = out->d_z_judge;
   a.p_at = out->d_p_at_draft; a.q_at = out->d_q_at_draft; a.judge_logit = out->d_judge_logit;
   a.row_max = out->d_row_max; a.row_sumexp = out->d_row_sumexp;
-  JD_HIP(launch_accept(a, st));
-  if (ev) JD_HIP(hipEventRecord(ev[3], st));
 
   // steps 5-7: OR of the masks, accepted prefix, replacement / bonus token
   SamplerArgs s;
@@ -437,10 +435,22 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
   s.chunk_mass = c->chunk_mass; s.nChunk = c->nChunk;
   s.accept_len = out->d_accept_len; s.next_token = out->d_next_token; s.status = out->d_status;
   s.resample_target = cfg.resample == JD_RESAMPLE_TARGET;
-  if (topk) {
+  if (fused_side && !topk && M + 1 <= 16) {
+    // Short drafts in the small-row regime: the row kernel and the sampler's first kernel as one launch (the judge
+    // logits are in c->g).  Every sampler workgroup then recomputes the statistics of the sequence's M+1 rows,
+    // 16 rows per pass: one pass is cheaper than a launch (M = 5: 7.9 us against 6.0 + 4.6 us and the gap
+    // between them), two passes are not (M = 25: 11.1 us against 6.2 + 4.5 us).
+    JD_HIP(launch_rows_mass(a, s, st));
+    if (ev) JD_HIP(hipEventRecord(ev[3], st));
+    JD_HIP(launch_sampler_pick(s, st));
+  } else if (topk) {
+    JD_HIP(launch_accept(a, st));
+    if (ev) JD_HIP(hipEventRecord(ev[3], st));
     JD_HIP(launch_argmax(c->L, g.Vpad, c->t_max, c->zflags, s.mode_judge, out->d_accept_len, out->d_status, B, M, cfg.V,
                          reinterpret_cast<int*>(c->chunk_mass), c->nChunk, out->d_next_token, st));
   } else {
+    JD_HIP(launch_accept(a, st));
+    if (ev) JD_HIP(hipEventRecord(ev[3], st));
     JD_HIP(launch_sampler(s, st));
   }
   if (ev) JD_HIP(hipEventRecord(ev[4], st));

@@ -256,8 +256,11 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
   }
 
   // epilogue.  acc[sub][x][i] is logit of embedding row x*16 + n and vocabulary entry
-  // vg*64 + sub*16 + gq*4 + i.
-  if (vg >= nVG) return;
+  // vg*64 + sub*16 + gq*4 + i.  Every wavefront reduces its 64 vocabulary entries to one (max, sum exp) per
+  // row; the four wavefronts' pairs are combined through LDS (the staging buffers are free: everybody is past
+  // the last barrier of the loop), so that the launch hands over ONE softmax partial per (row, workgroup).
+  const bool live = vg < nVG;  // a wavefront of padding groups contributes the empty partial
+  float2* ps = reinterpret_cast<float2*>(&xs[0][0]);  // [NWAVES][ROWS]
   float osc[4][4];  // output scale of this lane's 16 vocabulary entries: (per-entry scale) / T
 #pragma unroll
   for (int sub = 0; sub < 4; ++sub)
@@ -292,15 +295,25 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
       }
     sum += __shfl_xor(sum, 16);
     sum += __shfl_xor(sum, 32);
-    if (r < R) {
+    if (live && r < R) {
 #pragma unroll
       for (int sub = 0; sub < 4; ++sub) {
         const int v0 = vg * kVocabGroup + sub * 16 + gq * 4;
         *reinterpret_cast<float4*>(L + (size_t)r * Lld + v0) =
             make_float4(vals[sub][0], vals[sub][1], vals[sub][2], vals[sub][3]);
       }
-      if (gq == 0) part[(size_t)r * nVG + vg] = make_float2(mx, sum);
     }
+    if (gq == 0) ps[wave * ROWS + r] = live ? make_float2(mx, sum) : make_float2(-INFINITY, 0.f);
+  }
+  __syncthreads();
+  if (tid < ROWS && tid < R) {
+    MS st{-INFINITY, 0.f};
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) {  // fixed order: the result does not depend on timing
+      const float2 p = ps[w * ROWS + tid];
+      st = ms_combine(st, MS{p.x, p.y});
+    }
+    part[(size_t)tid * nLmBlocks + blockIdx.x] = make_float2(st.m, st.s);
   }
 }
 

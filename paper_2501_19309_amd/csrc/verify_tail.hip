@@ -274,6 +274,193 @@ __global__ __launch_bounds__(256) void sampler_mass_kernel(SamplerArgs a) {
   if (threadIdx.x == 0) a.chunk_mass[(size_t)b * a.nChunk + chunk] = s;
 }
 
+// Small-row regime (B*(M+1) <= 64, judge logits already computed beside the LM head): the row kernel and the
+// sampler's first kernel in ONE launch.  Every workgroup (sequence b, chunk) first recomputes what the row
+// kernel computes for its sequence - the M+1 target rows' softmax statistics from the LM head's partials (one
+// per row and LM-head workgroup, so a few hundred), the M draft rows' statistics, both tests of every slot, the
+// OR, the ballot and the prefix (steps 2-6) - and then sums its chunk of the sampler's masses (step 7).  The
+// recomputation costs each workgroup about as much as its chunk; in exchange the call has one dependent launch
+// fewer.  Workgroup 0 of a sequence writes the outputs and the statistics the pick kernel reads.
+__global__ __launch_bounds__(256) void rows_mass_kernel(AcceptArgs a, SamplerArgs s) {
+  __shared__ float2 tstat[64], qstat[64];  // (max, sum exp) of target rows 0..M and draft rows 0..M-1
+  __shared__ double red[256];
+  __shared__ int s_m;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int M = a.M, Mp1 = a.M + 1;
+  const int b = blockIdx.x / s.nChunk, chunk = blockIdx.x % s.nChunk;
+
+  // wavefront 0, lane j = slot j: the gathers travel while the partials are combined
+  int c = -1;
+  float l_c = 0.f, d_c = 0.f, u = 0.f, g = 0.f;
+  bool tok_ok = false;
+  if (wave == 0 && lane < M) {
+    const int slot = b * M + lane;
+    c = a.tokens[slot];
+    tok_ok = c >= 0 && c < a.V;
+    if (tok_ok) {
+      l_c = a.L[(size_t)(b * Mp1 + lane) * a.Lld + c];
+      d_c = a.D[((size_t)b * a.draft_rows + lane) * a.V + c];
+    }
+    u = a.uniforms[b * Mp1 + lane];
+    g = a.g[slot];
+  }
+
+  // Statistics of the rows: groups of 16 lanes, one row per group and turn (16 rows per turn of the workgroup).
+  // A lane's share of a row's partials (up to 32 at a time) is requested in one go and folded around its own
+  // maximum - independent exps, one dependent step - then the 16 lanes are combined by four exchange steps.
+  const int grp = tid >> 4, gl = tid & 15;
+  auto group_reduce = [&](MS st) {
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) {
+      MS t;
+      t.m = __shfl_xor(st.m, o);
+      t.s = __shfl_xor(st.s, o);
+      st = ms_combine(st, t);
+    }
+    return st;
+  };
+  // One row per group and pass (two in flight at once were no faster at 26 rows and slower at 6: the folding,
+  // not the second load latency, is what a pass costs).  The draft partials of the first 16 slots are requested
+  // before the (longer) target rows are worked on.
+  constexpr int kPer = 32, kTurns = 1;
+  float2 dv[kTurns];
+#pragma unroll
+  for (int t = 0; t < kTurns; ++t) {
+    const int j = 16 * t + grp;
+    dv[t] = (a.draft_is_logits && j < M && gl < a.nPartD) ? a.dpart[(size_t)(b * M + j) * a.nPartD + gl]
+                                                            : make_float2(-INFINITY, 0.f);
+  }
+  for (int r0 = 0; r0 <= M; r0 += 16 * kTurns) {
+    MS st[kTurns];
+    for (int i0 = 0; i0 < a.nPartT; i0 += 16 * kPer) {
+      float2 v[kTurns][kPer];
+#pragma unroll
+      for (int t = 0; t < kTurns; ++t) {
+        const int r = r0 + 16 * t + grp;
+        const float2* p = a.tpart + (size_t)(b * Mp1 + min(r, M)) * a.nPartT;
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) {
+          const int i = i0 + gl + 16 * e;
+          v[t][e] = (r <= M && i < a.nPartT) ? p[i] : make_float2(-INFINITY, 0.f);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < kTurns; ++t) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) mx = fmaxf(mx, v[t][e].x);
+        float sum = 0.f;
+        if (mx == -INFINITY) {  // nothing but empty partials (keeps NaN sums visible)
+#pragma unroll
+          for (int e = 0; e < kPer; ++e) sum += v[t][e].y;
+        } else {
+#pragma unroll
+          for (int e = 0; e < kPer; ++e) sum += v[t][e].y * __expf(v[t][e].x - mx);
+        }
+        st[t] = (i0 == 0) ? MS{mx, sum} : ms_combine(st[t], MS{mx, sum});
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < kTurns; ++t) {
+      const int r = r0 + 16 * t + grp;
+      const MS o = group_reduce(st[t]);
+      if (r <= M && gl == 0) tstat[r] = make_float2(o.m, o.s);
+    }
+  }
+  // draft rows the same way: the nPartD (16) partials of a slot are one per lane of a group
+  for (int j0 = 0; j0 < M; j0 += 16) {
+    const int j = j0 + grp;
+    const bool have = j < M;
+    MS st{0.f, 1.f};
+    if (a.draft_is_logits) {
+      st = MS{-INFINITY, 0.f};
+      if (j0 < 16 * kTurns) {
+        const float2 x = dv[0];
+        static_assert(kTurns == 1, "only the first 16 slots are prefetched");
+        st = MS{x.x, x.y};
+        for (int i = gl + 16; i < a.nPartD; i += 16) {  // more than 16 partials per slot
+          const float2 y = have ? a.dpart[(size_t)(b * M + j) * a.nPartD + i] : make_float2(-INFINITY, 0.f);
+          st = ms_combine(st, MS{y.x, y.y});
+        }
+      } else {
+        for (int i = gl; i < a.nPartD; i += 16) {
+          const float2 y = have ? a.dpart[(size_t)(b * M + j) * a.nPartD + i] : make_float2(-INFINITY, 0.f);
+          st = ms_combine(st, MS{y.x, y.y});
+        }
+      }
+      st = group_reduce(st);
+    }
+    if (have && gl == 0) qstat[j] = make_float2(st.m, st.s);
+  }
+  __syncthreads();
+
+  if (wave == 0) {
+    const bool first = chunk == 0;  // this workgroup writes the sequence's outputs
+    bool zs = false, zj = false;
+    float p_c = 0.f, q_c = 0.f;
+    uint8_t flags = 0;
+    if (lane < M) {
+      const float2 t = tstat[lane], q = qstat[lane];
+      if (tok_ok) {
+        p_c = expf(l_c - t.x) / t.y;
+        q_c = a.draft_is_logits ? expf(d_c - q.x) / q.y : d_c;
+        zs = u * q_c < p_c;   // Eq. 4, division-free and strict
+        zj = g > a.judge_threshold;
+      } else {
+        flags |= kZBadToken;
+      }
+      if (isnan(g) || isnan(t.y) || isnan(q.y) || isnan(q_c)) flags |= kZNan;
+      flags |= (zs ? kZStand : 0) | (zj ? kZJudge : 0);
+      if (first) {
+        const int slot = b * M + lane;
+        if (a.z_stand) a.z_stand[slot] = zs;
+        if (a.z_judge) a.z_judge[slot] = zj;
+        if (a.p_at) a.p_at[slot] = p_c;
+        if (a.q_at) a.q_at[slot] = q_c;
+        if (a.judge_logit) a.judge_logit[slot] = g;
+        if (a.draft_is_logits) { a.q_max[slot] = q.x; a.q_sum[slot] = q.y; }
+      }
+    } else if (lane == M) {
+      if (isnan(tstat[M].y)) flags |= kZNan;
+    }
+    if (lane <= M && first) {
+      const float2 t = tstat[lane];
+      const int row = b * Mp1 + lane;
+      a.zflags[row] = flags;
+      a.t_max[row] = t.x; a.t_sum[row] = t.y;
+      if (a.row_max) a.row_max[row] = t.x;
+      if (a.row_sumexp) a.row_sumexp[row] = t.y;
+    }
+    const bool z = lane < M && (zs || (s.mode_judge && zj));
+    const unsigned long long mask = __ballot(z);
+    uint32_t st = ((flags & kZBadToken) ? 1u : 0u) | ((flags & kZNan) ? 2u : 0u);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) st |= __shfl_xor(st, o);
+    const int m = __ffsll((long long)~mask) - 1;  // lanes >= M vote 0, so m <= M
+    if (lane == 0) {
+      s_m = m;
+      if (first) { s.accept_len[b] = m; s.status[b] = st; }
+    }
+  }
+  __syncthreads();
+  const int m = s_m;
+
+  // step 7, first pass: this workgroup's chunk of the masses of row m
+  MassRow row;
+  row.l = s.L + (size_t)(b * Mp1 + m) * s.Lld;
+  row.tm = tstat[m].x;
+  row.tinv = 1.f / tstat[m].y;
+  row.use_q = (m < M) && !s.resample_target;
+  row.q_is_logits = s.draft_is_logits;
+  row.dq = s.D; row.qm = 0.f; row.qinv = 1.f;
+  if (m < M) {
+    row.dq = s.D + ((size_t)b * s.draft_rows + m) * s.V;
+    if (s.draft_is_logits) { row.qm = qstat[m].x; row.qinv = 1.f / qstat[m].y; }
+  }
+  const double sum = chunk_sum(row, chunk, s.V, red);
+  if (tid == 0) s.chunk_mass[(size_t)b * s.nChunk + chunk] = sum;
+}
+
 // Block-wide helpers over 256 threads in float64 (fixed order, deterministic).
 __device__ __forceinline__ double block_sum256(double v, double* red) {
   const int tid = threadIdx.x;
@@ -429,6 +616,18 @@ __global__ __launch_bounds__(256) void sampler_pick_kernel(SamplerArgs a) {
     if (tok < 0) tok = 0;
     a.next_token[b] = tok;
   }
+}
+
+hipError_t launch_rows_mass(const AcceptArgs& a, const SamplerArgs& s, hipStream_t st) {
+  if (a.M > 63 || !a.judge_done || a.rule_topk) return hipErrorInvalidValue;
+  if ((size_t)s.nChunk * (size_t)s.B > 0x7fffffffULL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rows_mass_kernel, dim3((unsigned)(s.nChunk * s.B)), dim3(256), 0, st, a, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_sampler_pick(const SamplerArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(sampler_pick_kernel, dim3(a.B), dim3(256), 0, st, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_sampler(const SamplerArgs& a, hipStream_t st) {
