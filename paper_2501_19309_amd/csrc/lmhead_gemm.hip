@@ -81,7 +81,7 @@ hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks
 // lane's 16 bytes are its codes for the two K steps of a prefetch group): half the weight bytes from HBM
 // and through L2; fragments are converted to bf16 in registers one K step ahead, one instruction behind
 // an MFMA each; the per-entry scale is applied in the epilogue.
-template <bool W8>
+template <bool W8, int NLIVE>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
     int nChunks, int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L,
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub) {
           if constexpr (W8) {
-            mfma_16x16x32_bf16_inplace(acc[sub][x], cv[ks & 1][sub], bfrag[x % 3]);
+            if (x < NLIVE) mfma_16x16x32_bf16_inplace(acc[sub][x], cv[ks & 1][sub], bfrag[x % 3]);
             // codes of the group three ahead: four loads, in the first K step of a group only
             if (s == 0 && sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][0][x / 2] = wsrc[(x / 2) * 64];
             // fragments of the next K step (second half of this group's codes, or first half of the next
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
                         s == 0 ? fp8_frag_dword(codes.z, codes.w, c % 4) : fp8_frag_dword(codes.x, codes.y, c % 4));
             }
           } else {
-            mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
+            if (x < NLIVE) mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
             if (sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][s][x / 2] = wsrc[s * 256 + (x / 2) * 64];
           }
           if (sub == 0 && x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < IPT) stage_store(ks * 4 + x / 2);
@@ -341,14 +341,53 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
 
 constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * sizeof(uint4);
 
+// Instantiations by the number of 16-row blocks that hold rows when the launch is a single row tile (65 .. 176
+// rows): the MFMAs of the empty blocks are left out at compile time (a run-time branch around an MFMA would cost the
+// hand-dealt schedule its wait counts).  With few rows the kernel is bound by the weight stream - at half the bytes
+// per weight, FP8, only once the MFMAs of empty blocks are gone.
+template <bool W8, int NLIVE>
+static hipError_t set_lds_limit() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<W8, NLIVE>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+}
+template <bool W8>
+static hipError_t set_lds_limits() {
+  hipError_t e = set_lds_limit<W8, 5>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 6>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 7>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 8>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 9>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 10>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 11>();
+  return e;
+}
+
 // More LDS than the default limit of a launch: raised once per process, at context creation (not in the
 // launcher, which may run under stream capture).
 hipError_t init_lmhead_gemm() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+  hipError_t e = set_lds_limits<false>();
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<true>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+  return set_lds_limits<true>();
+}
+
+template <bool W8, int NLIVE>
+static void launch_gemm_t(int grid, hipStream_t st, const void* W, const float* vscale, const void* Xp, int R, int nChunks,
+                          const Geometry& g, int nRowTiles, int nVocabTiles, float invT, float* L, float2* part) {
+  hipLaunchKernelGGL((lmhead_gemm_kernel<W8, NLIVE>), dim3(grid), dim3(256), kGemmLdsBytes, st,
+                     static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,
+                     g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
+}
+
+template <bool W8>
+static void launch_gemm_live(int live, int grid, hipStream_t st, const void* W, const float* vscale, const void* Xp, int R,
+                             int nChunks, const Geometry& g, int nRowTiles, int nVocabTiles, float invT, float* L,
+                             float2* part) {
+#define JD_LIVE(N) case N: launch_gemm_t<W8, N>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break
+  switch (live) {
+    JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
+    default: launch_gemm_t<W8, 11>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
+  }
+#undef JD_LIVE
 }
 
 hipError_t launch_lmhead_gemm(const void* W, int w_fp8, const float* vscale, const void* X, int R, const Geometry& g,
@@ -361,14 +400,12 @@ hipError_t launch_lmhead_gemm(const void* W, int w_fp8, const float* vscale, con
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
+  // a single row tile: only the blocks that hold rows (at least 5, since 65 rows are the fewest this kernel is given)
+  const int live = nRowTiles == 1 ? (R + 15) / 16 : kGemmRowBlocks;
   if (w_fp8)
-    hipLaunchKernelGGL(lmhead_gemm_kernel<true>, dim3(grid), dim3(256), kGemmLdsBytes, st,
-                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,
-                       g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
+    launch_gemm_live<true>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part);
   else
-    hipLaunchKernelGGL(lmhead_gemm_kernel<false>, dim3(grid), dim3(256), kGemmLdsBytes, st,
-                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,
-                       g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
+    launch_gemm_live<false>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part);
   return hipGetLastError();
 }
 

@@ -115,6 +115,19 @@ def test_small_shapes_match_oracle(jd, shape, seed):
     print(rep, flush=True)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+def test_single_tile_row_block_counts(jd, dtype):
+    # 65 .. 176 rows run on one 176-row tile whose kernel is instantiated per number of 16-row blocks that hold rows
+    # (5 .. 11): one shape per instantiation, the last block ragged, and the exact block boundaries 80 and 176
+    for B, M in ((7, 10), (13, 6), (9, 11), (25, 4), (14, 9), (31, 4), (12, 13), (5, 15), (16, 10)):
+        R = B * (M + 1)
+        assert 64 < R <= 176
+        shape = VerifyShape(f"live_{dtype}_R{R}", B, M, 272, 1100, dtype, 1.2)
+        print(f"[case] {shape.name} ({(R + 15) // 16} row blocks)", flush=True)
+        x = make_inputs(shape, 11)
+        compare(jd.run_once(x, want_probs=True), oracle_for(x, return_probs=True))
+
+
 def test_bruteforce_interval_edges_on_gpu(jd):
     # the V = 8, M = 3 enumeration of tests/test_oracle_pins.py (every accept interval and every
     # CDF interval probed 1e-6 inside both ends) through the HIP library, ~30 k sequences in one call
