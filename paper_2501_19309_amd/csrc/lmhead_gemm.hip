@@ -81,11 +81,13 @@ hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks
 // lane's 16 bytes are its codes for the two K steps of a prefetch group): half the weight bytes from HBM
 // and through L2; fragments are converted to bf16 in registers one K step ahead, one instruction behind
 // an MFMA each; the per-entry scale is applied in the epilogue.
+// One tile: embedding rows rt*176 .. +175, vocabulary entries vt*256 .. +255.  NLIVE = number of the tile's 16-row
+// blocks that hold rows; the MFMAs of the others are left out at compile time.
 template <bool W8, int NLIVE>
-__global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
+__device__ __forceinline__ void gemm_tile(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
-    int nChunks, int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L,
-    int Lld, float2* __restrict__ part) {
+    int nChunks, int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part,
+    const int rt, const int vt) {
   constexpr int NXB = kGemmRowBlocks;
   constexpr int ITEMS = NXB * kGemmSteps * 64;  // 16-byte items per staged chunk (44 KiB)
   constexpr int IPT = ITEMS / 256;              // = NXB
@@ -94,14 +96,6 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
 
   extern __shared__ uint4 xs_raw[];  // 2 x ITEMS x 16 B = 88 KiB (dynamic: above the static limit)
   uint4 (*xs)[ITEMS] = reinterpret_cast<uint4 (*)[ITEMS]>(xs_raw);
-
-  // XCD-aware tile id: workgroups j = 0,1,2.. of one XCD walk row tiles fastest.
-  const int bid = blockIdx.x;
-  const int xcd = bid % kXcds;
-  const int j = bid / kXcds;
-  const int rt = j % nRowTiles;
-  const int vt = (j / nRowTiles) * kXcds + xcd;
-  if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -339,12 +333,32 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   }
 }
 
+// NLAST = row blocks that hold rows in the LAST row tile of the launch (all other row tiles are full).  The branch
+// is taken once per workgroup, outside the pipelined loop: a run-time branch around single MFMAs would cost the
+// hand-dealt schedule its wait counts.
+template <bool W8, int NLAST>
+__global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
+    const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
+    int nChunks, int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L,
+    int Lld, float2* __restrict__ part) {
+  // XCD-aware tile id: workgroups j = 0,1,2.. of one XCD walk row tiles fastest.
+  const int bid = blockIdx.x;
+  const int xcd = bid % kXcds;
+  const int j = bid / kXcds;
+  const int rt = j % nRowTiles;
+  const int vt = (j / nRowTiles) * kXcds + xcd;
+  if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
+  if (NLAST < kGemmRowBlocks && rt == nRowTiles - 1)
+    gemm_tile<W8, NLAST>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+  else
+    gemm_tile<W8, kGemmRowBlocks>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+}
+
 constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * sizeof(uint4);
 
-// Instantiations by the number of 16-row blocks that hold rows when the launch is a single row tile (65 .. 176
-// rows): the MFMAs of the empty blocks are left out at compile time (a run-time branch around an MFMA would cost the
-// hand-dealt schedule its wait counts).  With few rows the kernel is bound by the weight stream - at half the bytes
-// per weight, FP8, only once the MFMAs of empty blocks are gone.
+// Instantiations by the number of 16-row blocks that hold rows in the last row tile of a launch.  With one row tile
+// (65 .. 176 rows) the kernel is bound by the weight stream - at half the bytes per weight, FP8, only once the MFMAs
+// of empty blocks are gone; with several, a ragged last tile costs only the rows it has.
 template <bool W8, int NLIVE>
 static hipError_t set_lds_limit() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<W8, NLIVE>),
@@ -352,7 +366,11 @@ static hipError_t set_lds_limit() {
 }
 template <bool W8>
 static hipError_t set_lds_limits() {
-  hipError_t e = set_lds_limit<W8, 5>();
+  hipError_t e = set_lds_limit<W8, 1>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 2>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 3>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 4>();
+  if (e == hipSuccess) e = set_lds_limit<W8, 5>();
   if (e == hipSuccess) e = set_lds_limit<W8, 6>();
   if (e == hipSuccess) e = set_lds_limit<W8, 7>();
   if (e == hipSuccess) e = set_lds_limit<W8, 8>();
@@ -384,7 +402,7 @@ static void launch_gemm_live(int live, int grid, hipStream_t st, const void* W, 
                              float2* part) {
 #define JD_LIVE(N) case N: launch_gemm_t<W8, N>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break
   switch (live) {
-    JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
+    JD_LIVE(1); JD_LIVE(2); JD_LIVE(3); JD_LIVE(4); JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
     default: launch_gemm_t<W8, 11>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
   }
 #undef JD_LIVE
@@ -400,8 +418,8 @@ hipError_t launch_lmhead_gemm(const void* W, int w_fp8, const float* vscale, con
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
-  // a single row tile: only the blocks that hold rows (at least 5, since 65 rows are the fewest this kernel is given)
-  const int live = nRowTiles == 1 ? (R + 15) / 16 : kGemmRowBlocks;
+  // row blocks that hold rows in the last row tile (the others are full)
+  const int live = (R - (nRowTiles - 1) * kGemmRows + 15) / 16;
   if (w_fp8)
     launch_gemm_live<true>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part);
   else
