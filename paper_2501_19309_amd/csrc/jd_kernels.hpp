@@ -137,9 +137,9 @@ constexpr int kDmaRows = kDmaRowBlocks * 16;
 inline size_t gemm_xp_bytes(int R, const Geometry& g) {  // enough for either tiling
   return (size_t)((R + kDmaRows - 1) / kDmaRows) * kDmaRows * (size_t)g.dpad * 2;
 }
-// w_fp8: W is Wp8 (the FP8 copy of the small-row kernel) and vscale holds the per-entry scales; otherwise W is
-// the bf16 Wp.
-hipError_t launch_lmhead_gemm(const void* W, int w_fp8, const float* vscale, const void* X, int R, const Geometry& g,
+// w_code kWFp8 / kWInt8: W is Wp8 (the one-byte copy of the small-row kernel) and vscale holds the per-entry scales;
+// kWBf16: W is the bf16 Wp.
+hipError_t launch_lmhead_gemm(const void* W, int w_code, const float* vscale, const void* X, int R, const Geometry& g,
                               float invT, float* L, float2* part, void* Xp, hipStream_t st);
 // The same projection on 352-row x 256-entry tiles with both operands shared through LDS; the better
 // choice when gemm_prefers_352(R), i.e. when 352-row tiles add no padding rows over 176-row tiles.

@@ -250,8 +250,9 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
     JD_HIP_RC(hipDeviceSynchronize());
   }
   // FP8 contexts work from their FP8 copies in every regime; INT8 codes cost three instructions per two
-  // weights to convert, which the MFMA-bound large-row kernels cannot hide, so those run on an exact bf16 copy
-  if (rc == JD_OK && bf16 && !fp8 && !(int8 && maxR <= 64)) {
+  // weights to convert, which the MFMA-bound kernels (more than one 176-row tile) cannot hide, so those run on an
+  // exact bf16 copy
+  if (rc == JD_OK && bf16 && !fp8 && !(int8 && maxR <= (size_t)kGemmRows)) {
     uint8_t* wp = nullptr;
     rc = dev_alloc(c, &wp, c->geo.packed_bytes());
     c->Wp = wp;
@@ -388,8 +389,11 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
       JD_HIP(launch_lmhead_gemm_dma(fp8 ? c->Wg8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart,
                                     c->Xp, st));
     } else {
-      JD_HIP(launch_lmhead_gemm(fp8 ? c->Wp8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart, c->Xp,
-                                st));
+      // INT8 codes are converted in registers where the head is bound by the weight stream (one row tile); with
+      // more rows it is bound by the matrix cores, which cannot hide three instructions per two weights: bf16 copy
+      const bool int8_regs = int8 && R <= kGemmRows;
+      JD_HIP(launch_lmhead_gemm(fp8 || int8_regs ? c->Wp8 : c->Wp, fp8 ? kWFp8 : int8_regs ? kWInt8 : kWBf16, c->wscale, d_emb,
+                                R, g, invT, c->L, c->tpart, c->Xp, st));
     }
   } else {
     JD_HIP(launch_lmhead_f32(static_cast<const float*>(c->W), cfg.w_layout, static_cast<const float*>(d_emb), R,

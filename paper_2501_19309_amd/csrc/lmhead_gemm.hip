@@ -77,17 +77,18 @@ hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks
   return hipGetLastError();
 }
 
-// W8 = false: Wp is the re-tiled bf16 copy.  W8 = true: Wp is Wp8, the FP8 copy of the small-row kernel (a
+// WK = kWBf16: Wp is the re-tiled bf16 copy.  WK = kWFp8 / kWInt8: Wp is Wp8, the one-byte copy of the small-row kernel (a
 // lane's 16 bytes are its codes for the two K steps of a prefetch group): half the weight bytes from HBM
 // and through L2; fragments are converted to bf16 in registers one K step ahead, one instruction behind
 // an MFMA each; the per-entry scale is applied in the epilogue.
 // One tile: embedding rows rt*176 .. +175, vocabulary entries vt*256 .. +255.  NLIVE = number of the tile's 16-row
 // blocks that hold rows; the MFMAs of the others are left out at compile time.
-template <bool W8, int NLIVE>
+template <int WK, int NLIVE>
 __device__ __forceinline__ void gemm_tile(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
     int nChunks, int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part,
     const int rt, const int vt) {
+  constexpr bool W8 = WK != kWBf16;  // one-byte codes (FP8 E4M3 or INT8) in the Wp8 layout
   constexpr int NXB = kGemmRowBlocks;
   constexpr int ITEMS = NXB * kGemmSteps * 64;  // 16-byte items per staged chunk (44 KiB)
   constexpr int IPT = ITEMS / 256;              // = NXB
@@ -211,7 +212,7 @@ __device__ __forceinline__ void gemm_tile(
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub)
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) set_dword(cv[0][sub], jj, fp8_frag_dword(wbuf[0][0][sub].x, wbuf[0][0][sub].y, jj));
+      for (int jj = 0; jj < 4; ++jj) set_dword(cv[0][sub], jj, w8_frag_dword<WK>(wbuf[0][0][sub].x, wbuf[0][0][sub].y, jj));
   }
   __syncthreads();
 
@@ -289,7 +290,7 @@ __device__ __forceinline__ void gemm_tile(
             if (c >= 0) {
               const uint4& codes = wbuf[cslot][0][c / 4];
               set_dword(cv[(ks + 1) & 1][c / 4], c % 4,
-                        s == 0 ? fp8_frag_dword(codes.z, codes.w, c % 4) : fp8_frag_dword(codes.x, codes.y, c % 4));
+                        s == 0 ? w8_frag_dword<WK>(codes.z, codes.w, c % 4) : w8_frag_dword<WK>(codes.x, codes.y, c % 4));
             }
           } else {
             if (x < NLIVE) mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
@@ -370,7 +371,7 @@ __device__ __forceinline__ void gemm_tile(
 // NLAST = row blocks that hold rows in the LAST row tile of the launch (all other row tiles are full).  The branch
 // is taken once per workgroup, outside the pipelined loop: a run-time branch around single MFMAs would cost the
 // hand-dealt schedule its wait counts.
-template <bool W8, int NLAST>
+template <int WK, int NLAST>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
     int nChunks, int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L,
@@ -382,10 +383,11 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   const int rt = j % nRowTiles;
   const int vt = (j / nRowTiles) * kXcds + xcd;
   if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
-  if (NLAST < kGemmRowBlocks && rt == nRowTiles - 1)
-    gemm_tile<W8, NLAST>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+  // (INT8 codes are only ever launched on a single row tile: no second body)
+  if (WK == kWInt8 || (NLAST < kGemmRowBlocks && rt == nRowTiles - 1))
+    gemm_tile<WK, NLAST>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
   else
-    gemm_tile<W8, kGemmRowBlocks>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+    gemm_tile<WK, kGemmRowBlocks>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
 }
 
 constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * sizeof(uint4);
@@ -393,60 +395,72 @@ constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * 
 // Instantiations by the number of 16-row blocks that hold rows in the last row tile of a launch.  With one row tile
 // (65 .. 176 rows) the kernel is bound by the weight stream - at half the bytes per weight, FP8, only once the MFMAs
 // of empty blocks are gone; with several, a ragged last tile costs only the rows it has.
-template <bool W8, int NLIVE>
+template <int WK, int NLIVE>
 static hipError_t set_lds_limit() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<W8, NLIVE>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<WK, NLIVE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
 }
-template <bool W8>
+template <int WK>
 static hipError_t set_lds_limits() {
-  hipError_t e = set_lds_limit<W8, 1>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 2>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 3>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 4>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 5>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 6>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 7>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 8>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 9>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 10>();
-  if (e == hipSuccess) e = set_lds_limit<W8, 11>();
+  hipError_t e = hipSuccess;
+  if constexpr (WK != kWInt8) {  // a last row tile of fewer than 5 blocks only exists behind full ones
+    e = set_lds_limit<WK, 1>();
+    if (e == hipSuccess) e = set_lds_limit<WK, 2>();
+    if (e == hipSuccess) e = set_lds_limit<WK, 3>();
+    if (e == hipSuccess) e = set_lds_limit<WK, 4>();
+  }
+  if (e == hipSuccess) e = set_lds_limit<WK, 5>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 6>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 7>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 8>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 9>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 10>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 11>();
   return e;
 }
 
 // More LDS than the default limit of a launch: raised once per process, at context creation (not in the
 // launcher, which may run under stream capture).
 hipError_t init_lmhead_gemm() {
-  hipError_t e = set_lds_limits<false>();
-  if (e != hipSuccess) return e;
-  return set_lds_limits<true>();
+  hipError_t e = set_lds_limits<kWBf16>();
+  if (e == hipSuccess) e = set_lds_limits<kWFp8>();
+  if (e == hipSuccess) e = set_lds_limits<kWInt8>();
+  return e;
 }
 
-template <bool W8, int NLIVE>
+template <int WK, int NLIVE>
 static void launch_gemm_t(int grid, hipStream_t st, const void* W, const float* vscale, const void* Xp, int R, int nChunks,
                           const Geometry& g, int nRowTiles, int nVocabTiles, float invT, float* L, float2* part) {
-  hipLaunchKernelGGL((lmhead_gemm_kernel<W8, NLIVE>), dim3(grid), dim3(256), kGemmLdsBytes, st,
+  hipLaunchKernelGGL((lmhead_gemm_kernel<WK, NLIVE>), dim3(grid), dim3(256), kGemmLdsBytes, st,
                      static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,
                      g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
 }
 
-template <bool W8>
+template <int WK>
 static void launch_gemm_live(int live, int grid, hipStream_t st, const void* W, const float* vscale, const void* Xp, int R,
                              int nChunks, const Geometry& g, int nRowTiles, int nVocabTiles, float invT, float* L,
                              float2* part) {
-#define JD_LIVE(N) case N: launch_gemm_t<W8, N>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break
+#define JD_LIVE(N) case N: launch_gemm_t<WK, N>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break
+  if constexpr (WK != kWInt8) {
+    switch (live) {
+      JD_LIVE(1); JD_LIVE(2); JD_LIVE(3); JD_LIVE(4);
+      default: break;
+    }
+    if (live <= 4) return;
+  }
   switch (live) {
-    JD_LIVE(1); JD_LIVE(2); JD_LIVE(3); JD_LIVE(4); JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
-    default: launch_gemm_t<W8, 11>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
+    JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
+    default: launch_gemm_t<WK, 11>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
   }
 #undef JD_LIVE
 }
 
-hipError_t launch_lmhead_gemm(const void* W, int w_fp8, const float* vscale, const void* X, int R, const Geometry& g,
+hipError_t launch_lmhead_gemm(const void* W, int w_code, const float* vscale, const void* X, int R, const Geometry& g,
                               float invT, float* L, float2* part, void* Xp, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
   if (R <= 0 || !Xp || !W) return hipErrorInvalidValue;
   const int nRowTiles = (R + kGemmRows - 1) / kGemmRows;
+  if (w_code == kWInt8 && nRowTiles != 1) return hipErrorInvalidValue;  // INT8 codes: single row tile only
   const int nChunks = g.dpad / kGemmKChunk;
   hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, nChunks, kGemmRowBlocks, kGemmSteps, Xp, st);
   if (e != hipSuccess) return e;
@@ -454,10 +468,12 @@ hipError_t launch_lmhead_gemm(const void* W, int w_fp8, const float* vscale, con
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
   // row blocks that hold rows in the last row tile (the others are full)
   const int live = (R - (nRowTiles - 1) * kGemmRows + 15) / 16;
-  if (w_fp8)
-    launch_gemm_live<true>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part);
-  else
-    launch_gemm_live<false>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part);
+  switch (w_code) {
+    case kWFp8: launch_gemm_live<kWFp8>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
+    case kWInt8: launch_gemm_live<kWInt8>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
+    case kWBf16: launch_gemm_live<kWBf16>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -29,6 +29,22 @@ __device__ __forceinline__ uint32_t fp8_frag_dword(uint32_t lo, uint32_t hi, int
   return fp8x2_to_bf16x2(j < 2 ? lo : hi, (j & 1) != 0);
 }
 
+// The same for either one-byte code type.  INT8 (two's complement): two sign-extending byte -> float conversions;
+// an integer of magnitude <= 128 has at most 8 significant bits, so the upper half of its float is exactly its bf16,
+// and a byte permute packs the two halves - three instructions where FP8 needs one.
+template <int WK>
+__device__ __forceinline__ uint32_t w8_frag_dword(uint32_t lo, uint32_t hi, int j) {
+  if constexpr (WK == kWFp8) {
+    return fp8_frag_dword(lo, hi, j);
+  } else {
+    static_assert(WK == kWInt8, "8-bit code");
+    const uint32_t w = j < 2 ? lo : hi;
+    const int sh = (j & 1) * 16;
+    const float a = (float)(int)(int8_t)(w >> sh), b = (float)(int)(int8_t)(w >> (sh + 8));
+    return __builtin_amdgcn_perm(__float_as_uint(b), __float_as_uint(a), 0x07060302u);  // b.hi16 : a.hi16
+  }
+}
+
 __device__ __forceinline__ void set_dword(uint4& v, int j, uint32_t x) {
   if (j == 0) v.x = x; else if (j == 1) v.y = x; else if (j == 2) v.z = x; else v.w = x;
 }

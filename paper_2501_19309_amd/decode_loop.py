@@ -155,7 +155,7 @@ def sweep(batch_sizes: List[int], steps: int, seed: int, dtype: str = "bf16") ->
     dev = harness.to_device(x)
     ver = harness.make_verifier(dev)   # max_B = Bmax: one context, one re-tiled W_lm for every batch size
     recs = []
-    w_bytes = V * d * (1 if dtype == "fp8" else 2)
+    w_bytes = V * d * (1 if dtype in ("fp8", "int8") else 2)
     for B in batch_sizes:
         R = B * (M + 1)
         e, t, D, u = (dev[k][:B].contiguous() for k in ("emb", "draft_tokens", "draft_logits", "uniforms"))
@@ -197,7 +197,7 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true", help="also time the loop as replayed HIP graphs")
     ap.add_argument("--sweep", default="", help="comma-separated batch sizes; runs the sweep instead of the loop")
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--dtype", default="bf16", choices=("bf16", "fp8"), help="W_lm storage type of the sweep")
+    ap.add_argument("--dtype", default="bf16", choices=("bf16", "fp8", "int8"), help="W_lm storage type of the sweep")
     args = ap.parse_args()
     jb.load_library()
     if args.sweep:

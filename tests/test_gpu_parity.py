@@ -115,7 +115,7 @@ def test_small_shapes_match_oracle(jd, shape, seed):
     print(rep, flush=True)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp8", "int8"])
 def test_row_block_counts_of_the_last_176_row_tile(jd, dtype):
     # The 176-row kernel is instantiated per number of 16-row blocks that hold rows in the LAST row tile of a launch
     # (1 .. 11).  One row tile (65 .. 176 rows): one shape per instantiation from 5 blocks on, the last block ragged,
@@ -134,6 +134,7 @@ def test_row_block_counts_of_the_last_176_row_tile(jd, dtype):
         x = make_inputs(shape, 11)
         compare(jd.run_once(x), oracle_for(x))
     assert {l for t, l in seen if t == 1} == set(range(5, 12)) and {l for t, l in seen if t == 3} == set(range(1, 12)), seen
+    # (INT8 codes run through this kernel's own conversion on one row tile, and on the bf16 copy beyond)
 
 
 def test_bruteforce_interval_edges_on_gpu(jd):
@@ -395,7 +396,7 @@ INT8 = [
     VerifyShape("i_ragged", 2, 9, 272, 1000, "int8", 2.0),           # d % 256 != 0, V % 64 != 0
     VerifyShape("i_3blk", 4, 10, 768, 3000, "int8", 1.5),            # R = 44
     VerifyShape("i_4blk", 4, 15, 768, 3000, "int8", 1.5),            # R = 64
-    VerifyShape("i_gemm", 9, 10, 512, 5000, "int8", (0.5, 2.5)),     # R = 99: large-row regime on the bf16 copy
+    VerifyShape("i_gemm", 9, 10, 512, 5000, "int8", (0.5, 2.5)),     # R = 99: one 176-row tile, codes converted in registers
     VerifyShape("i_gemm352", 20, 10, 288, 2100, "int8", (0.5, 2.5)), # R = 220: 352-row tiling on the bf16 copy
     VerifyShape("i_d16", 2, 3, 16, 200, "int8", 1.0),                # smallest hidden size of the 8-bit path
 ]
