@@ -143,10 +143,9 @@ int jd_verify_create(const jd_verify_config* cfg, const void* d_W_lm, const void
  *   d_w_scale   [V] fp32 device pointer, borrowed for the lifetime of the context (every call reads it);
  *               NULL means all ones.
  *               Must be NULL for JD_F32 / JD_BF16 weights (INVALID_ARG otherwise).
- * The library builds a re-tiled copy of the codes (V*d bytes); for FP8 codes and max_B*(max_M+1) > 64 a second FP8
- * copy in the fragment order of the 352-row kernel (another V*d bytes); for INT8 codes and max_B*(max_M+1) > 176 a
- * bf16 copy (2*V*d bytes) for the calls with more than 176 rows, which are bound by the matrix cores and cannot hide
- * the integer conversion.  Codes become bf16 exactly, in registers or in that copy.
+ * The library builds a re-tiled copy of the codes (V*d bytes) and, for max_B*(max_M+1) > 176, a second one in the
+ * fragment order of the 352-row kernel (another V*d bytes).  No bf16 copy is held: every kernel turns the codes into
+ * bf16 exactly, in registers, on their way to the matrix cores.
  * d must be a multiple of 16.  Other errors as jd_verify_create.
  */
 int jd_verify_create_scaled(const jd_verify_config* cfg, const void* d_W_lm, const float* d_w_scale,

@@ -109,9 +109,8 @@ RowStatsArgs make_rowstats_args(const float* base, int rowsUsed, size_t seqStrid
 
 // ---- launchers (all asynchronous on `st`) -----------------------------------------
 
-// Re-tile W_lm ([V][d] if layout==0, [d][V] if layout==1) into bf16 Wp, zero padded.  The source
-// holds bf16 values (src_code kWBf16), or one-byte codes (kWFp8, kWInt8) that are converted exactly.
-hipError_t launch_pack_w(const void* W, int layout, int src_code, const Geometry& g, void* Wp, hipStream_t st);
+// Re-tile bf16 W_lm ([V][d] if layout==0, [d][V] if layout==1) into Wp, zero padded.
+hipError_t launch_pack_w(const void* W, int layout, const Geometry& g, void* Wp, hipStream_t st);
 
 // Re-tile one-byte codes of W_lm (FP8 E4M3 or INT8) into Wp8 (see above), zero padded.
 hipError_t launch_pack_w8(const void* W8, int layout, const Geometry& g, void* Wp8, hipStream_t st);
@@ -143,9 +142,9 @@ hipError_t launch_lmhead_gemm(const void* W, int w_code, const float* vscale, co
                               float invT, float* L, float2* part, void* Xp, hipStream_t st);
 // The same projection on 352-row x 256-entry tiles with both operands shared through LDS; the better
 // choice when gemm_prefers_352(R), i.e. when 352-row tiles add no padding rows over 176-row tiles.
-// w_fp8: W is Wg8, the FP8 copy that launch_pack_w8g builds (Geometry::packed8_bytes() bytes), and vscale
-// holds the per-entry scales; otherwise W is the bf16 Wp.
-hipError_t launch_lmhead_gemm_dma(const void* W, int w_fp8, const float* vscale, const void* X, int R,
+// w_code kWFp8 / kWInt8: W is Wg8, the one-byte copy that launch_pack_w8g builds (Geometry::packed8_bytes() bytes),
+// and vscale holds the per-entry scales; kWBf16: W is the bf16 Wp.
+hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale, const void* X, int R,
                                   const Geometry& g, float invT, float* L, float2* part, void* Xp, hipStream_t st);
 hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* Wg8, hipStream_t st);
 // Once per process before the first launch of either kernel (they use more dynamic LDS than the default limit).

@@ -20,9 +20,9 @@ struct jd_verify_ctx {
   Geometry geo;
   const void* W;        // the caller's W_lm: kept (and read by every call) for fp32 weights only, else NULL
   const void* wj;
-  void* Wp;             // re-tiled bf16 weights (bf16 weights; INT8 weights only for the large-row regime)
+  void* Wp;             // re-tiled bf16 weights (bf16 weights only)
   void* Wp8;            // re-tiled one-byte codes (FP8 and INT8 weights)
-  void* Wg8;            // re-tiled FP8 weights for the 352-row kernel (FP8 weights, max_R > 64)
+  void* Wg8;            // re-tiled one-byte weights for the 352-row kernel (FP8 / INT8 weights, max_R > 176)
   const float* wscale;  // per-vocabulary-entry weight scale (FP8 and INT8 weights, may be NULL)
   float* L;             // [maxR][Vpad] fp32 logits
   float2* tpart;        // [maxR][nPartT]
@@ -242,24 +242,24 @@ extern "C" int jd_verify_create_scaled(const jd_verify_config* cfg, const void* 
       c->zflags = pool + o_zf;
     }
   }
-  if (rc == JD_OK && (fp8 || int8)) {
+  const bool w8 = fp8 || int8;
+  if (rc == JD_OK && w8) {
     uint8_t* wp8 = nullptr;
     rc = dev_alloc(c, &wp8, c->geo.packed8_bytes());
     c->Wp8 = wp8;
     JD_HIP_RC(launch_pack_w8(d_W_lm, cfg->w_layout, c->geo, c->Wp8, nullptr));
     JD_HIP_RC(hipDeviceSynchronize());
   }
-  // FP8 contexts work from their FP8 copies in every regime; INT8 codes cost three instructions per two
-  // weights to convert, which the MFMA-bound kernels (more than one 176-row tile) cannot hide, so those run on an
-  // exact bf16 copy
-  if (rc == JD_OK && bf16 && !fp8 && !(int8 && maxR <= (size_t)kGemmRows)) {
+  // 8-bit contexts work from one-byte copies in every regime and hold no bf16 copy: Wp8 feeds the small-row and
+  // the 176-row kernel, Wg8 (the same codes in the 352-row kernel's order) exists when that kernel can be chosen
+  if (rc == JD_OK && bf16 && !w8) {
     uint8_t* wp = nullptr;
     rc = dev_alloc(c, &wp, c->geo.packed_bytes());
     c->Wp = wp;
-    JD_HIP_RC(launch_pack_w(d_W_lm, cfg->w_layout, int8 ? kWInt8 : kWBf16, c->geo, c->Wp, nullptr));
+    JD_HIP_RC(launch_pack_w(d_W_lm, cfg->w_layout, c->geo, c->Wp, nullptr));
     JD_HIP_RC(hipDeviceSynchronize());
   }
-  if (rc == JD_OK && fp8 && maxR > 64) {  // FP8 fragments for the 352-row kernel
+  if (rc == JD_OK && w8 && maxR > (size_t)kGemmRows) {
     uint8_t* wg8 = nullptr;
     rc = dev_alloc(c, &wg8, c->geo.packed8_bytes());
     c->Wg8 = wg8;
@@ -382,18 +382,17 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
 
   // step 1: LM head (+ first softmax pass)
   if (bf16) {
+    // 8-bit codes are converted to bf16 in registers by all three kernels (FP8: one instruction per two codes;
+    // INT8: three, which the matrix-core-bound 352-row kernel cannot hide completely - it runs 4-8 % behind
+    // the same kernel on bf16 weights and moves half the bytes)
+    const bool w8 = fp8 || int8;
+    const int wk = fp8 ? kWFp8 : int8 ? kWInt8 : kWBf16;
     if (R <= 64) {
-      JD_HIP(launch_lmhead_skinny(fp8 || int8 ? c->Wp8 : c->Wp, fp8 ? kWFp8 : int8 ? kWInt8 : kWBf16, c->wscale, d_emb, R,
-                                  g, invT, c->L, c->tpart, side, st));
+      JD_HIP(launch_lmhead_skinny(w8 ? c->Wp8 : c->Wp, wk, c->wscale, d_emb, R, g, invT, c->L, c->tpart, side, st));
     } else if (gemm_prefers_352(R)) {
-      JD_HIP(launch_lmhead_gemm_dma(fp8 ? c->Wg8 : c->Wp, fp8 ? 1 : 0, c->wscale, d_emb, R, g, invT, c->L, c->tpart,
-                                    c->Xp, st));
+      JD_HIP(launch_lmhead_gemm_dma(w8 ? c->Wg8 : c->Wp, wk, c->wscale, d_emb, R, g, invT, c->L, c->tpart, c->Xp, st));
     } else {
-      // INT8 codes are converted in registers where the head is bound by the weight stream (one row tile); with
-      // more rows it is bound by the matrix cores, which cannot hide three instructions per two weights: bf16 copy
-      const bool int8_regs = int8 && R <= kGemmRows;
-      JD_HIP(launch_lmhead_gemm(fp8 || int8_regs ? c->Wp8 : c->Wp, fp8 ? kWFp8 : int8_regs ? kWInt8 : kWBf16, c->wscale, d_emb,
-                                R, g, invT, c->L, c->tpart, c->Xp, st));
+      JD_HIP(launch_lmhead_gemm(w8 ? c->Wp8 : c->Wp, wk, c->wscale, d_emb, R, g, invT, c->L, c->tpart, c->Xp, st));
     }
   } else {
     JD_HIP(launch_lmhead_f32(static_cast<const float*>(c->W), cfg.w_layout, static_cast<const float*>(d_emb), R,

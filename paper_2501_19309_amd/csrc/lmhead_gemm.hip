@@ -383,8 +383,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   const int rt = j % nRowTiles;
   const int vt = (j / nRowTiles) * kXcds + xcd;
   if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
-  // (INT8 codes are only ever launched on a single row tile: no second body)
-  if (WK == kWInt8 || (NLAST < kGemmRowBlocks && rt == nRowTiles - 1))
+  if (NLAST < kGemmRowBlocks && rt == nRowTiles - 1)
     gemm_tile<WK, NLAST>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
   else
     gemm_tile<WK, kGemmRowBlocks>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
@@ -402,13 +401,10 @@ static hipError_t set_lds_limit() {
 }
 template <int WK>
 static hipError_t set_lds_limits() {
-  hipError_t e = hipSuccess;
-  if constexpr (WK != kWInt8) {  // a last row tile of fewer than 5 blocks only exists behind full ones
-    e = set_lds_limit<WK, 1>();
-    if (e == hipSuccess) e = set_lds_limit<WK, 2>();
-    if (e == hipSuccess) e = set_lds_limit<WK, 3>();
-    if (e == hipSuccess) e = set_lds_limit<WK, 4>();
-  }
+  hipError_t e = set_lds_limit<WK, 1>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 2>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 3>();
+  if (e == hipSuccess) e = set_lds_limit<WK, 4>();
   if (e == hipSuccess) e = set_lds_limit<WK, 5>();
   if (e == hipSuccess) e = set_lds_limit<WK, 6>();
   if (e == hipSuccess) e = set_lds_limit<WK, 7>();
@@ -441,15 +437,8 @@ static void launch_gemm_live(int live, int grid, hipStream_t st, const void* W, 
                              int nChunks, const Geometry& g, int nRowTiles, int nVocabTiles, float invT, float* L,
                              float2* part) {
 #define JD_LIVE(N) case N: launch_gemm_t<WK, N>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break
-  if constexpr (WK != kWInt8) {
-    switch (live) {
-      JD_LIVE(1); JD_LIVE(2); JD_LIVE(3); JD_LIVE(4);
-      default: break;
-    }
-    if (live <= 4) return;
-  }
   switch (live) {
-    JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
+    JD_LIVE(1); JD_LIVE(2); JD_LIVE(3); JD_LIVE(4); JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
     default: launch_gemm_t<WK, 11>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
   }
 #undef JD_LIVE
@@ -460,7 +449,6 @@ hipError_t launch_lmhead_gemm(const void* W, int w_code, const float* vscale, co
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
   if (R <= 0 || !Xp || !W) return hipErrorInvalidValue;
   const int nRowTiles = (R + kGemmRows - 1) / kGemmRows;
-  if (w_code == kWInt8 && nRowTiles != 1) return hipErrorInvalidValue;  // INT8 codes: single row tile only
   const int nChunks = g.dpad / kGemmKChunk;
   hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, nChunks, kGemmRowBlocks, kGemmSteps, Xp, st);
   if (e != hipSuccess) return e;

@@ -92,14 +92,16 @@ __device__ __forceinline__ void dma_issue(const uint4* gbase, unsigned lane_off)
   asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase) : "memory");
 }
 
-// W8 = false: Wsrc is the re-tiled bf16 copy Wp.  W8 = true: Wsrc is the FP8 copy Wg8 (see pack_w8g_kernel):
-// half the weight bytes through L2, L1 and LDS; fragments are converted to bf16 in registers, one
-// instruction behind each MFMA, one K step ahead; the per-entry scale is applied in the epilogue.
-template <bool W8>
+// WK = kWBf16: Wsrc is the re-tiled bf16 copy Wp.  WK = kWFp8, kWInt8: Wsrc is the one-byte copy Wg8 (see
+// pack_w8g_kernel): half the weight bytes through L2, L1 and LDS; fragments are converted to bf16 in registers
+// behind MFMAs that carry nothing else, one K step ahead (one instruction per two FP8 codes, three per two INT8
+// codes); the per-entry scale is applied in the epilogue.
+template <int WK>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
     int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld,
     float2* __restrict__ part) {
+  constexpr bool W8 = WK != kWBf16;
   constexpr int kStageItems = kDmaStageItems<W8>;
   constexpr int kNW = W8 ? 2 : 4;       // direct-to-LDS loads of weights per wavefront and K step
   constexpr int kPieces = kNW + 6;      // + up to six embedding row blocks
@@ -182,7 +184,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
       for (int s = 0; s < 8; ++s) {
         const uint2 c = wr[s * 64];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) set_dword(wf[0][s], jj, fp8_frag_dword(c.x, c.y, jj));
+        for (int jj = 0; jj < 4; ++jj) set_dword(wf[0][s], jj, w8_frag_dword<WK>(c.x, c.y, jj));
       }
     } else {
       const uint4* wr = lds + kDmaXItems + vh * 8 * 64 + lane;
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
       if constexpr (W8) {
         // weight sub-block x-1 of step k+1: codes read behind MFMA (x, 0), converted behind MFMAs (x+1, 2..5),
         // so that every MFMA of the step has at most one vector, LDS or memory instruction behind it
-        if constexpr (x >= 2 && x <= 9 && sb >= 2 && sb <= 5) set_dword(wf[nxt][x - 2], sb - 2, fp8_frag_dword(raw[x - 2].x, raw[x - 2].y, sb - 2));
+        if constexpr (x >= 2 && x <= 9 && sb >= 2 && sb <= 5) set_dword(wf[nxt][x - 2], sb - 2, w8_frag_dword<WK>(raw[x - 2].x, raw[x - 2].y, sb - 2));
         if constexpr (x >= 1 && x <= 8 && sb == 0) raw[x - 1] = wr8[(x - 1) * 64];
       } else {
         if constexpr (x >= 1 && x <= 8 && sb == 3) wf[nxt][x - 1] = wr[(x - 1) * 64];  // weight sub-block x-1
@@ -352,14 +354,17 @@ hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* 
 // More LDS than the default limit of a launch: raised once per process, at context creation (not in the
 // launcher, which may run under stream capture).
 hipError_t init_lmhead_gemm_dma() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<false>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<kWBf16>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<false>);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<true>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<kWFp8>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<true>);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<kWInt8>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<true>);
 }
 
-hipError_t launch_lmhead_gemm_dma(const void* W, int w_fp8, const float* vscale, const void* X, int R,
+hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale, const void* X, int R,
                                   const Geometry& g, float invT, float* L, float2* part, void* Xp, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
   static_assert(kWpKG * 256 == 4 * 256 && kKStep == 32, "a K step of one vocabulary group is 4 KiB, contiguous");
@@ -371,14 +376,14 @@ hipError_t launch_lmhead_gemm_dma(const void* W, int w_fp8, const float* vscale,
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
-  if (w_fp8)
-    hipLaunchKernelGGL(lmhead_gemm_dma_kernel<true>, dim3(grid), dim3(256), kDmaLdsBytes<true>, st,
-                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG,
-                       g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
-  else
-    hipLaunchKernelGGL(lmhead_gemm_dma_kernel<false>, dim3(grid), dim3(256), kDmaLdsBytes<false>, st,
-                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG,
-                       g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
+#define JD_DMA(WK_)                                                                                              \
+  hipLaunchKernelGGL(lmhead_gemm_dma_kernel<WK_>, dim3(grid), dim3(256), kDmaLdsBytes<(WK_) != kWBf16>, st,      \
+                     static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG,     \
+                     g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part)
+  if (w_code == kWFp8) JD_DMA(kWFp8);
+  else if (w_code == kWInt8) JD_DMA(kWInt8);
+  else JD_DMA(kWBf16);
+#undef JD_DMA
   return hipGetLastError();
 }
 

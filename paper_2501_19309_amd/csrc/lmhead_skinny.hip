@@ -34,10 +34,8 @@ constexpr int kPF = JD_PF;  // K steps per weight prefetch group
 // ------------------------------------------------------------------------------- pack
 
 // One thread writes one 16-byte element of Wp (8 consecutive hidden indices of one row).
-// src_code: kWBf16 = W holds bf16 values; kWFp8 / kWInt8 = W holds one-byte codes, converted exactly.
-__global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int layout, int src_code, int V,
-                                                      int d, int KS, int nVGalloc, size_t total,
-                                                      uint4* __restrict__ Wp) {
+__global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int layout, int V, int d, int KS,
+                                                      int nVGalloc, size_t total, uint4* __restrict__ Wp) {
   size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   int lane = (int)(idx & 63);
@@ -49,14 +47,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
   int k0 = ks * kKStep + (lane >> 4) * 8;
   union { uint4 q; uint16_t h[8]; } o;
   o.q = make_uint4(0u, 0u, 0u, 0u);
-  if (v < V && src_code != kWBf16) {
-    const uint8_t* W8 = reinterpret_cast<const uint8_t*>(W);
-    union { uint32_t w[2]; uint8_t b[8]; } c8;
-    c8.w[0] = c8.w[1] = 0u;
-    for (int e = 0; e < 8; ++e)
-      if (k0 + e < d) c8.b[e] = (layout == 0) ? W8[(size_t)v * d + k0 + e] : W8[(size_t)(k0 + e) * V + v];
-    o.q = src_code == kWFp8 ? w8x8_to_bf16x8<kWFp8>(c8.w[0], c8.w[1]) : w8x8_to_bf16x8<kWInt8>(c8.w[0], c8.w[1]);
-  } else if (v < V) {
+  if (v < V) {
     if (layout == 0) {
       if (k0 + 8 <= d && (d & 7) == 0) {
         o.q = *reinterpret_cast<const uint4*>(W + (size_t)v * d + k0);
@@ -72,15 +63,14 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
   Wp[idx] = o.q;
 }
 
-hipError_t launch_pack_w(const void* W, int layout, int src_code, const Geometry& g, void* Wp, hipStream_t st) {
+hipError_t launch_pack_w(const void* W, int layout, const Geometry& g, void* Wp, hipStream_t st) {
   if (!W || !Wp) return hipErrorInvalidValue;  // the kernel writes every element of Wp unconditionally
   const int KS = g.dpad / kKStep;
   const size_t total = (size_t)g.nVGalloc * KS * 256;
   const size_t blocks = (total + 255) / 256;
   if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(W), layout, src_code, g.V, g.d, KS, g.nVGalloc, total,
-                     static_cast<uint4*>(Wp));
+  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const uint16_t*>(W), layout,
+                     g.V, g.d, KS, g.nVGalloc, total, static_cast<uint4*>(Wp));
   return hipGetLastError();
 }
 

@@ -134,7 +134,6 @@ def test_row_block_counts_of_the_last_176_row_tile(jd, dtype):
         x = make_inputs(shape, 11)
         compare(jd.run_once(x), oracle_for(x))
     assert {l for t, l in seen if t == 1} == set(range(5, 12)) and {l for t, l in seen if t == 3} == set(range(1, 12)), seen
-    # (INT8 codes run through this kernel's own conversion on one row tile, and on the bf16 copy beyond)
 
 
 def test_bruteforce_interval_edges_on_gpu(jd):
