@@ -162,7 +162,7 @@ def measure(name: str, args, *, cpu_baseline: bool, spread: bool) -> dict:
                                         "achieved": probe, "unit": "TFLOP/s", "frac_of_peak": probe / MFMA_BF16_PEAK_TFLOPS}
         else:
             probe = jb.probe_hbm_read(0, 4 << 30)
-            roofline["device_probe"] = {"what": "pure streaming read of a 4 GiB buffer, 128-bit loads",
+            roofline["device_probe"] = {"what": "pure streaming read of a 4 GiB buffer, 128-bit non-temporal loads",
                                         "achieved": probe, "unit": "GB/s", "frac_of_peak": probe / HBM_PEAK_GBS}
         roofline["frac_of_probe"] = achieved / probe
     roofline["kernel"] = "lmhead"

@@ -278,7 +278,7 @@ int jd_verify_validate_config(const jd_verify_config* cfg);
  *       operands; 1: values spread like N(0,1), as embeddings and weights are (lower: the power
  *       drawn, hence the clock, depends on the data); 2: the same N(0,1)-like loop on the other bf16
  *       shape, v_mfma_f32_32x32x16_bf16 (the comparison behind the kernels' 16 x 16 tiles).
- *   jd_verify_probe_hbm_read: GB/s of a pure streaming read (128-bit loads, grid stride) of a
+ *   jd_verify_probe_hbm_read: GB/s of a pure streaming read (128-bit non-temporal loads, grid stride) of a
  *       zero-filled buffer of `bytes` bytes, 1 MiB <= bytes <= 64 GiB (use >= 2 GiB: smaller buffers
  *       measure the last-level cache).
  * Errors: INVALID_ARG (NULL pointer, mode, size), OOM, HIP.

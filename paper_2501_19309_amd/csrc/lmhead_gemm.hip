@@ -82,8 +82,10 @@ hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks
 // and through L2; fragments are converted to bf16 in registers one K step ahead, one instruction behind
 // an MFMA each; the per-entry scale is applied in the epilogue.
 // One tile: embedding rows rt*176 .. +175, vocabulary entries vt*256 .. +255.  NLIVE = number of the tile's 16-row
-// blocks that hold rows; the MFMAs of the others are left out at compile time.
-template <int WK, int NLIVE>
+// blocks that hold rows; the MFMAs of the others are left out at compile time.  STREAM: the launch has one row tile, so
+// every weight is read exactly once and its loads are non-temporal (3-4 % faster there; with several row tiles the
+// second reader of a vocabulary tile finds it in L2, and plain loads measure better).
+template <int WK, int NLIVE, bool STREAM>
 __device__ __forceinline__ void gemm_tile(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
     int nChunks, int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part,
@@ -97,6 +99,10 @@ __device__ __forceinline__ void gemm_tile(
 
   extern __shared__ uint4 xs_raw[];  // 2 x ITEMS x 16 B = 88 KiB (dynamic: above the static limit)
   uint4 (*xs)[ITEMS] = reinterpret_cast<uint4 (*)[ITEMS]>(xs_raw);
+  auto ldw = [](const uint4* p) -> uint4 {
+    if constexpr (STREAM) return load_stream(p);
+    else return *p;
+  };
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -183,13 +189,13 @@ __device__ __forceinline__ void gemm_tile(
     if constexpr (W8) {
       const uint4* src = wbase + wp8_pair_offset(g, nVGalloc);
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub) wbuf[buf][0][sub] = src[sub * 64 + lane];
+      for (int sub = 0; sub < 4; ++sub) wbuf[buf][0][sub] = ldw(src + sub * 64 + lane);
     } else {
       const uint4* src = wbase + wp_step_offset(g * kGemmPF, nVGalloc);
 #pragma unroll
       for (int s2 = 0; s2 < kGemmPF; ++s2)
 #pragma unroll
-        for (int sub = 0; sub < 4; ++sub) wbuf[buf][s2][sub] = src[s2 * 256 + sub * 64 + lane];
+        for (int sub = 0; sub < 4; ++sub) wbuf[buf][s2][sub] = ldw(src + s2 * 256 + sub * 64 + lane);
     }
   };
 
@@ -281,7 +287,7 @@ __device__ __forceinline__ void gemm_tile(
           if constexpr (W8) {
             if (x < NLIVE) mfma_16x16x32_bf16_inplace(acc[sub][x], cv[ks & 1][sub], bfrag[x % 3]);
             // codes of the group three ahead: four loads, in the first K step of a group only
-            if (s == 0 && sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][0][x / 2] = wsrc[(x / 2) * 64];
+            if (s == 0 && sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][0][x / 2] = ldw(wsrc + (x / 2) * 64);
             // fragments of the next K step (second half of this group's codes, or first half of the next
             // group's): 16 conversions, behind MFMA (x, 3) of every row block and five otherwise empty slots
             constexpr int cslot = (s == 0) ? slot : (slot + 1) % kGemmWBufs;
@@ -294,7 +300,7 @@ __device__ __forceinline__ void gemm_tile(
             }
           } else {
             if (x < NLIVE) mfma_16x16x32_bf16_inplace(acc[sub][x], wbuf[slot][s][sub], bfrag[x % 3]);
-            if (sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][s][x / 2] = wsrc[s * 256 + (x / 2) * 64];
+            if (sub == 0 && x % 2 == 0 && x / 2 < 4) wbuf[nslot][s][x / 2] = ldw(wsrc + s * 256 + (x / 2) * 64);
           }
           if (sub == 0 && x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < NSTAGE) stage_store(ks * 4 + x / 2);
           if (sub == 1 && x % 2 == 1 && x / 2 < 4 && ks * 4 + x / 2 < NSTAGE) stage_load(ks * 4 + x / 2);
@@ -370,8 +376,8 @@ __device__ __forceinline__ void gemm_tile(
 
 // NLAST = row blocks that hold rows in the LAST row tile of the launch (all other row tiles are full).  The branch
 // is taken once per workgroup, outside the pipelined loop: a run-time branch around single MFMAs would cost the
-// hand-dealt schedule its wait counts.
-template <int WK, int NLAST>
+// hand-dealt schedule its wait counts.  ONE: the launch has a single row tile (nRowTiles == 1).
+template <int WK, int NLAST, bool ONE>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
     int nChunks, int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L,
@@ -383,21 +389,33 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
   const int rt = j % nRowTiles;
   const int vt = (j / nRowTiles) * kXcds + xcd;
   if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
-  if (NLAST < kGemmRowBlocks && rt == nRowTiles - 1)
-    gemm_tile<WK, NLAST>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
-  else
-    gemm_tile<WK, kGemmRowBlocks>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+  if constexpr (ONE) {
+    gemm_tile<WK, NLAST, true>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, 0, vt);
+  } else {
+    if (NLAST < kGemmRowBlocks && rt == nRowTiles - 1)
+      gemm_tile<WK, NLAST, false>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+    else
+      gemm_tile<WK, kGemmRowBlocks, false>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+  }
 }
 
 constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * sizeof(uint4);
+// The single-row-tile form exists from this many row blocks on: the dispatcher gives launches of up to 64 rows to
+// the small-row kernel, so a single tile here holds at least 65 rows.
+constexpr int kGemmMinLiveOne = 5;
 
 // Instantiations by the number of 16-row blocks that hold rows in the last row tile of a launch.  With one row tile
 // (65 .. 176 rows) the kernel is bound by the weight stream - at half the bytes per weight, FP8, only once the MFMAs
 // of empty blocks are gone; with several, a ragged last tile costs only the rows it has.
 template <int WK, int NLIVE>
 static hipError_t set_lds_limit() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<WK, NLIVE>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<WK, NLIVE, false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+  if constexpr (NLIVE >= kGemmMinLiveOne)
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<WK, NLIVE, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+  return e;
 }
 template <int WK>
 static hipError_t set_lds_limits() {
@@ -427,9 +445,18 @@ hipError_t init_lmhead_gemm() {
 template <int WK, int NLIVE>
 static void launch_gemm_t(int grid, hipStream_t st, const void* W, const float* vscale, const void* Xp, int R, int nChunks,
                           const Geometry& g, int nRowTiles, int nVocabTiles, float invT, float* L, float2* part) {
-  hipLaunchKernelGGL((lmhead_gemm_kernel<WK, NLIVE>), dim3(grid), dim3(256), kGemmLdsBytes, st,
-                     static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,
-                     g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part);
+#define JD_GEMM_GO(ONE_)                                                                                            \
+  hipLaunchKernelGGL((lmhead_gemm_kernel<WK, NLIVE, ONE_>), dim3(grid), dim3(256), kGemmLdsBytes, st,             \
+                     static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,   \
+                     g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part)
+  if constexpr (NLIVE >= kGemmMinLiveOne) {
+    if (nRowTiles == 1) {
+      JD_GEMM_GO(true);
+      return;
+    }
+  }
+  JD_GEMM_GO(false);
+#undef JD_GEMM_GO
 }
 
 template <int WK>

@@ -201,7 +201,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
 #pragma unroll
   for (int s = 0; s < WS; ++s)
 #pragma unroll
-    for (int sub = 0; sub < 4; ++sub) wbuf[0][s][sub] = wptr[w_offset(0, s, sub)];
+    for (int sub = 0; sub < 4; ++sub) wbuf[0][s][sub] = load_stream(wptr + w_offset(0, s, sub));
   store_x(0, 0);
   __syncthreads();
 
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(NWAVES * 64) void lmhead_skinny_kernel(
 #pragma unroll
       for (int s = 0; s < WS; ++s)
 #pragma unroll
-        for (int sub = 0; sub < 4; ++sub) wbuf[(gi + 1) & 1][s][sub] = wptr[w_offset(gnext, s, sub)];
+        for (int sub = 0; sub < 4; ++sub) wbuf[(gi + 1) & 1][s][sub] = load_stream(wptr + w_offset(gnext, s, sub));
       // keep the prefetch ahead of this group's MFMAs: without the fence the machine
       // scheduler sinks the loads next to their uses and the stream loses its depth
       __builtin_amdgcn_sched_barrier(0);

@@ -72,7 +72,8 @@ __device__ __forceinline__ void rowstats_block(const RowStatsArgs& a, int row, i
   if (((reinterpret_cast<uintptr_t>(p) & 15) == 0)) {  // splitLen is a multiple of 4
     const int nvec = (c1 > c0) ? (c1 - c0) / 4 : 0;
     const float4* p4 = reinterpret_cast<const float4*>(p + c0);
-    // four 128-bit loads per thread are in flight before any of them is used; a batch is folded in
+    // four 128-bit loads per thread are in flight before any of them is used (non-temporal: of these rows only
+    // single elements and one row per sequence are read again); a batch is folded in
     // around its own maximum (one rescale of the running sum, sixteen independent exps)
     constexpr int kBatch = 4;
     for (int i0 = 0; i0 < nvec; i0 += 256 * kBatch) {
@@ -80,7 +81,7 @@ __device__ __forceinline__ void rowstats_block(const RowStatsArgs& a, int row, i
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int i = i0 + u * 256 + tid;
-        x[u] = (i < nvec) ? p4[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        x[u] = (i < nvec) ? load_stream(p4 + i) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
       }
       float mb = -INFINITY;
 #pragma unroll
