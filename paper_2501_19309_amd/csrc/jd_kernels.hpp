@@ -20,6 +20,11 @@ __device__ __forceinline__ float4 load_stream(const float4* p) {
   const jd_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const jd_f32x4*>(p));
   return make_float4(v.x, v.y, v.z, v.w);
 }
+// 128-bit non-temporal store, for results that the storing launch does not read back.
+__device__ __forceinline__ void store_stream(float4* p, float a, float b, float c, float d) {
+  const jd_f32x4 v = {a, b, c, d};
+  __builtin_nontemporal_store(v, reinterpret_cast<jd_f32x4*>(p));
+}
 
 // ---- packed W_lm geometry --------------------------------------------------------
 // The bf16 LM-head weight is re-tiled once, at context creation, into MFMA operand
