@@ -37,12 +37,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # instantiations share that epilogue, which moves 0.3 MB per launch; the large-row kernels are as first measured).
 # Workloads without an entry report null.
 MEASURED_TRAFFIC = {
-    "C4": (4.2531e9, "profiles/lmhead_skinny_C4_hbm_traffic.md: lmhead_skinny_kernel<2,4,0>"),
-    "C2": (1.0576e9, "profiles/lmhead_skinny_C4_hbm_traffic.md: lmhead_skinny_kernel<1,4,0>"),
-    "C4q": (2.1496e9, "profiles/verify_call_C4q_fp8_kernel_stats_and_traffic.md: lmhead_skinny_kernel<2,4,1>"),
-    "C4i": (2.1499e9, "profiles/verify_call_C4q_C4i_C5q_8bit_kernel_stats.md: lmhead_skinny_kernel<2,4,2>"),
-    "C5": (2.855e9, "profiles/lmhead_gemm_C5_counters.md: lmhead_gemm_dma_kernel<false>"),
-    "C5q": (1.8058e9, "profiles/verify_call_C4q_C4i_C5q_8bit_kernel_stats.md: lmhead_gemm_dma_kernel<true>"),
+    "C4": (4.2463e9, "profiles/lmhead_skinny_C4_hbm_traffic.md: lmhead_skinny_kernel<2,4,0>"),
+    "C2": (1.0638e9, "profiles/lmhead_skinny_C4_hbm_traffic.md: lmhead_skinny_kernel<1,4,0>"),
+    "C4q": (2.1454e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_skinny_kernel<2,4,1>"),
+    "C4i": (2.1467e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_skinny_kernel<2,4,2>"),
+    "C5": (2.855e9, "profiles/lmhead_gemm_C5_counters.md: lmhead_gemm_dma_kernel<0>"),
+    "C5q": (1.8048e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_gemm_dma_kernel<1>"),
+    "C5i": (1.8048e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_gemm_dma_kernel<2>"),
 }
 MFMA_BOUND = ("C5", "C5q", "C5i")
 SECONDARY = ("C5", "C2", "C3")   # measured after the headline workload C4, in the same process
