@@ -164,7 +164,8 @@ def measure(name: str, args, *, cpu_baseline: bool, spread: bool) -> dict:
         else:
             probe = jb.probe_hbm_read(0, 4 << 30)
             roofline["device_probe"] = {"what": "pure streaming read of a 4 GiB buffer, 128-bit non-temporal loads",
-                                        "achieved": probe, "unit": "GB/s", "frac_of_peak": probe / HBM_PEAK_GBS}
+                                        "achieved": probe, "unit": "GB/s", "frac_of_peak": probe / HBM_PEAK_GBS,
+                                        "same_read_with_plain_loads": jb.probe_hbm_read(0, 4 << 30, plain_loads=True)}
         roofline["frac_of_probe"] = achieved / probe
     roofline["kernel"] = "lmhead"
     roofline["kernel_ms"] = lm_ms

@@ -280,11 +280,14 @@ int jd_verify_validate_config(const jd_verify_config* cfg);
  *       shape, v_mfma_f32_32x32x16_bf16 (the comparison behind the kernels' 16 x 16 tiles).
  *   jd_verify_probe_hbm_read: GB/s of a pure streaming read (128-bit non-temporal loads, grid stride) of a
  *       zero-filled buffer of `bytes` bytes, 1 MiB <= bytes <= 64 GiB (use >= 2 GiB: smaller buffers
- *       measure the last-level cache).
+ *       measure the last-level cache).  jd_verify_probe_hbm_read_plain: the same kernel with plain (temporal)
+ *       loads, which reach about an eighth less on this chip - the reason the library reads everything it reads
+ *       once per launch non-temporally.
  * Errors: INVALID_ARG (NULL pointer, mode, size), OOM, HIP.
  */
 int jd_verify_probe_mfma_bf16(int32_t device, int32_t operand_mode, double* out_tflops);
 int jd_verify_probe_hbm_read(int32_t device, uint64_t bytes, double* out_gbs);
+int jd_verify_probe_hbm_read_plain(int32_t device, uint64_t bytes, double* out_gbs);
 
 #ifdef __cplusplus
 }

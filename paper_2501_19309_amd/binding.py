@@ -32,7 +32,7 @@ EXPORTED_SYMBOLS = (
     "jd_verify_create", "jd_verify_create_scaled", "jd_verify_run", "jd_verify_run_prenorm", "jd_verify_append_tokens",
     "jd_verify_destroy", "jd_verify_strerror", "jd_verify_last_error_detail",
     "jd_verify_profile_begin", "jd_verify_profile_end", "jd_verify_workspace_bytes",
-    "jd_verify_validate_config", "jd_verify_probe_mfma_bf16", "jd_verify_probe_hbm_read",
+    "jd_verify_validate_config", "jd_verify_probe_mfma_bf16", "jd_verify_probe_hbm_read", "jd_verify_probe_hbm_read_plain",
     "jd_verify_run_noalloc",
 )
 JD_NOALLOC_SCRATCH_BYTES = 16 << 20
@@ -116,6 +116,8 @@ def load_library() -> ctypes.CDLL:
     lib.jd_verify_probe_mfma_bf16.restype = ctypes.c_int
     lib.jd_verify_probe_hbm_read.argtypes = [i32, ctypes.c_uint64, ctypes.POINTER(ctypes.c_double)]
     lib.jd_verify_probe_hbm_read.restype = ctypes.c_int
+    lib.jd_verify_probe_hbm_read_plain.argtypes = [i32, ctypes.c_uint64, ctypes.POINTER(ctypes.c_double)]
+    lib.jd_verify_probe_hbm_read_plain.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -148,12 +150,14 @@ def probe_mfma_bf16(device: int = 0, operand_mode: int = 1) -> float:
     return float(v.value)
 
 
-def probe_hbm_read(device: int = 0, nbytes: int = 4 << 30) -> float:
-    """jd_verify_probe_hbm_read: GB/s of a pure streaming read of an nbytes buffer on this device."""
+def probe_hbm_read(device: int = 0, nbytes: int = 4 << 30, plain_loads: bool = False) -> float:
+    """jd_verify_probe_hbm_read(_plain): GB/s of a pure streaming read of an nbytes buffer on this device, with
+    non-temporal loads (as the library streams its weights) or, for the comparison, with plain ones."""
     v = ctypes.c_double()
-    rc = load_library().jd_verify_probe_hbm_read(device, nbytes, ctypes.byref(v))
+    name = "jd_verify_probe_hbm_read_plain" if plain_loads else "jd_verify_probe_hbm_read"
+    rc = getattr(load_library(), name)(device, nbytes, ctypes.byref(v))
     if rc != JD_OK:
-        raise JDError(rc, "jd_verify_probe_hbm_read")
+        raise JDError(rc, name)
     return float(v.value)
 
 

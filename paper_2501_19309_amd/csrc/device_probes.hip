@@ -88,9 +88,15 @@ __global__ __launch_bounds__(256) void mfma_rate_32x32_kernel(float* out, int it
 
 // Streaming read: a wavefront reads 32 KiB of consecutive memory per turn as four batches of eight 128-bit
 // non-temporal loads per lane (plain loads reach 6.0-6.2 TB/s where these reach 6.8-7.1), two batches in flight
-// while a third is folded (straight-line code inside a turn, so the compiler's wait counts are exact); the wavefronts of the grid read consecutive pieces and the grid moves
-// through the buffer as one window - the access pattern of the LM-head weight stream.
+// while a third is folded (straight-line code inside a turn, so the compiler's wait counts are exact); the
+// wavefronts of the grid read consecutive pieces and the grid moves through the buffer as one window - the access
+// pattern of the LM-head weight stream.  STREAM = false: the same with plain loads, for the comparison.
+template <bool STREAM>
 __global__ __launch_bounds__(256) void hbm_read_kernel(const uint4* __restrict__ src, size_t n_items, uint4* out) {
+  auto ld = [](const uint4* q) -> uint4 {
+    if constexpr (STREAM) return load_stream(q);
+    else return *q;
+  };
   const size_t lane = threadIdx.x & 63;
   const size_t n_chunks = n_items / 2048;                            // 2048 items = 32 KiB
   const size_t n_waves = (size_t)gridDim.x * 4;
@@ -103,22 +109,22 @@ __global__ __launch_bounds__(256) void hbm_read_kernel(const uint4* __restrict__
     const uint4* p = src + c * 2048 + lane;
     uint4 a[8], b[8], x[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) a[u] = load_stream(p + u * 64);
+    for (int u = 0; u < 8; ++u) a[u] = ld(p + u * 64);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) b[u] = load_stream(p + 512 + u * 64);
+    for (int u = 0; u < 8; ++u) b[u] = ld(p + 512 + u * 64);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < 8; ++u) x[u] = a[u];
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) a[u] = load_stream(p + 1024 + u * 64);
+    for (int u = 0; u < 8; ++u) a[u] = ld(p + 1024 + u * 64);
     __builtin_amdgcn_sched_barrier(0);
     fold(x);
 #pragma unroll
     for (int u = 0; u < 8; ++u) x[u] = b[u];
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) b[u] = load_stream(p + 1536 + u * 64);
+    for (int u = 0; u < 8; ++u) b[u] = ld(p + 1536 + u * 64);
     __builtin_amdgcn_sched_barrier(0);
     fold(x);
     fold(a);
@@ -172,7 +178,7 @@ done:
   return rc;
 }
 
-extern "C" int jd_verify_probe_hbm_read(int32_t device, uint64_t bytes, double* out_gbs) {
+static int probe_hbm_read(int32_t device, uint64_t bytes, bool stream, double* out_gbs) {
   if (!out_gbs || device < 0 || bytes < (1ull << 20) || bytes > (64ull << 30)) return JD_ERR_INVALID_ARG;
   *out_gbs = 0.0;
   int rc = JD_OK;
@@ -183,6 +189,10 @@ extern "C" int jd_verify_probe_hbm_read(int32_t device, uint64_t bytes, double* 
   int wgs = 0;
   float ms = 0.f;
   const size_t n_items = bytes / sizeof(uint4);
+  auto launch = [stream](int grid, const uint4* src, size_t n, uint4* dst) {
+    if (stream) hipLaunchKernelGGL(hbm_read_kernel<true>, dim3(grid), dim3(256), 0, nullptr, src, n, dst);
+    else hipLaunchKernelGGL(hbm_read_kernel<false>, dim3(grid), dim3(256), 0, nullptr, src, n, dst);
+  };
   JD_TRY(hipSetDevice(device));
   JD_TRY(hipGetDeviceProperties(&prop, device));
   wgs = prop.multiProcessorCount * 8;
@@ -191,10 +201,10 @@ extern "C" int jd_verify_probe_hbm_read(int32_t device, uint64_t bytes, double* 
   JD_TRY(hipMemset(buf, 0, n_items * sizeof(uint4)));
   JD_TRY(hipEventCreate(&e0));
   JD_TRY(hipEventCreate(&e1));
-  hipLaunchKernelGGL(hbm_read_kernel, dim3(wgs), dim3(256), 0, nullptr, buf, n_items, out);
+  launch(wgs, buf, n_items, out);
   JD_TRY(hipGetLastError());
   JD_TRY(hipEventRecord(e0, nullptr));
-  for (int w = 0; w < 3; ++w) hipLaunchKernelGGL(hbm_read_kernel, dim3(wgs), dim3(256), 0, nullptr, buf, n_items, out);
+  for (int w = 0; w < 3; ++w) launch(wgs, buf, n_items, out);
   JD_TRY(hipGetLastError());
   JD_TRY(hipEventRecord(e1, nullptr));
   JD_TRY(hipEventSynchronize(e1));
@@ -206,4 +216,11 @@ done:
   if (buf) (void)hipFree(buf);
   if (out) (void)hipFree(out);
   return rc;
+}
+
+extern "C" int jd_verify_probe_hbm_read(int32_t device, uint64_t bytes, double* out_gbs) {
+  return probe_hbm_read(device, bytes, true, out_gbs);
+}
+extern "C" int jd_verify_probe_hbm_read_plain(int32_t device, uint64_t bytes, double* out_gbs) {
+  return probe_hbm_read(device, bytes, false, out_gbs);
 }

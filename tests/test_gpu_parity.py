@@ -791,15 +791,19 @@ def test_device_probes(jd):
     lib = jb.load_library()
     tf = jb.probe_mfma_bf16(0, 1)
     gbs = jb.probe_hbm_read(0, 2 << 30)
+    gbs_plain = jb.probe_hbm_read(0, 2 << 30, plain_loads=True)
     tf32 = jb.probe_mfma_bf16(0, 2)
-    print(f"[probe] mfma bf16 16x16x32 {tf:.0f} TFLOP/s, 32x32x16 {tf32:.0f} TFLOP/s, hbm read {gbs:.0f} GB/s", flush=True)
+    print(f"[probe] mfma bf16 16x16x32 {tf:.0f} TFLOP/s, 32x32x16 {tf32:.0f} TFLOP/s, hbm read {gbs:.0f} GB/s "
+          f"(plain loads {gbs_plain:.0f})", flush=True)
     assert 300.0 < tf <= 2600.0 and 1000.0 < gbs <= 8200.0      # below the published peaks, far above a broken loop
+    assert 1000.0 < gbs_plain <= 8200.0
     assert 300.0 < tf32 <= 2600.0
     v = ctypes.c_double()
     assert lib.jd_verify_probe_mfma_bf16(0, 7, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_verify_probe_mfma_bf16(0, 1, None) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_verify_probe_hbm_read(0, 1000, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
     assert lib.jd_verify_probe_hbm_read(-1, 1 << 30, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
+    assert lib.jd_verify_probe_hbm_read_plain(0, 1000, ctypes.byref(v)) == jb.JD_ERR_INVALID_ARG
 
 
 def test_bench_json_contract(repo_root):
