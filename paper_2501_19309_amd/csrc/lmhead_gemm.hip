@@ -140,11 +140,11 @@ __device__ __forceinline__ void gemm_tile(
   uint4 xa0, xa1, xa2, xa3, xb0, xb1, xb2, xb3, xc0, xc1, xc2;
 
   // item i of a thread belongs to row block i of the tile (items are laid out row block by row block, 256 per
-  // block): blocks without rows are never read back from LDS, and with FP8 weights neither loaded nor staged
-  // (measured both ways: 66 rows FP8 0.220 -> 0.197 ms, 374 rows FP8 0.723 -> 0.683 ms; with bf16 weights leaving
-  // the staging out makes ragged multi-tile launches 2-4 % slower - 374 rows 0.783 -> 0.819 ms - and single tiles no
-  // faster, so there the zero rows keep travelling)
-  constexpr int NSTAGE = W8 ? NLIVE : NXB;
+  // block): blocks without rows are never read back from LDS.  With one-byte weights, and in launches with a single
+  // row tile, they are neither loaded nor staged (66 rows FP8 0.220 -> 0.197 ms, 374 rows FP8 0.723 -> 0.683 ms,
+  // 66-110 rows bf16 0.338-0.344 -> 0.334-0.337 ms); with bf16 weights on several row tiles leaving the staging out
+  // makes ragged launches 2-4 % slower (374 rows 0.783 -> 0.819 ms), so there the zero rows keep travelling
+  constexpr int NSTAGE = (W8 || STREAM) ? NLIVE : NXB;
   auto load_portion = [&](const uint4* src, auto pc) {
     constexpr int p = decltype(pc)::value;
     if constexpr (p == 0) {
