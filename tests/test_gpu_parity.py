@@ -1158,7 +1158,7 @@ def test_full_size_prenorm_C4(jd):
     print("C4 prenorm", rep, flush=True)
 
 
-@pytest.mark.parametrize("name,seed", [("C5", 0), ("C5", 1), ("C5q", 0)], ids=lambda v: str(v))
+@pytest.mark.parametrize("name,seed", [("C5", 0), ("C5", 1), ("C5q", 0), ("C5i", 0)], ids=lambda v: str(v))
 def test_full_size_batched_sampled_sequences(jd, name, seed):
     # B = 64 sequences are independent, so the oracle checks a sample of them exactly: 16 sequences, eight in each
     # of the two 352-row tiles of the launch (sequences 0..31 and 32..63), first and last rows of both included
