@@ -152,6 +152,15 @@ constexpr int kGemmRows = kGemmRowBlocks * 16;     // 176: 704 = 4 x 176, no pad
 constexpr int kGemmKChunk = 128;                   // hidden indices per LDS-staged chunk
 constexpr int kDmaRowBlocks = 22;                  // 352-row tiles of the second tiling (two 176-row halves)
 constexpr int kDmaRows = kDmaRowBlocks * 16;
+constexpr int kDmaMinHalfBlocks = 6;               // fewest row blocks per half the 352-row kernel is instantiated for
+// 16-row blocks per row half that hold rows in the last 352-row tile of an R-row launch: its rows are spread over
+// both halves (half 1 starts at row dma_half_blocks * 16 of the tile), so that both row halves of a workgroup
+// run equally long K steps.
+inline int dma_half_blocks(int R) {
+  const int last = R - (R - 1) / kDmaRows * kDmaRows;  // 1 .. 352 rows in the last tile
+  const int b = (last + 31) / 32;
+  return b < kDmaMinHalfBlocks ? kDmaMinHalfBlocks : b;
+}
 inline size_t gemm_xp_bytes(int R, const Geometry& g) {  // enough for either tiling
   return (size_t)((R + kDmaRows - 1) / kDmaRows) * kDmaRows * (size_t)g.dpad * 2;
 }
@@ -174,8 +183,10 @@ inline bool gemm_prefers_352(int R) {
 }
 // Re-tile bf16 embeddings X[R][d] into MFMA fragment order Xp[rt][chunk][xb][s][lane][8] (row tiles of
 // rowBlocks*16 rows, chunks of `steps` K steps), zero padded.
-hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks, int rowBlocks, int steps, void* Xp,
-                         hipStream_t st);
+// splitRt >= 0: that row tile is laid out in two halves of rowBlocks/2 block positions, of which the first halfBlocks
+// hold rows (the 352-row kernel's ragged last tile); -1: none.
+hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks, int rowBlocks, int steps, int splitRt,
+                         int halfBlocks, void* Xp, hipStream_t st);
 
 // fp32 LM head (any layout), plain FMA; writes logits only.
 hipError_t launch_lmhead_f32(const float* W, int layout, const float* X, int R, int d, int V, float invT,

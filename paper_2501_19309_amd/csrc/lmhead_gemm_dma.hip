@@ -91,30 +91,51 @@ __device__ __forceinline__ void set_m0(unsigned lds_byte) { asm volatile("s_mov_
 __device__ __forceinline__ void dma_issue(const uint4* gbase, unsigned lane_off) {
   asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase) : "memory");
 }
+// Non-temporal forms, for weights that the call reads once (see load_stream).
+__device__ __forceinline__ void dma_1k_stream(const uint4* gsrc, unsigned lds_byte, unsigned lane16) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+               :: "s"(lds_byte), "v"(lane16), "s"(gsrc) : "memory");
+}
+__device__ __forceinline__ void dma_issue_stream(const uint4* gbase, unsigned lane_off) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 nt" ::"v"(lane_off), "s"(gbase) : "memory");
+}
 
 // WK = kWBf16: Wsrc is the re-tiled bf16 copy Wp.  WK = kWFp8, kWInt8: Wsrc is the one-byte copy Wg8 (see
 // pack_w8g_kernel): half the weight bytes through L2, L1 and LDS; fragments are converted to bf16 in registers
 // behind MFMAs that carry nothing else, one K step ahead (one instruction per two FP8 codes, three per two INT8
 // codes); the per-entry scale is applied in the epilogue.
-template <int WK>
-__global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
-    const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
-    int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld,
-    float2* __restrict__ part) {
-  constexpr bool W8 = WK != kWBf16;
-  constexpr int kStageItems = kDmaStageItems<W8>;
-  constexpr int kNW = W8 ? 2 : 4;       // direct-to-LDS loads of weights per wavefront and K step
-  constexpr int kPieces = kNW + 6;      // + up to six embedding row blocks
-  extern __shared__ uint4 lds[];  // kDmaStages stages of [22 x 64 embedding items][weight items]
+// Which weight sub-block (0..7) of the next K step a bf16 tile reads behind MFMA (row block x, sub-block sb); -1: none.
+constexpr int dma_wf_slot(int x, int sb, int nlive) {
+  if (sb == 3 && x >= 1 && x <= 8 && x <= nlive - 1) return x - 1;
+  if (sb == 7 && x >= 1 && (nlive - 1) + (x - 1) < 8) return (nlive - 1) + (x - 1);
+  return -1;
+}
+// Which direct-to-LDS piece has its M0 write (2*p) or its load (2*p + 1) behind MFMA (x, sb); -1: none.
+constexpr int dma_piece_slot(int x, int sb, int nlive, int pieces) {
+  if (x < 1) return -1;
+  if ((sb == 5 || sb == 6) && x <= pieces && x <= nlive - 1) return 2 * (x - 1) + (sb == 6);
+  if ((sb == 2 || sb == 4) && (nlive - 1) + (x - 1) < pieces) return 2 * ((nlive - 1) + (x - 1)) + (sb == 4);
+  return -1;
+}
 
-  // XCD-aware tile id: the row tiles that stream the same 256 vocabulary rows get ids that the
-  // hardware deals to one XCD, so W_lm crosses from HBM into one L2 only.
-  const int bid = blockIdx.x;
-  const int xcd = bid % kXcds;
-  const int j = bid / kXcds;
-  const int rt = j % nRowTiles;
-  const int vt = (j / nRowTiles) * kXcds + xcd;
-  if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
+// One tile: rows rt*352 .. and vocabulary entries vt*256 .. +255.  NLIVE = 16-row blocks per row half that hold rows
+// (dma_half_blocks(): 11 for a full tile; a ragged last tile spreads its rows over both halves, NLIVE blocks each,
+// half 1 starting at row NLIVE*16 of the tile).  Blocks beyond NLIVE are neither loaded nor multiplied: a K step is
+// 8*NLIVE MFMAs long.  One-byte weights are instantiated for full tiles only.  STREAM: the call has a single row
+// tile, every weight is read once, and the weight loads are non-temporal.
+template <int WK, int NLIVE, bool STREAM>
+__device__ __forceinline__ void dma_tile(
+    const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
+    int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part, const int rt,
+    const int vt) {
+  constexpr bool W8 = WK != kWBf16;
+  static_assert(NLIVE >= kDmaMinHalfBlocks && NLIVE <= kDmaWaveRowBlocks && (!W8 || NLIVE == kDmaWaveRowBlocks), "instantiated tiles");
+  constexpr int kStageItems = kDmaStageItems<W8>;
+  constexpr int kNW = W8 ? 2 : 4;            // direct-to-LDS loads of weights per wavefront and K step
+  constexpr int PXhi = (NLIVE + 1) / 2;      // embedding row blocks per K step of wavefronts 0, 1 (2*NLIVE dealt to four)
+  constexpr int PXlo = NLIVE / 2;            // ... of wavefronts 2, 3
+  constexpr int kPieces = kNW + PXhi;
+  extern __shared__ uint4 lds[];  // kDmaStages stages of [22 x 64 embedding items][weight items]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -126,34 +147,39 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)lds;
 
   // direct-to-LDS sources of this wavefront: the weights of vocabulary group vt*4 + wave (< nVGalloc,
-  // allocated in multiples of 8 groups; 4 KiB per K step as bf16, 2 KiB as FP8), and embedding row
-  // blocks wave, wave+4, .. (< 22)
+  // allocated in multiples of 8 groups; 4 KiB per K step as bf16, 2 KiB as FP8), and the embedding row
+  // blocks number wave, wave+4, .. of the 2*NLIVE that hold rows (block (rh, x) sits at position rh*11 + x
+  // of a K step, in Xp and in the stage alike)
   const uint4* wsrc0 = W8 ? Wsrc + (size_t)(vt * 4 + wave) * 128 : Wsrc + wp_group_offset(vt * 4 + wave);
   const size_t wStep8 = (size_t)nVGalloc * 128;  // FP8: 16-byte items between consecutive K steps
-  const uint4* xsrc0 = Xp + ((size_t)rt * KS * kDmaRowBlocks + wave) * 64;
-  const bool six = wave < 2;  // wavefronts 0, 1 own six embedding row blocks, 2, 3 own five
+  const uint4* xsrc0 = Xp + (size_t)rt * KS * kDmaRowBlocks * 64;
+  const bool more = (NLIVE % 2 == 0) || wave < 2;  // NLIVE odd: wavefronts 0, 1 own one row block more than 2, 3
   const unsigned ldsW0 = lds0 + (unsigned)(kDmaXItems + wave * kNW * 64) * 16;
-  const unsigned ldsX0 = lds0 + (unsigned)(wave * 64) * 16;
+  unsigned xblk[PXhi];  // position of this wavefront's q-th row block (wave-uniform)
+#pragma unroll
+  for (int q = 0; q < PXhi; ++q) {
+    const int li = min(wave + 4 * q, 2 * NLIVE - 1);
+    xblk[q] = (unsigned)((li / NLIVE) * kDmaWaveRowBlocks + li % NLIVE);
+  }
 
   // Wait until at most `groups` K steps of this wavefront's direct-to-LDS loads are outstanding and all
-  // its LDS reads have returned.  Wavefronts 0, 1 issue kPieces loads per step and 2, 3 one fewer; loads
+  // its LDS reads have returned.  With NLIVE odd, wavefronts 0, 1 issue one load more per step than 2, 3; loads
   // complete in issue order, so the count for the smaller number is right for both (0, 1 then also wait
   // for the first one or two loads of the following, much older, step).
   auto wait_groups = [&](auto gc) {
     constexpr int g = decltype(gc)::value;
-    if constexpr (g == 3 && !W8) asm volatile("s_waitcnt vmcnt(27) lgkmcnt(0)" ::: "memory");
-    if constexpr (g == 2 && !W8) asm volatile("s_waitcnt vmcnt(18) lgkmcnt(0)" ::: "memory");
-    if constexpr (g == 3 && W8) asm volatile("s_waitcnt vmcnt(21) lgkmcnt(0)" ::: "memory");
-    if constexpr (g == 2 && W8) asm volatile("s_waitcnt vmcnt(14) lgkmcnt(0)" ::: "memory");
-    if constexpr (g == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    constexpr int outstanding = g * (kNW + PXlo);
+    static_assert(outstanding < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(outstanding) : "memory");
   };
-  static_assert(3 * (kPieces - 1) == (W8 ? 21 : 27) && 2 * (kPieces - 1) == (W8 ? 14 : 18), "wait counts above");
+  static_assert(NLIVE != kDmaWaveRowBlocks || (3 * (kNW + PXlo) == (W8 ? 21 : 27) && 2 * (kNW + PXlo) == (W8 ? 14 : 18)),
+                "full tiles: 27 / 18 loads (bf16), 21 / 14 (one-byte weights)");
 
   f32x4 acc[8][kDmaWaveRowBlocks];
 #pragma unroll
   for (int s = 0; s < 8; ++s)
 #pragma unroll
-    for (int x = 0; x < kDmaWaveRowBlocks; ++x) acc[s][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int x = 0; x < NLIVE; ++x) acc[s][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   uint4 xf[kDmaWaveRowBlocks];  // embedding fragments of the current K step, refilled in place
   uint4 wf[2][8];               // weight fragments (bf16): current step / next step
@@ -166,10 +192,13 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     const uint4* wg = W8 ? wsrc0 + (size_t)s * wStep8 : wsrc0 + wp_step_offset(s, nVGalloc);
     const uint4* xg = xsrc0 + (size_t)s * (kDmaRowBlocks * 64);
 #pragma unroll
-    for (int p = 0; p < kNW; ++p) dma_1k(wg + p * 64, ldsW0 + dst + p * 1024, lane16);
+    for (int p = 0; p < kNW; ++p) {
+      if constexpr (STREAM) dma_1k_stream(wg + p * 64, ldsW0 + dst + p * 1024, lane16);
+      else dma_1k(wg + p * 64, ldsW0 + dst + p * 1024, lane16);
+    }
 #pragma unroll
-    for (int q = 0; q < 6; ++q)
-      if (q < 5 || six) dma_1k(xg + q * 256, ldsX0 + dst + q * 4096, lane16);
+    for (int q = 0; q < PXhi; ++q)
+      if (q < PXlo || more) dma_1k(xg + xblk[q] * 64, lds0 + dst + xblk[q] * 1024, lane16);
   }
   wait_groups(std::integral_constant<int, 3>{});
   __builtin_amdgcn_s_barrier();
@@ -177,7 +206,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   {
     const uint4* xr = lds + rh * kDmaWaveRowBlocks * 64 + lane;
 #pragma unroll
-    for (int x = 0; x < kDmaWaveRowBlocks; ++x) xf[x] = xr[x * 64];
+    for (int x = 0; x < NLIVE; ++x) xf[x] = xr[x * 64];
     if constexpr (W8) {
       const uint2* wr = reinterpret_cast<const uint2*>(lds + kDmaXItems) + vh * 8 * 64 + lane;
 #pragma unroll
@@ -211,7 +240,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     // (branch-free, unread).
     const uint4* wg = W8 ? wIter + (size_t)ST * wStep8 : wIter + ST * 256;
     const uint4* xg = xIter + ST * (kDmaRowBlocks * 64);
-    static_for<0, 8 * kDmaWaveRowBlocks>([&](auto ic) {
+    static_for<0, 8 * NLIVE>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       constexpr int x = i / 8, sb = i % 8;  // row block, weight sub-block
       mfma_inplace<acc_in_agpr(x, sb)>(acc[sb][x], wf[cur][sb], xf[x]);
@@ -223,25 +252,34 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
         asm volatile("" ::: "memory");  // no LDS read moves above the barrier
       }
       if constexpr (x >= 1 && sb == 1) xf[x - 1] = xr[(x - 1) * 64];  // row block x-1 of step k+1, in place
-      if constexpr (i == 8 * kDmaWaveRowBlocks - 1) xf[x] = xr[x * 64];
+      if constexpr (i == 8 * NLIVE - 1) xf[x] = xr[x * 64];
       if constexpr (W8) {
         // weight sub-block x-1 of step k+1: codes read behind MFMA (x, 0), converted behind MFMAs (x+1, 2..5),
         // so that every MFMA of the step has at most one vector, LDS or memory instruction behind it
         if constexpr (x >= 2 && x <= 9 && sb >= 2 && sb <= 5) set_dword(wf[nxt][x - 2], sb - 2, w8_frag_dword<WK>(raw[x - 2].x, raw[x - 2].y, sb - 2));
         if constexpr (x >= 1 && x <= 8 && sb == 0) raw[x - 1] = wr8[(x - 1) * 64];
       } else {
-        if constexpr (x >= 1 && x <= 8 && sb == 3) wf[nxt][x - 1] = wr[(x - 1) * 64];  // weight sub-block x-1
+        // weight sub-block s behind MFMA (s+1, 3); with fewer than nine row blocks the last ones behind (.., 7)
+        constexpr int ws = dma_wf_slot(x, sb, NLIVE);
+        if constexpr (ws >= 0) wf[nxt][ws] = wr[ws * 64];
       }
-      if constexpr (x >= 1 && x <= kPieces && (sb == 5 || sb == 6)) {  // piece x-1: weights first, then row blocks wave+4q
-        constexpr int p = x - 1, q = p - kNW;
-        if constexpr (p < kNW) {
-          if constexpr (sb == 5) set_m0(ldsW0 + stageByte + p * 1024);
-          if constexpr (sb == 6) dma_issue(wg, lane16 + p * 1024);
-        } else if constexpr (q < 5) {
-          if constexpr (sb == 5) set_m0(ldsX0 + stageByte + q * 4096);
-          if constexpr (sb == 6) dma_issue(xg, lane16 + q * 4096);
-        } else if constexpr (sb == 6) {
-          if (six) dma_1k(xg + q * 256, ldsX0 + stageByte + q * 4096, lane16);  // sixth row block: wavefronts 0, 1
+      {
+        // direct-to-LDS piece p (weights first, then this wavefront's row blocks): M0 write and load behind
+        // MFMAs (p+1, 5) and (p+1, 6); pieces that find no row block of their own there behind (.., 2) and (.., 4)
+        constexpr int pp = dma_piece_slot(x, sb, NLIVE, kPieces);  // 2*p + (0: M0 write, 1: load), or -1
+        if constexpr (pp >= 0) {
+          constexpr int p = pp / 2, q = p - kNW;
+          constexpr bool issue = (pp % 2) != 0;
+          if constexpr (p < kNW) {
+            if constexpr (!issue) set_m0(ldsW0 + stageByte + p * 1024);
+            else if constexpr (STREAM) dma_issue_stream(wg, lane16 + p * 1024);
+            else dma_issue(wg, lane16 + p * 1024);
+          } else if constexpr (q < PXlo) {
+            if constexpr (!issue) set_m0(lds0 + stageByte + xblk[q] * 1024);
+            else dma_issue(xg + xblk[q] * 64, lane16);
+          } else if constexpr (issue) {
+            if (more) dma_1k(xg + xblk[q] * 64, lds0 + stageByte + xblk[q] * 1024, lane16);  // wavefronts 0, 1 only
+          }
         }
       }
       __builtin_amdgcn_sched_barrier(0);  // keep this dealing-out as written
@@ -265,7 +303,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   __builtin_amdgcn_sched_barrier(0);
 
-  // epilogue: acc[s][x][i] = logit of row rt*352 + rh*176 + x*16 + n,
+  // epilogue: acc[s][x][i] = logit of row rt*352 + rh*NLIVE*16 + x*16 + n,
   //           vocabulary entry (vt*4 + vh*2 + s/4)*64 + (s%4)*16 + gq*4 + i
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
@@ -280,8 +318,8 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
         osc[sub][i] = (vscale != nullptr && v < V) ? vscale[v] * invT : invT;
       }
 #pragma unroll
-    for (int x = 0; x < kDmaWaveRowBlocks; ++x) {
-      const int r = rt * kDmaRows + rh * (kDmaWaveRowBlocks * 16) + x * 16 + n;
+    for (int x = 0; x < NLIVE; ++x) {
+      const int r = rt * kDmaRows + rh * (NLIVE * 16) + x * 16 + n;
       float vals[4][4];
       float mx = -INFINITY;
 #pragma unroll
@@ -316,6 +354,25 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
       }
     }
   }
+}
+
+// One launch runs row tiles rt0 .. rt0 + nRowTiles - 1, all with NLIVE row blocks per half: the full row tiles of a
+// call in one launch, a ragged last row tile in a launch of its own (one body per kernel: with a second body behind a
+// branch the register allocator has to spill, and it does so around the MFMAs it cannot see into).
+template <int WK, int NLIVE, bool STREAM>
+__global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
+    const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
+    int V, int nVG, int nVGalloc, int rt0, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld,
+    float2* __restrict__ part) {
+  // XCD-aware tile id: the row tiles that stream the same 256 vocabulary rows get ids that the
+  // hardware deals to one XCD, so W_lm crosses from HBM into one L2 only.
+  const int bid = blockIdx.x;
+  const int xcd = bid % kXcds;
+  const int j = bid / kXcds;
+  const int rt = rt0 + j % nRowTiles;
+  const int vt = (j / nRowTiles) * kXcds + xcd;
+  if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
+  dma_tile<WK, NLIVE, STREAM>(Wsrc, vscale, Xp, R, KS, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
 }
 
 // Wg8[ks][vg][sub][lane][8 B]: the FP8 E4M3 codes of W_lm in MFMA fragment order for this kernel, one
@@ -353,36 +410,71 @@ hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* 
 
 // More LDS than the default limit of a launch: raised once per process, at context creation (not in the
 // launcher, which may run under stream capture).
+template <int WK, int NLAST>
+static hipError_t dma_lds_limit() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<WK, NLAST, false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<WK != kWBf16>);
+  if constexpr (WK == kWBf16)
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<WK, NLAST, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<false>);
+  return e;
+}
+
 hipError_t init_lmhead_gemm_dma() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<kWBf16>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<false>);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<kWFp8>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<true>);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<kWInt8>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<true>);
+  hipError_t e = dma_lds_limit<kWBf16, 6>();
+  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 7>();
+  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 8>();
+  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 9>();
+  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 10>();
+  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 11>();
+  if (e == hipSuccess) e = dma_lds_limit<kWFp8, 11>();
+  if (e == hipSuccess) e = dma_lds_limit<kWInt8, 11>();
+  return e;
 }
 
 hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale, const void* X, int R,
                                   const Geometry& g, float invT, float* L, float2* part, void* Xp, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
   static_assert(kWpKG * 256 == 4 * 256 && kKStep == 32, "a K step of one vocabulary group is 4 KiB, contiguous");
+  static_assert(kDmaMinHalfBlocks == 6, "instantiations below");
   if (R <= 0 || !Xp || !W) return hipErrorInvalidValue;
   const int nRowTiles = (R + kDmaRows - 1) / kDmaRows;
   const int KS = g.dpad / kKStep;  // multiple of 8
   if (KS < 2 * kDmaStages) return hipErrorInvalidValue;
-  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, KS, kDmaRowBlocks, 1, Xp, st);
+  // row blocks per half of the last row tile; one-byte weights always run full tiles
+  const int nlast = w_code == kWBf16 ? dma_half_blocks(R) : kDmaWaveRowBlocks;
+  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, KS, kDmaRowBlocks, 1, nRowTiles - 1, nlast, Xp, st);
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
-  const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
-#define JD_DMA(WK_)                                                                                              \
-  hipLaunchKernelGGL(lmhead_gemm_dma_kernel<WK_>, dim3(grid), dim3(256), kDmaLdsBytes<(WK_) != kWBf16>, st,      \
-                     static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG,     \
-                     g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part)
-  if (w_code == kWFp8) JD_DMA(kWFp8);
-  else if (w_code == kWInt8) JD_DMA(kWInt8);
-  else JD_DMA(kWBf16);
+  const int perRt = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds;  // workgroups per row tile
+#define JD_DMA(WK_, NL_, ST_, RT0_, NRT_)                                                                         \
+  hipLaunchKernelGGL((lmhead_gemm_dma_kernel<WK_, NL_, ST_>), dim3(perRt * (NRT_)), dim3(256),                     \
+                     kDmaLdsBytes<(WK_) != kWBf16>, st, static_cast<const uint4*>(W), vscale,                      \
+                     static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG, g.nVGalloc, RT0_, NRT_, nVocabTiles, invT, \
+                     L, g.Vpad, part)
+#define JD_DMA_LAST(ST_)                                                  \
+  switch (nlast) {                                                        \
+    case 6: JD_DMA(kWBf16, 6, ST_, nRowTiles - 1, 1); break;             \
+    case 7: JD_DMA(kWBf16, 7, ST_, nRowTiles - 1, 1); break;             \
+    case 8: JD_DMA(kWBf16, 8, ST_, nRowTiles - 1, 1); break;             \
+    case 9: JD_DMA(kWBf16, 9, ST_, nRowTiles - 1, 1); break;             \
+    case 10: JD_DMA(kWBf16, 10, ST_, nRowTiles - 1, 1); break;           \
+    default: JD_DMA(kWBf16, 11, ST_, nRowTiles - 1, 1); break;           \
+  }
+  if (w_code == kWFp8) {
+    JD_DMA(kWFp8, 11, false, 0, nRowTiles);
+  } else if (w_code == kWInt8) {
+    JD_DMA(kWInt8, 11, false, 0, nRowTiles);
+  } else if (nRowTiles == 1) {
+    JD_DMA_LAST(true);  // one row tile: every weight is read once
+  } else if (nlast == kDmaWaveRowBlocks) {
+    JD_DMA(kWBf16, 11, false, 0, nRowTiles);
+  } else {
+    JD_DMA(kWBf16, 11, false, 0, nRowTiles - 1);  // the full row tiles
+    JD_DMA_LAST(false);                           // the ragged last one
+  }
+#undef JD_DMA_LAST
 #undef JD_DMA
   return hipGetLastError();
 }
