@@ -169,7 +169,8 @@ inline size_t gemm_xp_bytes(int R, const Geometry& g) {  // enough for either ti
 hipError_t launch_lmhead_gemm(const void* W, int w_code, const float* vscale, const void* X, int R, const Geometry& g,
                               float invT, float* L, float2* part, void* Xp, hipStream_t st);
 // The same projection on 352-row x 256-entry tiles with both operands shared through LDS; the better
-// choice when gemm_prefers_352(R), i.e. when 352-row tiles add no padding rows over 176-row tiles.
+// choice when gemm_prefers_352(R, w_code): when 352-row tiles add no padding rows over 176-row tiles, and for bf16
+// weights from three 352-row tiles on.
 // w_code kWFp8 / kWInt8: W is Wg8, the one-byte copy that launch_pack_w8g builds (Geometry::packed8_bytes() bytes),
 // and vscale holds the per-entry scales; kWBf16: W is the bf16 Wp.
 hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale, const void* X, int R,
@@ -178,7 +179,11 @@ hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* 
 // Once per process before the first launch of either kernel (they use more dynamic LDS than the default limit).
 hipError_t init_lmhead_gemm();
 hipError_t init_lmhead_gemm_dma();
-inline bool gemm_prefers_352(int R) {
+inline bool gemm_prefers_352(int R, int w_code) {
+  // bf16 weights also from three 352-row tiles on: a ragged last tile then costs less there than a fifth or sixth
+  // 176-row tile (792 rows 1.41 against 1.44 ms, 880 rows 1.44 against 1.49 ms at d = 8192); one-byte weights run
+  // full 352-row tiles only
+  if (w_code == kWBf16 && R > 2 * kDmaRows) return true;
   return (R + kDmaRows - 1) / kDmaRows * kDmaRows == (R + kGemmRows - 1) / kGemmRows * kGemmRows;
 }
 // Re-tile bf16 embeddings X[R][d] into MFMA fragment order Xp[rt][chunk][xb][s][lane][8] (row tiles of

@@ -136,6 +136,31 @@ def test_row_block_counts_of_the_last_176_row_tile(jd, dtype):
     assert {l for t, l in seen if t == 1} == set(range(5, 12)) and {l for t, l in seen if t == 3} == set(range(1, 12)), seen
 
 
+def test_ragged_last_352_row_tile(jd):
+    # The 352-row kernel spreads the rows of a ragged last row tile over both row halves and is instantiated per number
+    # of 16-row blocks per half that hold rows (6 .. 11).  One row tile: every instantiation, rows ending inside half 0,
+    # at its end and inside half 1.  Several row tiles: the ragged tile in a launch of its own (up to 8 blocks per half,
+    # down to a single row) and inside the shared launch (more).
+    cases = [(3, 58), (20, 9), (24, 9), (27, 9), (30, 9), (34, 9),          # 177 .. 340 rows: 6 .. 11 blocks per half
+             (12, 15), (13, 15), (18, 15), (22, 15),                        # 192, 208, 288, 352 rows: block boundaries
+             (23, 22), (60, 9), (62, 9),                                    # 529, 600, 620 rows: two row tiles
+             (47, 14), (80, 9), (81, 9), (88, 10), (104, 10)]               # 705, 800, 810, 968, 1144 rows: three, four
+    seen = set()
+    for B, M in cases:
+        R = B * (M + 1)
+        tiles = (R + 351) // 352
+        last = R - (tiles - 1) * 352
+        half = max(6, (last + 31) // 32)
+        own_launch = tiles > 1 and half <= 8
+        seen.add((min(tiles, 3), half if (tiles == 1 or own_launch) else 11))
+        shape = VerifyShape(f"ragged352_R{R}", B, M, 144, 600, "bf16", 1.2)
+        print(f"[case] {shape.name} ({tiles} row tiles, {last} rows in the last, {half} blocks per half)", flush=True)
+        x = make_inputs(shape, 12)
+        compare(jd.run_once(x), oracle_for(x))
+    assert {h for t, h in seen if t == 1} == set(range(6, 12)), seen
+    assert {(2, 6), (2, 8), (2, 11), (3, 6), (3, 11)} <= seen, seen
+
+
 def test_bruteforce_interval_edges_on_gpu(jd):
     # the V = 8, M = 3 enumeration of tests/test_oracle_pins.py (every accept interval and every
     # CDF interval probed 1e-6 inside both ends) through the HIP library, ~30 k sequences in one call
