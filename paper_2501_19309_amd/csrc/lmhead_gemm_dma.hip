@@ -91,14 +91,6 @@ __device__ __forceinline__ void set_m0(unsigned lds_byte) { asm volatile("s_mov_
 __device__ __forceinline__ void dma_issue(const uint4* gbase, unsigned lane_off) {
   asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase) : "memory");
 }
-// Non-temporal forms, for weights that the call reads once (see load_stream).
-__device__ __forceinline__ void dma_1k_stream(const uint4* gsrc, unsigned lds_byte, unsigned lane16) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
-               :: "s"(lds_byte), "v"(lane16), "s"(gsrc) : "memory");
-}
-__device__ __forceinline__ void dma_issue_stream(const uint4* gbase, unsigned lane_off) {
-  asm volatile("global_load_lds_dwordx4 %0, %1 nt" ::"v"(lane_off), "s"(gbase) : "memory");
-}
 
 // WK = kWBf16: Wsrc is the re-tiled bf16 copy Wp.  WK = kWFp8, kWInt8: Wsrc is the one-byte copy Wg8 (see
 // pack_w8g_kernel): half the weight bytes through L2, L1 and LDS; fragments are converted to bf16 in registers
@@ -121,15 +113,15 @@ constexpr int dma_piece_slot(int x, int sb, int nlive, int pieces) {
 // One tile: rows rt*352 .. and vocabulary entries vt*256 .. +255.  NLIVE = 16-row blocks per row half that hold rows
 // (dma_half_blocks(): 11 for a full tile; a ragged last tile spreads its rows over both halves, NLIVE blocks each,
 // half 1 starting at row NLIVE*16 of the tile).  Blocks beyond NLIVE are neither loaded nor multiplied: a K step is
-// 8*NLIVE MFMAs long.  One-byte weights are instantiated for full tiles only.  STREAM: the call has a single row
-// tile, every weight is read once, and the weight loads are non-temporal.
-template <int WK, int NLIVE, bool STREAM>
+// 8*NLIVE MFMAs long.  (Non-temporal weight loads for calls with a single row tile were measured: 0.376 -> 0.372 ms at
+// 187 rows, within the noise elsewhere; not kept.)
+template <int WK, int NLIVE>
 __device__ __forceinline__ void dma_tile(
     const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
     int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part, const int rt,
     const int vt) {
   constexpr bool W8 = WK != kWBf16;
-  static_assert(NLIVE >= kDmaMinHalfBlocks && NLIVE <= kDmaWaveRowBlocks && (!W8 || NLIVE == kDmaWaveRowBlocks), "instantiated tiles");
+  static_assert(NLIVE >= kDmaMinHalfBlocks && NLIVE <= kDmaWaveRowBlocks, "instantiated tiles");
   constexpr int kStageItems = kDmaStageItems<W8>;
   constexpr int kNW = W8 ? 2 : 4;            // direct-to-LDS loads of weights per wavefront and K step
   constexpr int PXhi = (NLIVE + 1) / 2;      // embedding row blocks per K step of wavefronts 0, 1 (2*NLIVE dealt to four)
@@ -192,10 +184,7 @@ __device__ __forceinline__ void dma_tile(
     const uint4* wg = W8 ? wsrc0 + (size_t)s * wStep8 : wsrc0 + wp_step_offset(s, nVGalloc);
     const uint4* xg = xsrc0 + (size_t)s * (kDmaRowBlocks * 64);
 #pragma unroll
-    for (int p = 0; p < kNW; ++p) {
-      if constexpr (STREAM) dma_1k_stream(wg + p * 64, ldsW0 + dst + p * 1024, lane16);
-      else dma_1k(wg + p * 64, ldsW0 + dst + p * 1024, lane16);
-    }
+    for (int p = 0; p < kNW; ++p) dma_1k(wg + p * 64, ldsW0 + dst + p * 1024, lane16);
 #pragma unroll
     for (int q = 0; q < PXhi; ++q)
       if (q < PXlo || more) dma_1k(xg + xblk[q] * 64, lds0 + dst + xblk[q] * 1024, lane16);
@@ -256,8 +245,20 @@ __device__ __forceinline__ void dma_tile(
       if constexpr (W8) {
         // weight sub-block x-1 of step k+1: codes read behind MFMA (x, 0), converted behind MFMAs (x+1, 2..5),
         // so that every MFMA of the step has at most one vector, LDS or memory instruction behind it
-        if constexpr (x >= 2 && x <= 9 && sb >= 2 && sb <= 5) set_dword(wf[nxt][x - 2], sb - 2, w8_frag_dword<WK>(raw[x - 2].x, raw[x - 2].y, sb - 2));
-        if constexpr (x >= 1 && x <= 8 && sb == 0) raw[x - 1] = wr8[(x - 1) * 64];
+        if constexpr (NLIVE >= 10) {
+          if constexpr (x >= 2 && x <= 9 && sb >= 2 && sb <= 5) set_dword(wf[nxt][x - 2], sb - 2, w8_frag_dword<WK>(raw[x - 2].x, raw[x - 2].y, sb - 2));
+          if constexpr (x >= 1 && x <= 8 && sb == 0) raw[x - 1] = wr8[(x - 1) * 64];
+        } else {
+          // fewer than ten row blocks: codes of sub-blocks 2(x-1), 2(x-1)+1 read behind MFMAs (x, 0), (x, 7) for
+          // x = 1..4, two fragment dwords converted behind each of MFMAs (x, 2..5) for x = 2..5
+          if constexpr (x >= 1 && x <= 4 && sb == 0) raw[2 * (x - 1)] = wr8[(2 * (x - 1)) * 64];
+          if constexpr (x >= 1 && x <= 4 && sb == 7) raw[2 * (x - 1) + 1] = wr8[(2 * (x - 1) + 1) * 64];
+          if constexpr (x >= 2 && x <= 5 && sb >= 2 && sb <= 5) {
+            constexpr int c0 = 2 * ((x - 2) * 4 + (sb - 2)), c1 = c0 + 1;
+            set_dword(wf[nxt][c0 / 4], c0 % 4, w8_frag_dword<WK>(raw[c0 / 4].x, raw[c0 / 4].y, c0 % 4));
+            set_dword(wf[nxt][c1 / 4], c1 % 4, w8_frag_dword<WK>(raw[c1 / 4].x, raw[c1 / 4].y, c1 % 4));
+          }
+        }
       } else {
         // weight sub-block s behind MFMA (s+1, 3); with fewer than nine row blocks the last ones behind (.., 7)
         constexpr int ws = dma_wf_slot(x, sb, NLIVE);
@@ -272,7 +273,6 @@ __device__ __forceinline__ void dma_tile(
           constexpr bool issue = (pp % 2) != 0;
           if constexpr (p < kNW) {
             if constexpr (!issue) set_m0(ldsW0 + stageByte + p * 1024);
-            else if constexpr (STREAM) dma_issue_stream(wg, lane16 + p * 1024);
             else dma_issue(wg, lane16 + p * 1024);
           } else if constexpr (q < PXlo) {
             if constexpr (!issue) set_m0(lds0 + stageByte + xblk[q] * 1024);
@@ -359,7 +359,7 @@ __device__ __forceinline__ void dma_tile(
 // One launch runs row tiles rt0 .. rt0 + nRowTiles - 1, all with NLIVE row blocks per half: the full row tiles of a
 // call in one launch, a ragged last row tile in a launch of its own (one body per kernel: with a second body behind a
 // branch the register allocator has to spill, and it does so around the MFMAs it cannot see into).
-template <int WK, int NLIVE, bool STREAM>
+template <int WK, int NLIVE>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
     int V, int nVG, int nVGalloc, int rt0, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld,
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   const int rt = rt0 + j % nRowTiles;
   const int vt = (j / nRowTiles) * kXcds + xcd;
   if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
-  dma_tile<WK, NLIVE, STREAM>(Wsrc, vscale, Xp, R, KS, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+  dma_tile<WK, NLIVE>(Wsrc, vscale, Xp, R, KS, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
 }
 
 // Wg8[ks][vg][sub][lane][8 B]: the FP8 E4M3 codes of W_lm in MFMA fragment order for this kernel, one
@@ -412,25 +412,44 @@ hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* 
 // launcher, which may run under stream capture).
 template <int WK, int NLAST>
 static hipError_t dma_lds_limit() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<WK, NLAST, false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<WK != kWBf16>);
-  if constexpr (WK == kWBf16)
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<WK, NLAST, true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<false>);
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_dma_kernel<WK, NLAST>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes<WK != kWBf16>);
+}
+template <int WK>
+static hipError_t dma_lds_limits() {
+  hipError_t e = dma_lds_limit<WK, 6>();
+  if (e == hipSuccess) e = dma_lds_limit<WK, 7>();
+  if (e == hipSuccess) e = dma_lds_limit<WK, 8>();
+  if (e == hipSuccess) e = dma_lds_limit<WK, 9>();
+  if (e == hipSuccess) e = dma_lds_limit<WK, 10>();
+  if (e == hipSuccess) e = dma_lds_limit<WK, 11>();
   return e;
 }
 
 hipError_t init_lmhead_gemm_dma() {
-  hipError_t e = dma_lds_limit<kWBf16, 6>();
-  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 7>();
-  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 8>();
-  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 9>();
-  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 10>();
-  if (e == hipSuccess) e = dma_lds_limit<kWBf16, 11>();
-  if (e == hipSuccess) e = dma_lds_limit<kWFp8, 11>();
-  if (e == hipSuccess) e = dma_lds_limit<kWInt8, 11>();
+  hipError_t e = dma_lds_limits<kWBf16>();
+  if (e == hipSuccess) e = dma_lds_limits<kWFp8>();
+  if (e == hipSuccess) e = dma_lds_limits<kWInt8>();
   return e;
+}
+
+template <int WK>
+static void launch_dma(int nlive, int rt0, int nRt, int perRt, hipStream_t st, const void* W, const float* vscale,
+                       const void* Xp, int R, int KS, const Geometry& g, int nVocabTiles, float invT, float* L,
+                       float2* part) {
+#define JD_DMA(NL_)                                                                                                \
+  hipLaunchKernelGGL((lmhead_gemm_dma_kernel<WK, NL_>), dim3(perRt * nRt), dim3(256), kDmaLdsBytes<WK != kWBf16>, st, \
+                     static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG,          \
+                     g.nVGalloc, rt0, nRt, nVocabTiles, invT, L, g.Vpad, part)
+  switch (nlive) {
+    case 6: JD_DMA(6); break;
+    case 7: JD_DMA(7); break;
+    case 8: JD_DMA(8); break;
+    case 9: JD_DMA(9); break;
+    case 10: JD_DMA(10); break;
+    default: JD_DMA(11); break;
+  }
+#undef JD_DMA
 }
 
 hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale, const void* X, int R,
@@ -442,44 +461,28 @@ hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale
   const int nRowTiles = (R + kDmaRows - 1) / kDmaRows;
   const int KS = g.dpad / kKStep;  // multiple of 8
   if (KS < 2 * kDmaStages) return hipErrorInvalidValue;
-  // row blocks per half of the last row tile; one-byte weights always run full tiles
   // With several row tiles a ragged last one gets a launch of its own only where that pays: its launch streams the
-  // weights again instead of sharing them through L2 with the full tiles (measured at d = 8192: 0.37 / 0.40 / 0.44 /
-  // 0.47 / 0.51 ms for 6 .. 10 blocks per half against 0.52 ms for a full tile inside a shared launch).
-  int nlast = w_code == kWBf16 ? dma_half_blocks(R) : kDmaWaveRowBlocks;
+  // weights again instead of sharing them through L2 with the full tiles (measured at d = 8192, bf16: 0.37 / 0.40 /
+  // 0.44 / 0.47 / 0.51 ms for 6 .. 10 blocks per half against 0.52 ms for a full tile inside a shared launch).
+  int nlast = dma_half_blocks(R);
   if (nRowTiles > 1 && nlast > 8) nlast = kDmaWaveRowBlocks;
   hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, KS, kDmaRowBlocks, 1, nRowTiles - 1, nlast, Xp, st);
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int perRt = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds;  // workgroups per row tile
-#define JD_DMA(WK_, NL_, ST_, RT0_, NRT_)                                                                         \
-  hipLaunchKernelGGL((lmhead_gemm_dma_kernel<WK_, NL_, ST_>), dim3(perRt * (NRT_)), dim3(256),                     \
-                     kDmaLdsBytes<(WK_) != kWBf16>, st, static_cast<const uint4*>(W), vscale,                      \
-                     static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG, g.nVGalloc, RT0_, NRT_, nVocabTiles, invT, \
-                     L, g.Vpad, part)
-#define JD_DMA_LAST(ST_)                                                  \
-  switch (nlast) {                                                        \
-    case 6: JD_DMA(kWBf16, 6, ST_, nRowTiles - 1, 1); break;             \
-    case 7: JD_DMA(kWBf16, 7, ST_, nRowTiles - 1, 1); break;             \
-    case 8: JD_DMA(kWBf16, 8, ST_, nRowTiles - 1, 1); break;             \
-    case 9: JD_DMA(kWBf16, 9, ST_, nRowTiles - 1, 1); break;             \
-    case 10: JD_DMA(kWBf16, 10, ST_, nRowTiles - 1, 1); break;           \
-    default: JD_DMA(kWBf16, 11, ST_, nRowTiles - 1, 1); break;           \
-  }
-  if (w_code == kWFp8) {
-    JD_DMA(kWFp8, 11, false, 0, nRowTiles);
-  } else if (w_code == kWInt8) {
-    JD_DMA(kWInt8, 11, false, 0, nRowTiles);
-  } else if (nRowTiles == 1) {
-    JD_DMA_LAST(true);  // one row tile: every weight is read once
-  } else if (nlast == kDmaWaveRowBlocks) {
-    JD_DMA(kWBf16, 11, false, 0, nRowTiles);
+  auto go = [&](int nlive, int rt0, int nRt) {
+    switch (w_code) {
+      case kWFp8: launch_dma<kWFp8>(nlive, rt0, nRt, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
+      case kWInt8: launch_dma<kWInt8>(nlive, rt0, nRt, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
+      default: launch_dma<kWBf16>(nlive, rt0, nRt, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
+    }
+  };
+  if (nlast == kDmaWaveRowBlocks) {
+    go(kDmaWaveRowBlocks, 0, nRowTiles);
   } else {
-    JD_DMA(kWBf16, 11, false, 0, nRowTiles - 1);  // the full row tiles
-    JD_DMA_LAST(false);                           // the ragged last one
+    if (nRowTiles > 1) go(kDmaWaveRowBlocks, 0, nRowTiles - 1);  // the full row tiles
+    go(nlast, nRowTiles - 1, 1);                                 // the ragged last one
   }
-#undef JD_DMA_LAST
-#undef JD_DMA
   return hipGetLastError();
 }
 

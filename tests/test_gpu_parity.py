@@ -136,7 +136,8 @@ def test_row_block_counts_of_the_last_176_row_tile(jd, dtype):
     assert {l for t, l in seen if t == 1} == set(range(5, 12)) and {l for t, l in seen if t == 3} == set(range(1, 12)), seen
 
 
-def test_ragged_last_352_row_tile(jd):
+@pytest.mark.parametrize("dtype", ["bf16", "fp8", "int8"])
+def test_ragged_last_352_row_tile(jd, dtype):
     # The 352-row kernel spreads the rows of a ragged last row tile over both row halves and is instantiated per number
     # of 16-row blocks per half that hold rows (6 .. 11).  One row tile: every instantiation, rows ending inside half 0,
     # at its end and inside half 1.  Several row tiles: the ragged tile in a launch of its own (up to 8 blocks per half,
@@ -153,12 +154,13 @@ def test_ragged_last_352_row_tile(jd):
         half = max(6, (last + 31) // 32)
         own_launch = tiles > 1 and half <= 8
         seen.add((min(tiles, 3), half if (tiles == 1 or own_launch) else 11))
-        shape = VerifyShape(f"ragged352_R{R}", B, M, 144, 600, "bf16", 1.2)
+        shape = VerifyShape(f"ragged352_{dtype}_R{R}", B, M, 144, 600, dtype, 1.2)
         print(f"[case] {shape.name} ({tiles} row tiles, {last} rows in the last, {half} blocks per half)", flush=True)
         x = make_inputs(shape, 12)
         compare(jd.run_once(x), oracle_for(x))
     assert {h for t, h in seen if t == 1} == set(range(6, 12)), seen
     assert {(2, 6), (2, 8), (2, 11), (3, 6), (3, 11)} <= seen, seen
+    # (with one-byte weights the row counts above 704 that do not fill 352-row tiles run on 176-row tiles)
 
 
 def test_bruteforce_interval_edges_on_gpu(jd):
