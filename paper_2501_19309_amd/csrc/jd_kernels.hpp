@@ -180,18 +180,16 @@ hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* 
 hipError_t init_lmhead_gemm();
 hipError_t init_lmhead_gemm_dma();
 inline bool gemm_prefers_352(int R, int w_code) {
-  // bf16 weights also from three 352-row tiles on: a ragged last tile then costs less there than a fifth or sixth
-  // 176-row tile (792 rows 1.41 against 1.44 ms, 880 rows 1.44 against 1.49 ms at d = 8192); one-byte weights run
-  // full 352-row tiles only
-  if (w_code == kWBf16 && R > 2 * kDmaRows) return true;
-  return (R + kDmaRows - 1) / kDmaRows * kDmaRows == (R + kGemmRows - 1) / kGemmRows * kGemmRows;
+  (void)w_code;
+  return R > kGemmRows;  // every call of more than one 176-row tile (the 352-row kernel sizes its row tiles to the call)
 }
 // Re-tile bf16 embeddings X[R][d] into MFMA fragment order Xp[rt][chunk][xb][s][lane][8] (row tiles of
 // rowBlocks*16 rows, chunks of `steps` K steps), zero padded.
-// splitRt >= 0: that row tile is laid out in two halves of rowBlocks/2 block positions, of which the first halfBlocks
-// hold rows (the 352-row kernel's ragged last tile); -1: none.
-hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks, int rowBlocks, int steps, int splitRt,
-                         int halfBlocks, void* Xp, hipStream_t st);
+// halfBlocks == 0: block position xb of row tile rt holds rows rt*tileRows + xb*16 .. +15 (176-row kernel).
+// halfBlocks > 0: a row tile is two halves of rowBlocks/2 positions, of which the first halfBlocks (row tile splitRt:
+// splitHalfBlocks) hold rows, half h starting at row h*halfBlocks*16 of the tile (352-row kernel).
+hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks, int rowBlocks, int steps, int tileRows,
+                         int halfBlocks, int splitRt, int splitHalfBlocks, void* Xp, hipStream_t st);
 
 // fp32 LM head (any layout), plain FMA; writes logits only.
 hipError_t launch_lmhead_f32(const float* W, int layout, const float* X, int R, int d, int V, float invT,

@@ -48,14 +48,16 @@ constexpr int kGemmSteps = kGemmKChunk / kKStep;  // 4 K steps per staged chunk
 constexpr int kGemmPF = 2;                        // K steps per weight prefetch group
 constexpr int kGemmWBufs = 4;                     // register ring of weight groups: 3 groups (6 K steps) ahead
 
-// Xp[rt][chunk][xb][s][lane][8]: row rt*(rowBlocks*16) + xb*16 + lane%16, hidden index
-// chunk*(steps*32) + s*32 + (lane/16)*8 + 0..7; zero for rows >= R and indices >= d.
-// Row tile `splitRt` (-1: none) is laid out in two halves of rowBlocks/2 block positions each, of which the first
-// `halfBlocks` hold rows: position xb holds rows rt*(rowBlocks*16) + (xb / (rowBlocks/2)) * halfBlocks*16 +
-// (xb % (rowBlocks/2)) * 16 + lane%16, the other positions zeros (the 352-row kernel's ragged last tile).
+// Xp[rt][chunk][xb][s][lane][8]: hidden index chunk*(steps*32) + s*32 + (lane/16)*8 + 0..7 of the row that block
+// position xb of row tile rt holds; zero for rows >= R, indices >= d and positions without a row.
+// halfBlocks == 0 (176-row kernel): position xb holds rows rt*tileRows + xb*16 + lane%16.
+// halfBlocks > 0 (352-row kernel): a row tile is two halves of rowBlocks/2 positions each, of which the first
+// halfBlocks (row tile splitRt: splitHalfBlocks) hold rows: position xb holds row
+// rt*tileRows + (xb / (rowBlocks/2)) * hb*16 + (xb % (rowBlocks/2)) * 16 + lane%16.
 __global__ __launch_bounds__(256) void pack_x_kernel(const uint16_t* __restrict__ X, int R, int d, int nChunks,
-                                                      int rowBlocks, int steps, int splitRt, int halfBlocks,
-                                                      size_t total, uint4* __restrict__ Xp) {
+                                                      int rowBlocks, int steps, int tileRows, int halfBlocks,
+                                                      int splitRt, int splitHalfBlocks, size_t total,
+                                                      uint4* __restrict__ Xp) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   const int lane = (int)(idx & 63);
@@ -64,10 +66,11 @@ __global__ __launch_bounds__(256) void pack_x_kernel(const uint16_t* __restrict_
   const int xb = (int)(t % rowBlocks); t /= rowBlocks;
   const int ch = (int)(t % (size_t)nChunks);
   const int rt = (int)(t / (size_t)nChunks);
-  int row = rt * rowBlocks * 16 + xb * 16 + (lane & 15);
-  if (rt == splitRt) {
+  int row = rt * tileRows + xb * 16 + (lane & 15);
+  if (halfBlocks > 0) {
     const int half = rowBlocks / 2, h = xb / half, x = xb % half;
-    row = (x < halfBlocks) ? rt * rowBlocks * 16 + h * halfBlocks * 16 + x * 16 + (lane & 15) : R;
+    const int hb = (rt == splitRt) ? splitHalfBlocks : halfBlocks;
+    row = (x < hb) ? rt * tileRows + h * hb * 16 + x * 16 + (lane & 15) : R;
   }
   const int k = (ch * steps + s) * kKStep + (lane >> 4) * 8;
   uint4 v = make_uint4(0u, 0u, 0u, 0u);
@@ -75,12 +78,12 @@ __global__ __launch_bounds__(256) void pack_x_kernel(const uint16_t* __restrict_
   Xp[idx] = v;
 }
 
-hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks, int rowBlocks, int steps, int splitRt,
-                         int halfBlocks, void* Xp, hipStream_t st) {
+hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks, int rowBlocks, int steps, int tileRows,
+                         int halfBlocks, int splitRt, int splitHalfBlocks, void* Xp, hipStream_t st) {
   const size_t total = (size_t)nRowTiles * nChunks * rowBlocks * steps * 64;
   hipLaunchKernelGGL(pack_x_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(X), R, d, nChunks, rowBlocks, steps, splitRt, halfBlocks, total,
-                     static_cast<uint4*>(Xp));
+                     static_cast<const uint16_t*>(X), R, d, nChunks, rowBlocks, steps, tileRows, halfBlocks, splitRt,
+                     splitHalfBlocks, total, static_cast<uint4*>(Xp));
   return hipGetLastError();
 }
 
@@ -484,7 +487,7 @@ hipError_t launch_lmhead_gemm(const void* W, int w_code, const float* vscale, co
   if (R <= 0 || !Xp || !W) return hipErrorInvalidValue;
   const int nRowTiles = (R + kGemmRows - 1) / kGemmRows;
   const int nChunks = g.dpad / kGemmKChunk;
-  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, nChunks, kGemmRowBlocks, kGemmSteps, -1, 0, Xp, st);
+  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, nChunks, kGemmRowBlocks, kGemmSteps, kGemmRows, 0, -1, 0, Xp, st);
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;

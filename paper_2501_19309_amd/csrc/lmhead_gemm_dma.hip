@@ -110,8 +110,8 @@ constexpr int dma_piece_slot(int x, int sb, int nlive, int pieces) {
   return -1;
 }
 
-// One tile: rows rt*352 .. and vocabulary entries vt*256 .. +255.  NLIVE = 16-row blocks per row half that hold rows
-// (dma_half_blocks(): 11 for a full tile; a ragged last tile spreads its rows over both halves, NLIVE blocks each,
+// One tile: rows rt*tileRows .. and vocabulary entries vt*256 .. +255.  NLIVE = 16-row blocks per row half that hold
+// rows (11 for a full tile of 352 rows; a smaller or ragged tile spreads its rows over both halves, NLIVE blocks each,
 // half 1 starting at row NLIVE*16 of the tile).  Blocks beyond NLIVE are neither loaded nor multiplied: a K step is
 // 8*NLIVE MFMAs long.  (Non-temporal weight loads for calls with a single row tile were measured: 0.376 -> 0.372 ms at
 // 187 rows, within the noise elsewhere; not kept.)
@@ -119,7 +119,7 @@ template <int WK, int NLIVE>
 __device__ __forceinline__ void dma_tile(
     const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
     int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part, const int rt,
-    const int vt) {
+    const int vt, const int tileRows) {
   constexpr bool W8 = WK != kWBf16;
   static_assert(NLIVE >= kDmaMinHalfBlocks && NLIVE <= kDmaWaveRowBlocks, "instantiated tiles");
   constexpr int kStageItems = kDmaStageItems<W8>;
@@ -303,7 +303,7 @@ __device__ __forceinline__ void dma_tile(
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   __builtin_amdgcn_sched_barrier(0);
 
-  // epilogue: acc[s][x][i] = logit of row rt*352 + rh*NLIVE*16 + x*16 + n,
+  // epilogue: acc[s][x][i] = logit of row rt*tileRows + rh*NLIVE*16 + x*16 + n,
   //           vocabulary entry (vt*4 + vh*2 + s/4)*64 + (s%4)*16 + gq*4 + i
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
@@ -319,7 +319,7 @@ __device__ __forceinline__ void dma_tile(
       }
 #pragma unroll
     for (int x = 0; x < NLIVE; ++x) {
-      const int r = rt * kDmaRows + rh * (NLIVE * 16) + x * 16 + n;
+      const int r = rt * tileRows + rh * (NLIVE * 16) + x * 16 + n;
       float vals[4][4];
       float mx = -INFINITY;
 #pragma unroll
@@ -356,14 +356,15 @@ __device__ __forceinline__ void dma_tile(
   }
 }
 
-// One launch runs row tiles rt0 .. rt0 + nRowTiles - 1, all with NLIVE row blocks per half: the full row tiles of a
-// call in one launch, a ragged last row tile in a launch of its own (one body per kernel: with a second body behind a
-// branch the register allocator has to spill, and it does so around the MFMAs it cannot see into).
+// One launch runs row tiles rt0 .. rt0 + nRowTiles - 1 (tile rt starts at row rt*tileRows), all with NLIVE row blocks
+// per half: the equally sized row tiles of a call in one launch, or its full row tiles in one launch and a ragged last
+// one in a launch of its own (one body per kernel: with a second body behind a branch the register allocator has
+// to spill, and it does so around the MFMAs it cannot see into).
 template <int WK, int NLIVE>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
     const uint4* __restrict__ Wsrc, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R, int KS,
-    int V, int nVG, int nVGalloc, int rt0, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L, int Lld,
-    float2* __restrict__ part) {
+    int V, int nVG, int nVGalloc, int rt0, int nRowTiles, int tileRows, int nVocabTiles, float invT,
+    float* __restrict__ L, int Lld, float2* __restrict__ part) {
   // XCD-aware tile id: the row tiles that stream the same 256 vocabulary rows get ids that the
   // hardware deals to one XCD, so W_lm crosses from HBM into one L2 only.
   const int bid = blockIdx.x;
@@ -372,7 +373,7 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_dma_kernel(
   const int rt = rt0 + j % nRowTiles;
   const int vt = (j / nRowTiles) * kXcds + xcd;
   if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
-  dma_tile<WK, NLIVE>(Wsrc, vscale, Xp, R, KS, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
+  dma_tile<WK, NLIVE>(Wsrc, vscale, Xp, R, KS, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt, tileRows);
 }
 
 // Wg8[ks][vg][sub][lane][8 B]: the FP8 E4M3 codes of W_lm in MFMA fragment order for this kernel, one
@@ -434,13 +435,13 @@ hipError_t init_lmhead_gemm_dma() {
 }
 
 template <int WK>
-static void launch_dma(int nlive, int rt0, int nRt, int perRt, hipStream_t st, const void* W, const float* vscale,
+static void launch_dma(int nlive, int rt0, int nRt, int tileRows, int perRt, hipStream_t st, const void* W, const float* vscale,
                        const void* Xp, int R, int KS, const Geometry& g, int nVocabTiles, float invT, float* L,
                        float2* part) {
 #define JD_DMA(NL_)                                                                                                \
   hipLaunchKernelGGL((lmhead_gemm_dma_kernel<WK, NL_>), dim3(perRt * nRt), dim3(256), kDmaLdsBytes<WK != kWBf16>, st, \
                      static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, KS, g.V, g.nVG,          \
-                     g.nVGalloc, rt0, nRt, nVocabTiles, invT, L, g.Vpad, part)
+                     g.nVGalloc, rt0, nRt, tileRows, nVocabTiles, invT, L, g.Vpad, part)
   switch (nlive) {
     case 6: JD_DMA(6); break;
     case 7: JD_DMA(7); break;
@@ -452,6 +453,23 @@ static void launch_dma(int nlive, int rt0, int nRt, int perRt, hipStream_t st, c
 #undef JD_DMA
 }
 
+// How the rows of a call are cut into row tiles (measured at d = 8192, bf16: a tile with 6 .. 11 row blocks per half
+// costs 0.37 / 0.40 / 0.44 / 0.47 / 0.51 / 0.55 ms in a launch of its own and about 5 % less next to the other row
+// tiles of its vocabulary tiles, with which it shares the weights through L2):
+//  * one row tile: as many blocks per half as its rows need;
+//  * several: equally sized tiles if they need at most 9 blocks per half (363 rows = 2 x 6 blocks per half);
+//  * else full tiles, and the last one in a launch of its own if it needs at most 8 blocks per half
+//    (880 rows = 2 full tiles + 6 blocks per half), which streams the weights again, or as one more full tile.
+struct DmaPlan { int tileRows, halfBlocks, lastHalfBlocks; };
+static DmaPlan dma_plan(int R) {
+  const int nRt = (R + kDmaRows - 1) / kDmaRows;
+  if (nRt == 1) { const int n = dma_half_blocks(R); return {kDmaRows, n, n}; }
+  const int nb = (R + 32 * nRt - 1) / (32 * nRt);  // blocks per half of equally sized tiles, 6 .. 11
+  if (nb <= 9) return {32 * nb, nb, nb};
+  const int nlast = dma_half_blocks(R);
+  return {kDmaRows, kDmaWaveRowBlocks, nlast <= 8 ? nlast : kDmaWaveRowBlocks};
+}
+
 hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale, const void* X, int R,
                                   const Geometry& g, float invT, float* L, float2* part, void* Xp, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
@@ -461,27 +479,24 @@ hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale
   const int nRowTiles = (R + kDmaRows - 1) / kDmaRows;
   const int KS = g.dpad / kKStep;  // multiple of 8
   if (KS < 2 * kDmaStages) return hipErrorInvalidValue;
-  // With several row tiles a ragged last one gets a launch of its own only where that pays: its launch streams the
-  // weights again instead of sharing them through L2 with the full tiles (measured at d = 8192, bf16: 0.37 / 0.40 /
-  // 0.44 / 0.47 / 0.51 ms for 6 .. 10 blocks per half against 0.52 ms for a full tile inside a shared launch).
-  int nlast = dma_half_blocks(R);
-  if (nRowTiles > 1 && nlast > 8) nlast = kDmaWaveRowBlocks;
-  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, KS, kDmaRowBlocks, 1, nRowTiles - 1, nlast, Xp, st);
-  if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
   const int perRt = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds;  // workgroups per row tile
-  auto go = [&](int nlive, int rt0, int nRt) {
+  auto go = [&](int nlive, int rt0, int nRt, int tileRows) {
     switch (w_code) {
-      case kWFp8: launch_dma<kWFp8>(nlive, rt0, nRt, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
-      case kWInt8: launch_dma<kWInt8>(nlive, rt0, nRt, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
-      default: launch_dma<kWBf16>(nlive, rt0, nRt, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
+      case kWFp8: launch_dma<kWFp8>(nlive, rt0, nRt, tileRows, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
+      case kWInt8: launch_dma<kWInt8>(nlive, rt0, nRt, tileRows, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
+      default: launch_dma<kWBf16>(nlive, rt0, nRt, tileRows, perRt, st, W, vscale, Xp, R, KS, g, nVocabTiles, invT, L, part); break;
     }
   };
-  if (nlast == kDmaWaveRowBlocks) {
-    go(kDmaWaveRowBlocks, 0, nRowTiles);
+  const DmaPlan plan = dma_plan(R);
+  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, KS, kDmaRowBlocks, 1, plan.tileRows, plan.halfBlocks,
+                               plan.lastHalfBlocks != plan.halfBlocks ? nRowTiles - 1 : -1, plan.lastHalfBlocks, Xp, st);
+  if (e != hipSuccess) return e;
+  if (plan.lastHalfBlocks == plan.halfBlocks) {
+    go(plan.halfBlocks, 0, nRowTiles, plan.tileRows);       // equally sized row tiles, one launch
   } else {
-    if (nRowTiles > 1) go(kDmaWaveRowBlocks, 0, nRowTiles - 1);  // the full row tiles
-    go(nlast, nRowTiles - 1, 1);                                 // the ragged last one
+    go(plan.halfBlocks, 0, nRowTiles - 1, plan.tileRows);   // the full row tiles
+    go(plan.lastHalfBlocks, nRowTiles - 1, 1, plan.tileRows);  // the ragged last one
   }
   return hipGetLastError();
 }

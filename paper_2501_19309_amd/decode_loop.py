@@ -174,8 +174,7 @@ def sweep(batch_sizes: List[int], steps: int, seed: int, dtype: str = "bf16") ->
         torch.cuda.synchronize()
         kms, _ = ver.profile_end()
         lm = kms["lmhead"]
-        uses_352 = -(-R // 352) * 352 == -(-R // 176) * 176 or (dtype == "bf16" and R > 704)   # the library's dispatch
-        kernel = "skinny (W_lm streamed once)" if R <= 64 else ("352 x 256 tiles" if uses_352 else "176 x 256 tiles")
+        kernel = "skinny (W_lm streamed once)" if R <= 64 else ("352-row kernel" if R > 176 else "176-row kernel")  # the library's dispatch
         recs.append({"B": B, "M": M, "W_lm": dtype, "rows": R, "ms_per_call": ms, "verified_positions_per_s": B * M / (ms * 1e-3),
                      "lmhead_ms": lm, "lmhead_kernel": kernel,
                      "lmhead_W_GBs": w_bytes / (lm * 1e-3) / 1e9, "lmhead_frac_hbm_peak": w_bytes / (lm * 1e-3) / 8e12,

@@ -137,30 +137,38 @@ def test_row_block_counts_of_the_last_176_row_tile(jd, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp8", "int8"])
-def test_ragged_last_352_row_tile(jd, dtype):
-    # The 352-row kernel spreads the rows of a ragged last row tile over both row halves and is instantiated per number
-    # of 16-row blocks per half that hold rows (6 .. 11).  One row tile: every instantiation, rows ending inside half 0,
-    # at its end and inside half 1.  Several row tiles: the ragged tile in a launch of its own (up to 8 blocks per half,
-    # down to a single row) and inside the shared launch (more).
-    cases = [(3, 58), (20, 9), (24, 9), (27, 9), (30, 9), (34, 9),          # 177 .. 340 rows: 6 .. 11 blocks per half
+def test_row_tiles_of_the_352_row_kernel(jd, dtype):
+    # Above 176 rows the 352-row kernel cuts a call into row tiles of two halves with 6 .. 11 sixteen-row blocks each
+    # (one instantiation per block count): one tile sized to its rows; several equally sized tiles if they need at
+    # most 9 blocks per half; else full tiles, the last one in a launch of its own if it needs at most 8 blocks per
+    # half.  Every instantiation in every form, rows ending inside half 0, at its end, inside half 1, and a single
+    # row in the last tile.
+    def plan(R):
+        tiles = -(-R // 352)
+        if tiles == 1:
+            return "one", max(6, -(-R // 32)), None
+        nb = -(-R // (32 * tiles))
+        if nb <= 9:
+            return "equal", nb, None
+        last = max(6, -(-(R - (tiles - 1) * 352) // 32))
+        return "full", 11, (last if last <= 8 else 11)
+    cases = [(3, 58), (20, 9), (24, 9), (27, 9), (30, 9), (34, 9),          # 177 .. 340 rows: one tile, 6 .. 11 blocks per half
              (12, 15), (13, 15), (18, 15), (22, 15),                        # 192, 208, 288, 352 rows: block boundaries
-             (23, 22), (60, 9), (62, 9),                                    # 529, 600, 620 rows: two row tiles
-             (47, 14), (80, 9), (81, 9), (88, 10), (104, 10)]               # 705, 800, 810, 968, 1144 rows: three, four
+             (6, 58), (40, 9), (48, 9), (23, 22), (56, 9),                  # 354, 400, 480, 529, 560 rows: two equal tiles, 6 .. 9
+             (60, 9), (62, 9), (64, 10),                                    # 600, 620, 704 rows: two full tiles
+             (47, 14), (80, 9), (88, 9), (100, 9), (104, 10)]               # 705, 800, 880, 1000, 1144 rows: three and four tiles
     seen = set()
     for B, M in cases:
         R = B * (M + 1)
-        tiles = (R + 351) // 352
-        last = R - (tiles - 1) * 352
-        half = max(6, (last + 31) // 32)
-        own_launch = tiles > 1 and half <= 8
-        seen.add((min(tiles, 3), half if (tiles == 1 or own_launch) else 11))
-        shape = VerifyShape(f"ragged352_{dtype}_R{R}", B, M, 144, 600, dtype, 1.2)
-        print(f"[case] {shape.name} ({tiles} row tiles, {last} rows in the last, {half} blocks per half)", flush=True)
+        form = plan(R)
+        seen.add(form)
+        shape = VerifyShape(f"tiles352_{dtype}_R{R}", B, M, 144, 600, dtype, 1.2)
+        print(f"[case] {shape.name} {form}", flush=True)
         x = make_inputs(shape, 12)
         compare(jd.run_once(x), oracle_for(x))
-    assert {h for t, h in seen if t == 1} == set(range(6, 12)), seen
-    assert {(2, 6), (2, 8), (2, 11), (3, 6), (3, 11)} <= seen, seen
-    # (with one-byte weights the row counts above 704 that do not fill 352-row tiles run on 176-row tiles)
+    assert {f[1] for f in seen if f[0] == "one"} == set(range(6, 12)), seen
+    assert {f[1] for f in seen if f[0] == "equal"} == set(range(6, 10)), seen
+    assert {("full", 11, 6), ("full", 11, 8), ("full", 11, 11)} <= seen, seen
 
 
 def test_bruteforce_interval_edges_on_gpu(jd):
