@@ -458,8 +458,9 @@ static void launch_dma(int nlive, int rt0, int nRt, int tileRows, int perRt, hip
 // tiles of its vocabulary tiles, with which it shares the weights through L2):
 //  * one row tile: as many blocks per half as its rows need;
 //  * several: equally sized tiles if they need at most 9 blocks per half (363 rows = 2 x 6 blocks per half);
-//  * else full tiles, and the last one in a launch of its own if it needs at most 8 blocks per half
-//    (880 rows = 2 full tiles + 6 blocks per half), which streams the weights again, or as one more full tile.
+//  * else full tiles and the last one in a launch of its own, which streams the weights again, if that one needs at
+//    most 8 blocks per half (880 rows = 2 full tiles + 6 blocks per half); else equally sized tiles of 10 blocks per
+//    half if they hold the rows, else full tiles throughout.
 struct DmaPlan { int tileRows, halfBlocks, lastHalfBlocks; };
 static DmaPlan dma_plan(int R) {
   const int nRt = (R + kDmaRows - 1) / kDmaRows;
@@ -467,7 +468,9 @@ static DmaPlan dma_plan(int R) {
   const int nb = (R + 32 * nRt - 1) / (32 * nRt);  // blocks per half of equally sized tiles, 6 .. 11
   if (nb <= 9) return {32 * nb, nb, nb};
   const int nlast = dma_half_blocks(R);
-  return {kDmaRows, kDmaWaveRowBlocks, nlast <= 8 ? nlast : kDmaWaveRowBlocks};
+  if (nlast <= 8) return {kDmaRows, kDmaWaveRowBlocks, nlast};
+  if (nb == 10) return {32 * nb, nb, nb};
+  return {kDmaRows, kDmaWaveRowBlocks, kDmaWaveRowBlocks};
 }
 
 hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale, const void* X, int R,

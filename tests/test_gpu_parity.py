@@ -140,8 +140,8 @@ def test_row_block_counts_of_the_last_176_row_tile(jd, dtype):
 def test_row_tiles_of_the_352_row_kernel(jd, dtype):
     # Above 176 rows the 352-row kernel cuts a call into row tiles of two halves with 6 .. 11 sixteen-row blocks each
     # (one instantiation per block count): one tile sized to its rows; several equally sized tiles if they need at
-    # most 9 blocks per half; else full tiles, the last one in a launch of its own if it needs at most 8 blocks per
-    # half.  Every instantiation in every form, rows ending inside half 0, at its end, inside half 1, and a single
+    # most 9 blocks per half; else full tiles with the last one in a launch of its own if that needs at most 8 blocks
+    # per half; else equal tiles of 10 blocks per half or full tiles.  Every instantiation in every form, rows ending inside half 0, at its end, inside half 1, and a single
     # row in the last tile.
     def plan(R):
         tiles = -(-R // 352)
@@ -151,7 +151,9 @@ def test_row_tiles_of_the_352_row_kernel(jd, dtype):
         if nb <= 9:
             return "equal", nb, None
         last = max(6, -(-(R - (tiles - 1) * 352) // 32))
-        return "full", 11, (last if last <= 8 else 11)
+        if last <= 8:
+            return "full", 11, last
+        return ("equal", 10, None) if nb == 10 else ("full", 11, 11)
     cases = [(3, 58), (20, 9), (24, 9), (27, 9), (30, 9), (34, 9),          # 177 .. 340 rows: one tile, 6 .. 11 blocks per half
              (12, 15), (13, 15), (18, 15), (22, 15),                        # 192, 208, 288, 352 rows: block boundaries
              (6, 58), (40, 9), (48, 9), (23, 22), (56, 9),                  # 354, 400, 480, 529, 560 rows: two equal tiles, 6 .. 9
@@ -167,7 +169,7 @@ def test_row_tiles_of_the_352_row_kernel(jd, dtype):
         x = make_inputs(shape, 12)
         compare(jd.run_once(x), oracle_for(x))
     assert {f[1] for f in seen if f[0] == "one"} == set(range(6, 12)), seen
-    assert {f[1] for f in seen if f[0] == "equal"} == set(range(6, 10)), seen
+    assert {f[1] for f in seen if f[0] == "equal"} == set(range(6, 11)), seen
     assert {("full", 11, 6), ("full", 11, 8), ("full", 11, 11)} <= seen, seen
 
 
