@@ -40,10 +40,10 @@ MEASURED_TRAFFIC = {
     "C4": (4.2463e9, "profiles/lmhead_skinny_C4_hbm_traffic.md: lmhead_skinny_kernel<2,4,0>"),
     "C2": (1.0638e9, "profiles/lmhead_skinny_C4_hbm_traffic.md: lmhead_skinny_kernel<1,4,0>"),
     "C4q": (2.1454e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_skinny_kernel<2,4,1>"),
-    "C4i": (2.1467e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_skinny_kernel<2,4,2>"),
-    "C5": (2.855e9, "profiles/lmhead_gemm_C5_counters.md: lmhead_gemm_dma_kernel<0>"),
-    "C5q": (1.8048e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_gemm_dma_kernel<1>"),
-    "C5i": (1.8048e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_gemm_dma_kernel<2>"),
+    "C4i": (2.1466e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_skinny_kernel<2,4,2>"),
+    "C5": (2.856e9, "profiles/lmhead_gemm_C5_counters.md: lmhead_gemm_dma_kernel<0, 11>"),
+    "C5q": (1.8049e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_gemm_dma_kernel<1, 11>"),
+    "C5i": (1.8049e9, "profiles/verify_call_8bit_weights_kernel_stats_and_traffic.md: lmhead_gemm_dma_kernel<2, 11>"),
 }
 MFMA_BOUND = ("C5", "C5q", "C5i")
 SECONDARY = ("C5", "C2", "C3")   # measured after the headline workload C4, in the same process
