@@ -1,22 +1,18 @@
-// LM-head projection for the large-row regime (R = B*(M+1) > 64, e.g. 64 sequences x 11
-// rows = 704) on gfx950: here the contraction (Sec. 3.1, Eq. 2, for all rows of a batch)
-// is dense enough to be bound by the matrix cores, not by the W_lm stream.
+// LM-head projection for calls of one 176-row tile (65 .. 176 rows; Sec. 3.1, Eq. 2 for all rows of a batch) on
+// gfx950.  Up to about 130 rows the launch is bound by the W_lm stream, beyond by the matrix cores; calls with more
+// rows run on the 352-row kernel next door, which began as this kernel with both operands shared through LDS.
 //
-// Tiling.  One workgroup (4 wavefronts, one per SIMD, up to 512 registers each) owns
-// 176 embedding rows x 256 vocabulary entries; each wavefront owns 176 x 64 of it as
-// 11 x 4 accumulator tiles of v_mfma_f32_16x16x32_bf16 (176 registers).  704 rows are
-// exactly four such row tiles, so the B=64, M=10 batch carries no padding rows.
+// Tiling.  One workgroup (4 wavefronts, one per SIMD, up to 512 registers each) owns all rows x 256 vocabulary
+// entries; each wavefront owns 64 of them as up to 11 x 4 accumulator tiles of v_mfma_f32_16x16x32_bf16.
 //   * W_lm fragments go straight from the re-tiled global copy into MFMA A operands
 //     (a wavefront's 64 vocabulary rows are its own - nothing to share through LDS),
-//     prefetched two K steps ahead;
+//     prefetched two K steps ahead, with non-temporal loads;
 //   * the embedding tile is what the four wavefronts share: it is re-tiled once per call
 //     into fragment order (pack_x_kernel) so that staging a 128-wide K chunk is a linear
-//     44 KiB copy into LDS and every operand read is a conflict-free lane-linear
+//     copy into LDS and every operand read is a conflict-free lane-linear
 //     ds_read_b128; double buffered, one barrier per chunk;
-//   * per K step a wavefront issues 44 MFMAs against 11 LDS reads and 4 global loads.
-// Workgroup -> tile mapping is XCD aware: hardware deals consecutive workgroups round-robin
-// to the 8 XCDs, so the four row tiles that stream the same 256 vocabulary rows are given
-// ids that land on one XCD and share its L2: W_lm is fetched from HBM once.
+//   * per K step a wavefront issues up to 44 MFMAs against 11 LDS reads and 4 global loads; row blocks without rows
+//     are left out at compile time (one instantiation per number of row blocks that hold rows).
 // Epilogue as in the small-row kernel: fp32 logits / T and one (max, sum exp) softmax
 // partial per (row, 64-entry vocabulary group).
 #include <type_traits>
@@ -43,7 +39,6 @@ __device__ __forceinline__ void mfma_16x16x32_bf16_inplace(f32x4& acc, const uin
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(av), "v"(bv));
 }
 
-constexpr int kXcds = 8;
 constexpr int kGemmSteps = kGemmKChunk / kKStep;  // 4 K steps per staged chunk
 constexpr int kGemmPF = 2;                        // K steps per weight prefetch group
 constexpr int kGemmWBufs = 4;                     // register ring of weight groups: 3 groups (6 K steps) ahead
@@ -91,15 +86,14 @@ hipError_t launch_pack_x(const void* X, int R, int d, int nRowTiles, int nChunks
 // lane's 16 bytes are its codes for the two K steps of a prefetch group): half the weight bytes from HBM
 // and through L2; fragments are converted to bf16 in registers one K step ahead, one instruction behind
 // an MFMA each; the per-entry scale is applied in the epilogue.
-// One tile: embedding rows rt*176 .. +175, vocabulary entries vt*256 .. +255.  NLIVE = number of the tile's 16-row
-// blocks that hold rows; the MFMAs of the others are left out at compile time.  STREAM: the launch has one row tile, so
-// every weight is read exactly once and its loads are non-temporal (3-4 % faster there; with several row tiles the
-// second reader of a vocabulary tile finds it in L2, and plain loads measure better).
-template <int WK, int NLIVE, bool STREAM>
+// One tile: embedding rows 0 .. 175 (the kernel serves calls of one row tile, 65 .. 176 rows), vocabulary entries
+// vt*256 .. +255.  NLIVE = number of the tile's 16-row blocks that hold rows; the MFMAs, loads and staging of the others
+// are left out at compile time.  Every weight is read exactly once, so its loads are non-temporal (3-4 % faster).
+template <int WK, int NLIVE>
 __device__ __forceinline__ void gemm_tile(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
     int nChunks, int V, int nVG, int nVGalloc, float invT, float* __restrict__ L, int Lld, float2* __restrict__ part,
-    const int rt, const int vt) {
+    const int vt) {
   constexpr bool W8 = WK != kWBf16;  // one-byte codes (FP8 E4M3 or INT8) in the Wp8 layout
   constexpr int NXB = kGemmRowBlocks;
   constexpr int ITEMS = NXB * kGemmSteps * 64;  // 16-byte items per staged chunk (44 KiB)
@@ -109,10 +103,7 @@ __device__ __forceinline__ void gemm_tile(
 
   extern __shared__ uint4 xs_raw[];  // 2 x ITEMS x 16 B = 88 KiB (dynamic: above the static limit)
   uint4 (*xs)[ITEMS] = reinterpret_cast<uint4 (*)[ITEMS]>(xs_raw);
-  auto ldw = [](const uint4* p) -> uint4 {
-    if constexpr (STREAM) return load_stream(p);
-    else return *p;
-  };
+  auto ldw = [](const uint4* p) -> uint4 { return load_stream(p); };
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -128,7 +119,7 @@ __device__ __forceinline__ void gemm_tile(
 
   static_assert(kGemmPF == 2 && kW8KG % 2 == 0, "a prefetch group is one FP8 K-step pair");
   const uint4* wbase = Wp + (W8 ? wp8_group_offset(vg) : wp_group_offset(vg));
-  const uint4* xbase = Xp + (size_t)rt * nChunks * ITEMS;
+  const uint4* xbase = Xp;
 
   f32x4 acc[4][NXB];
 #pragma unroll
@@ -154,7 +145,7 @@ __device__ __forceinline__ void gemm_tile(
   // row tile, they are neither loaded nor staged (66 rows FP8 0.220 -> 0.197 ms, 374 rows FP8 0.723 -> 0.683 ms,
   // 66-110 rows bf16 0.338-0.344 -> 0.334-0.337 ms); with bf16 weights on several row tiles leaving the staging out
   // makes ragged launches 2-4 % slower (374 rows 0.783 -> 0.819 ms), so there the zero rows keep travelling
-  constexpr int NSTAGE = (W8 || STREAM) ? NLIVE : NXB;
+  constexpr int NSTAGE = NLIVE;
   auto load_portion = [&](const uint4* src, auto pc) {
     constexpr int p = decltype(pc)::value;
     if constexpr (p == 0) {
@@ -336,7 +327,7 @@ __device__ __forceinline__ void gemm_tile(
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   __builtin_amdgcn_sched_barrier(0);
 
-  // epilogue: acc[sub][x][i] = logit of row rt*176 + x*16 + n, entry vg*64 + sub*16 + gq*4 + i
+  // epilogue: acc[sub][x][i] = logit of row x*16 + n, entry vg*64 + sub*16 + gq*4 + i
   if (vg >= nVG) return;
   float osc[4][4];  // (per-entry weight scale, FP8 weights only) / T for this lane's 16 vocabulary entries
 #pragma unroll
@@ -348,7 +339,7 @@ __device__ __forceinline__ void gemm_tile(
     }
 #pragma unroll
   for (int x = 0; x < NXB; ++x) {
-    const int r = rt * kGemmRows + x * 16 + n;
+    const int r = x * 16 + n;
     float vals[4][4];
     float mx = -INFINITY;
 #pragma unroll
@@ -384,56 +375,31 @@ __device__ __forceinline__ void gemm_tile(
   }
 }
 
-// NLAST = row blocks that hold rows in the LAST row tile of the launch (all other row tiles are full).  The branch
-// is taken once per workgroup, outside the pipelined loop: a run-time branch around single MFMAs would cost the
-// hand-dealt schedule its wait counts.  ONE: the launch has a single row tile (nRowTiles == 1).
-template <int WK, int NLAST, bool ONE>
+// One workgroup per vocabulary tile, XCD aware like the other kernels' grids (workgroup b runs on XCD b % 8).
+template <int WK, int NLIVE>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(
     const uint4* __restrict__ Wp, const float* __restrict__ vscale, const uint4* __restrict__ Xp, int R,
-    int nChunks, int V, int nVG, int nVGalloc, int nRowTiles, int nVocabTiles, float invT, float* __restrict__ L,
+    int nChunks, int V, int nVG, int nVGalloc, int nVocabTiles, float invT, float* __restrict__ L,
     int Lld, float2* __restrict__ part) {
-  // XCD-aware tile id: workgroups j = 0,1,2.. of one XCD walk row tiles fastest.
-  const int bid = blockIdx.x;
-  const int xcd = bid % kXcds;
-  const int j = bid / kXcds;
-  const int rt = j % nRowTiles;
-  const int vt = (j / nRowTiles) * kXcds + xcd;
+  const int vt = blockIdx.x;
   if (vt >= nVocabTiles) return;  // uniform for the whole workgroup, before any barrier
-  if constexpr (ONE) {
-    gemm_tile<WK, NLAST, true>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, 0, vt);
-  } else {
-    if (NLAST < kGemmRowBlocks && rt == nRowTiles - 1)
-      gemm_tile<WK, NLAST, false>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
-    else
-      gemm_tile<WK, kGemmRowBlocks, false>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, rt, vt);
-  }
+  gemm_tile<WK, NLIVE>(Wp, vscale, Xp, R, nChunks, V, nVG, nVGalloc, invT, L, Lld, part, vt);
 }
 
 constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmRowBlocks * kGemmSteps * 64 * sizeof(uint4);
-// The single-row-tile form exists from this many row blocks on: the dispatcher gives launches of up to 64 rows to
-// the small-row kernel, so a single tile here holds at least 65 rows.
-constexpr int kGemmMinLiveOne = 5;
+// The dispatcher gives calls of up to 64 rows to the small-row kernel, so a tile here holds at least 65 rows.
+constexpr int kGemmMinLive = 5;
 
-// Instantiations by the number of 16-row blocks that hold rows in the last row tile of a launch.  With one row tile
-// (65 .. 176 rows) the kernel is bound by the weight stream - at half the bytes per weight, FP8, only once the MFMAs
-// of empty blocks are gone; with several, a ragged last tile costs only the rows it has.
+// Instantiations by the number of 16-row blocks that hold rows (65 .. 176 rows): the kernel is bound by the weight
+// stream - at half the bytes per weight, FP8, only once the MFMAs of empty blocks are gone.
 template <int WK, int NLIVE>
 static hipError_t set_lds_limit() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<WK, NLIVE, false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
-  if constexpr (NLIVE >= kGemmMinLiveOne)
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<WK, NLIVE, true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
-  return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_gemm_kernel<WK, NLIVE>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
 }
 template <int WK>
 static hipError_t set_lds_limits() {
-  hipError_t e = set_lds_limit<WK, 1>();
-  if (e == hipSuccess) e = set_lds_limit<WK, 2>();
-  if (e == hipSuccess) e = set_lds_limit<WK, 3>();
-  if (e == hipSuccess) e = set_lds_limit<WK, 4>();
-  if (e == hipSuccess) e = set_lds_limit<WK, 5>();
+  hipError_t e = set_lds_limit<WK, 5>();
   if (e == hipSuccess) e = set_lds_limit<WK, 6>();
   if (e == hipSuccess) e = set_lds_limit<WK, 7>();
   if (e == hipSuccess) e = set_lds_limit<WK, 8>();
@@ -446,37 +412,25 @@ static hipError_t set_lds_limits() {
 // More LDS than the default limit of a launch: raised once per process, at context creation (not in the
 // launcher, which may run under stream capture).
 hipError_t init_lmhead_gemm() {
+  static_assert(kGemmMinLive == 5, "instantiations above and below");
   hipError_t e = set_lds_limits<kWBf16>();
   if (e == hipSuccess) e = set_lds_limits<kWFp8>();
   if (e == hipSuccess) e = set_lds_limits<kWInt8>();
   return e;
 }
 
-template <int WK, int NLIVE>
-static void launch_gemm_t(int grid, hipStream_t st, const void* W, const float* vscale, const void* Xp, int R, int nChunks,
-                          const Geometry& g, int nRowTiles, int nVocabTiles, float invT, float* L, float2* part) {
-#define JD_GEMM_GO(ONE_)                                                                                            \
-  hipLaunchKernelGGL((lmhead_gemm_kernel<WK, NLIVE, ONE_>), dim3(grid), dim3(256), kGemmLdsBytes, st,             \
-                     static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG,   \
-                     g.nVGalloc, nRowTiles, nVocabTiles, invT, L, g.Vpad, part)
-  if constexpr (NLIVE >= kGemmMinLiveOne) {
-    if (nRowTiles == 1) {
-      JD_GEMM_GO(true);
-      return;
-    }
-  }
-  JD_GEMM_GO(false);
-#undef JD_GEMM_GO
-}
-
 template <int WK>
 static void launch_gemm_live(int live, int grid, hipStream_t st, const void* W, const float* vscale, const void* Xp, int R,
-                             int nChunks, const Geometry& g, int nRowTiles, int nVocabTiles, float invT, float* L,
-                             float2* part) {
-#define JD_LIVE(N) case N: launch_gemm_t<WK, N>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break
-  switch (live) {
-    JD_LIVE(1); JD_LIVE(2); JD_LIVE(3); JD_LIVE(4); JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
-    default: launch_gemm_t<WK, 11>(grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
+                             int nChunks, const Geometry& g, int nVocabTiles, float invT, float* L, float2* part) {
+#define JD_LIVE(N)                                                                                                 \
+  case N:                                                                                                          \
+    hipLaunchKernelGGL((lmhead_gemm_kernel<WK, N>), dim3(grid), dim3(256), kGemmLdsBytes, st,                      \
+                       static_cast<const uint4*>(W), vscale, static_cast<const uint4*>(Xp), R, nChunks, g.V, g.nVG, \
+                       g.nVGalloc, nVocabTiles, invT, L, g.Vpad, part);                                            \
+    break
+  switch (live < kGemmMinLive ? kGemmMinLive : live) {
+    JD_LIVE(5); JD_LIVE(6); JD_LIVE(7); JD_LIVE(8); JD_LIVE(9); JD_LIVE(10);
+    default: JD_LIVE(11);
   }
 #undef JD_LIVE
 }
@@ -484,19 +438,16 @@ static void launch_gemm_live(int live, int grid, hipStream_t st, const void* W, 
 hipError_t launch_lmhead_gemm(const void* W, int w_code, const float* vscale, const void* X, int R, const Geometry& g,
                               float invT, float* L, float2* part, void* Xp, hipStream_t st) {
   static_assert(kGroupAlloc % 4 == 0, "a vocabulary tile of 4 groups never leaves the allocation");
-  if (R <= 0 || !Xp || !W) return hipErrorInvalidValue;
-  const int nRowTiles = (R + kGemmRows - 1) / kGemmRows;
+  if (R <= 0 || R > kGemmRows || !Xp || !W) return hipErrorInvalidValue;  // one row tile
   const int nChunks = g.dpad / kGemmKChunk;
-  hipError_t e = launch_pack_x(X, R, g.d, nRowTiles, nChunks, kGemmRowBlocks, kGemmSteps, kGemmRows, 0, -1, 0, Xp, st);
+  hipError_t e = launch_pack_x(X, R, g.d, 1, nChunks, kGemmRowBlocks, kGemmSteps, kGemmRows, 0, -1, 0, Xp, st);
   if (e != hipSuccess) return e;
   const int nVocabTiles = (g.nVG + 3) / 4;
-  const int grid = ((nVocabTiles + kXcds - 1) / kXcds) * kXcds * nRowTiles;
-  // row blocks that hold rows in the last row tile (the others are full)
-  const int live = (R - (nRowTiles - 1) * kGemmRows + 15) / 16;
+  const int live = (R + 15) / 16;  // row blocks that hold rows
   switch (w_code) {
-    case kWFp8: launch_gemm_live<kWFp8>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
-    case kWInt8: launch_gemm_live<kWInt8>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
-    case kWBf16: launch_gemm_live<kWBf16>(live, grid, st, W, vscale, Xp, R, nChunks, g, nRowTiles, nVocabTiles, invT, L, part); break;
+    case kWFp8: launch_gemm_live<kWFp8>(live, nVocabTiles, st, W, vscale, Xp, R, nChunks, g, nVocabTiles, invT, L, part); break;
+    case kWInt8: launch_gemm_live<kWInt8>(live, nVocabTiles, st, W, vscale, Xp, R, nChunks, g, nVocabTiles, invT, L, part); break;
+    case kWBf16: launch_gemm_live<kWBf16>(live, nVocabTiles, st, W, vscale, Xp, R, nChunks, g, nVocabTiles, invT, L, part); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

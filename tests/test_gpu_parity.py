@@ -78,19 +78,19 @@ EDGE = [
     VerifyShape("e_d8", 2, 5, 8, 700, "bf16", 1.0),              # smallest hidden size the bf16 path takes
     VerifyShape("e_B200", 200, 2, 64, 333, "bf16", 1.0),         # many sequences, R = 600
     VerifyShape("e_R65", 5, 12, 96, 1024, "bf16", 1.0),          # first row count of the GEMM regime
-    VerifyShape("e_R177", 3, 58, 64, 640, "bf16", 1.0),          # one row into a second 176-row tile (352-row tiling)
+    VerifyShape("e_R177", 3, 58, 64, 640, "bf16", 1.0),          # first row count of the 352-row kernel (6 row blocks per half)
     VerifyShape("e_R352", 32, 10, 520, 4100, "bf16", (0.5, 2.0)),  # exactly one 352-row tile, 24 K steps, ragged V
-    VerifyShape("e_R400", 40, 9, 264, 1000, "bf16", 1.0),        # three 176-row tiles (176-row tiling)
-    VerifyShape("e_R1000", 100, 9, 128, 700, "bf16", 1.0),       # three 352-row tiles, the last one ragged
+    VerifyShape("e_R400", 40, 9, 264, 1000, "bf16", 1.0),        # two equally sized row tiles of the 352-row kernel
+    VerifyShape("e_R1000", 100, 9, 128, 700, "bf16", 1.0),       # three full 352-row tiles, the last one ragged
     VerifyShape("e_R704_M63", 11, 63, 72, 130, "bf16", 1.0),     # two full 352-row tiles, widest ballot, 3 vocabulary groups
     VerifyShape("e_R352_d8", 44, 7, 8, 300, "bf16", 1.0),        # 352-row tiling at the smallest hidden size (one real K step)
     VerifyShape("e_R300_V9", 30, 9, 40, 9, "bf16", 1.0),         # 352-row tiling with one partial vocabulary group
     VerifyShape("e_V1", 2, 2, 8, 1, "f32", 1.0),                 # single token vocabulary: everything is certain
     VerifyShape("e_R2816", 256, 10, 256, 3000, "bf16", (0.5, 2.0)),  # eight 352-row tiles: several rounds of workgroups per unit
-    VerifyShape("e_R2640_fp8", 240, 10, 272, 1500, "fp8", (0.5, 2.0)),  # fifteen 176-row tiles, FP8 codes, ragged d
+    VerifyShape("e_R2640_fp8", 240, 10, 272, 1500, "fp8", (0.5, 2.0)),  # eight row tiles of 330 rows, FP8 codes, ragged d
     VerifyShape("e_B70000", 70000, 1, 16, 40, "bf16", 1.0),      # more sequences (and rows) than a grid's y dimension holds
     VerifyShape("e_R264", 24, 10, 264, 2100, "bf16", (0.5, 2.0)),  # 264 rows: a 352-row tile three quarters full
-    VerifyShape("e_R528", 48, 10, 264, 2100, "bf16", (0.5, 2.0)),  # 528 rows: three 176-row tiles
+    VerifyShape("e_R528", 48, 10, 264, 2100, "bf16", (0.5, 2.0)),  # 528 rows: two row tiles of 264 rows
 ]
 
 
@@ -116,24 +116,20 @@ def test_small_shapes_match_oracle(jd, shape, seed):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp8", "int8"])
-def test_row_block_counts_of_the_last_176_row_tile(jd, dtype):
-    # The 176-row kernel is instantiated per number of 16-row blocks that hold rows in the LAST row tile of a launch
-    # (1 .. 11).  One row tile (65 .. 176 rows): one shape per instantiation from 5 blocks on, the last block ragged,
-    # and the exact block boundaries 80 and 176.  Three row tiles (353 .. 528 rows, two of them full): every count.
-    single = [(7, 10), (13, 6), (9, 11), (25, 4), (14, 9), (31, 4), (12, 13), (5, 15), (16, 10)]
-    triple = [(119, 2), (41, 8), (55, 6), (101, 3), (61, 6), (49, 8), (113, 3), (93, 4), (121, 3), (45, 10), (64, 7), (48, 10)]
+def test_row_block_counts_of_the_176_row_kernel(jd, dtype):
+    # The 176-row kernel (65 .. 176 rows) is instantiated per number of 16-row blocks that hold rows (5 .. 11): one
+    # shape per instantiation, the last block ragged, and the exact block boundaries 80 and 176.
     seen = set()
-    for B, M in single + triple:
+    for B, M in [(7, 10), (13, 6), (9, 11), (25, 4), (14, 9), (31, 4), (12, 13), (5, 15), (16, 10)]:
         R = B * (M + 1)
-        tiles = (R + 175) // 176
-        assert (64 < R <= 176) or (352 < R <= 528), R
-        live = (R - (tiles - 1) * 176 + 15) // 16
-        seen.add((tiles, live))
+        assert 64 < R <= 176, R
+        live = (R + 15) // 16
+        seen.add(live)
         shape = VerifyShape(f"live_{dtype}_R{R}", B, M, 144, 600, dtype, 1.2)
-        print(f"[case] {shape.name} ({tiles} row tiles, {live} row blocks in the last)", flush=True)
+        print(f"[case] {shape.name} ({live} row blocks)", flush=True)
         x = make_inputs(shape, 11)
         compare(jd.run_once(x), oracle_for(x))
-    assert {l for t, l in seen if t == 1} == set(range(5, 12)) and {l for t, l in seen if t == 3} == set(range(1, 12)), seen
+    assert seen == set(range(5, 12)), seen
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp8", "int8"])
@@ -380,7 +376,7 @@ FP8 = [
     VerifyShape("q_ragged", 2, 9, 272, 1000, "fp8", 2.0),        # d % 256 != 0, V % 64 != 0
     VerifyShape("q_4blk", 4, 15, 768, 3000, "fp8", 1.5),         # R = 64
     VerifyShape("q_gemm", 9, 10, 512, 5000, "fp8", (0.5, 2.5)),  # R = 99: 176-row tiling, FP8 codes converted in registers
-    VerifyShape("q_gemm176x3", 40, 10, 784, 3333, "fp8", (0.5, 2.5)),  # R = 440: three 176-row tiles, ragged d and V
+    VerifyShape("q_gemm176x3", 40, 10, 784, 3333, "fp8", (0.5, 2.5)),  # R = 440: two row tiles of 224 rows (352-row kernel), ragged d and V
     VerifyShape("q_gemm352", 20, 10, 288, 2100, "fp8", (0.5, 2.5)),  # R = 220: 352-row tiling, FP8 fragments
     VerifyShape("q_gemm704", 64, 10, 528, 4100, "fp8", (0.5, 2.5)),  # R = 704: two 352-row tiles, ragged d and V
     VerifyShape("q_gemm_d16", 33, 10, 16, 130, "fp8", 1.0),          # R = 363: two tiles, one real K step
