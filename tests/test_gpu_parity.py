@@ -658,7 +658,9 @@ def test_side_stream_and_two_contexts(jd):
 @pytest.mark.parametrize("shape", [VerifyShape("g_skinny", 2, 9, 264, 3000, "bf16", 1.0),
                                    VerifyShape("g_gemm", 20, 10, 256, 2100, "bf16", 1.5),
                                    VerifyShape("g_176", 9, 10, 256, 2100, "bf16", 1.5),
-                                   VerifyShape("g_fp8_352", 32, 10, 272, 2100, "fp8", 1.5)], ids=lambda s: s.name)
+                                   VerifyShape("g_fp8_352", 32, 10, 272, 2100, "fp8", 1.5),
+                                   VerifyShape("g_two_launches", 60, 9, 256, 2100, "bf16", 1.5)],   # 600 rows: a full row tile + a ragged one of its own
+                         ids=lambda s: s.name)
 def test_graph_capture_and_replay(jd, shape):
     # a serving loop may capture verify + append into a HIP graph: run() allocates nothing, never synchronises and
     # sets no function attributes, so it can be captured; every replay (with eager work and synchronisations between
