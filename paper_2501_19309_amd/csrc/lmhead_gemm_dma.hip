@@ -1,6 +1,7 @@
-// LM-head projection for the large-row regime, 352-row tiles (Sec. 3.1, Eq. 2 for all rows
-// of a batch), gfx950.  Same contract as the 176-row kernel next door; used when the row
-// count fills 352-row tiles without extra padding (704 rows = 2 tiles at B=64, M=10).
+// LM-head projection for calls of more than 176 rows, row tiles of up to 352 rows (Sec. 3.1, Eq. 2 for
+// all rows of a batch), gfx950.  Same contract as the 176-row kernel next door.  704 rows (B=64, M=10) are two
+// full tiles; other row counts get row tiles sized to the call (dma_plan below): a tile's rows are spread over
+// its two row halves, and only the 16-row blocks that hold rows are loaded and multiplied.
 //
 // Why a second tiling.  With one 176 x 256 tile per workgroup the compute units request
 // 27 KiB of operands from L2 per 704 matrix-core cycles, which is about what the
@@ -19,10 +20,10 @@
 //     one stage of 38 KiB (22 KiB embeddings in fragment order + 16 KiB weights, which the
 //     re-tiled W_lm already holds in fragment order); four stages = 152 KiB of LDS, so a
 //     stage is requested three K steps (~2 us) before it is read.
-//   * per K step a wavefront issues 88 MFMAs, 19 conflict-free ds_read_b128 (11 embedding
-//     fragments, refilled in place right after their row block, 8 weight fragments into the
-//     other half of a double buffer), 9-10 direct-to-LDS loads and one barrier, each placed
-//     alone behind an MFMA of its own.
+//   * per K step a wavefront issues 88 MFMAs (8 per row block that holds rows), 19 conflict-free
+//     ds_read_b128 (11 embedding fragments, refilled in place right after their row block, 8 weight
+//     fragments into the other half of a double buffer), 9-10 direct-to-LDS loads and one barrier, each
+//     placed alone behind an MFMA of its own.
 //   * direct-to-LDS loads are written as inline assembly: the compiler then neither knows
 //     nor waits for them, and the kernel counts them itself (they complete in issue order):
 //     before the barrier of step k a wavefront waits until only its loads for steps k+2 and
