@@ -144,13 +144,13 @@ hipError_t launch_lmhead_skinny(const void* Wp, int w_code, const float* vscale,
                                 const Geometry& g, float invT, float* L, float2* part, const SideWork& side,
                                 hipStream_t st);
 
-// Large-row regime LM head (R > 64): row tiles of kGemmRows rows x 256 vocabulary entries per
+// LM head of calls of one 176-row tile (64 < R <= kGemmRows): all rows x 256 vocabulary entries per
 // workgroup; same outputs as the skinny launcher.  Xp is scratch for the re-tiled embeddings,
 // gemm_xp_bytes(R, g) bytes.
 constexpr int kGemmRowBlocks = 11;                 // 16-row MFMA blocks per row tile
-constexpr int kGemmRows = kGemmRowBlocks * 16;     // 176: 704 = 4 x 176, no padding at B=64, M=10
+constexpr int kGemmRows = kGemmRowBlocks * 16;     // 176
 constexpr int kGemmKChunk = 128;                   // hidden indices per LDS-staged chunk
-constexpr int kDmaRowBlocks = 22;                  // 352-row tiles of the second tiling (two 176-row halves)
+constexpr int kDmaRowBlocks = 22;                  // row tiles of up to 352 rows (two halves of up to 11 row blocks)
 constexpr int kDmaRows = kDmaRowBlocks * 16;
 constexpr int kDmaMinHalfBlocks = 6;               // fewest row blocks per half the 352-row kernel is instantiated for
 // 16-row blocks per row half that hold rows in the last 352-row tile of an R-row launch: its rows are spread over
@@ -168,9 +168,8 @@ inline size_t gemm_xp_bytes(int R, const Geometry& g) {  // enough for either ti
 // kWBf16: W is the bf16 Wp.
 hipError_t launch_lmhead_gemm(const void* W, int w_code, const float* vscale, const void* X, int R, const Geometry& g,
                               float invT, float* L, float2* part, void* Xp, hipStream_t st);
-// The same projection on 352-row x 256-entry tiles with both operands shared through LDS; the better
-// choice when gemm_prefers_352(R, w_code): when 352-row tiles add no padding rows over 176-row tiles, and for bf16
-// weights from three 352-row tiles on.
+// The same projection on row tiles of up to 352 rows x 256 entries with both operands shared through LDS: the
+// kernel of every call of more than 176 rows (gemm_uses_352); its row tiles are sized to the call.
 // w_code kWFp8 / kWInt8: W is Wg8, the one-byte copy that launch_pack_w8g builds (Geometry::packed8_bytes() bytes),
 // and vscale holds the per-entry scales; kWBf16: W is the bf16 Wp.
 hipError_t launch_lmhead_gemm_dma(const void* W, int w_code, const float* vscale, const void* X, int R,
@@ -179,8 +178,7 @@ hipError_t launch_pack_w8g(const void* W8, int layout, const Geometry& g, void* 
 // Once per process before the first launch of either kernel (they use more dynamic LDS than the default limit).
 hipError_t init_lmhead_gemm();
 hipError_t init_lmhead_gemm_dma();
-inline bool gemm_prefers_352(int R, int w_code) {
-  (void)w_code;
+inline bool gemm_uses_352(int R) {
   return R > kGemmRows;  // every call of more than one 176-row tile (the 352-row kernel sizes its row tiles to the call)
 }
 // Re-tile bf16 embeddings X[R][d] into MFMA fragment order Xp[rt][chunk][xb][s][lane][8] (row tiles of

@@ -389,7 +389,7 @@ static int run_impl(jd_verify_ctx* c, int32_t B, int32_t M, const void* d_emb, c
     const int wk = fp8 ? kWFp8 : int8 ? kWInt8 : kWBf16;
     if (R <= 64) {
       JD_HIP(launch_lmhead_skinny(w8 ? c->Wp8 : c->Wp, wk, c->wscale, d_emb, R, g, invT, c->L, c->tpart, side, st));
-    } else if (gemm_prefers_352(R, wk)) {
+    } else if (gemm_uses_352(R)) {
       JD_HIP(launch_lmhead_gemm_dma(w8 ? c->Wg8 : c->Wp, wk, c->wscale, d_emb, R, g, invT, c->L, c->tpart, c->Xp, st));
     } else {
       JD_HIP(launch_lmhead_gemm(w8 ? c->Wp8 : c->Wp, wk, c->wscale, d_emb, R, g, invT, c->L, c->tpart, c->Xp, st));
